@@ -1,0 +1,154 @@
+/*
+ * marlaas_lora.h -- C ABI of the MI355X (gfx950) mixed-tenant multi-LoRA linear layer.
+ *
+ * One frozen base weight W is shared by every tenant; token i of a batch
+ * belongs to task t(i) and gets that task's LoRA adapter (A_t, B_t) added
+ * (shared base + per-task adapters: paper Sec. 1 principle (1), Sec. 4.2 and
+ * Sec. 4.5; LoRA itself is the cited low-rank update of Sec. 2.3):
+ *
+ *     y_i = x_i W + s_t (x_i A_t) B_t          t = t(i);  t = -1: y_i = x_i W
+ *
+ * The same layer runs in rollout decode and prefill (forward only, Sec. 4.4
+ * "Rollout") and in the policy update (forward + backward, Sec. 4.4
+ * "Training"), where only the LoRA parameters are trained (Sec. 4.2), so the
+ * backward produces dX and per-adapter dA_t, dB_t and never dW.
+ *
+ * Conventions common to all entry points
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller unless it is
+ *    marked HOST.  The library never frees caller memory.  Outputs must not
+ *    alias inputs.
+ *  - All tensors are row-major.  Device pointers must be 16-byte aligned,
+ *    leading dimensions are in elements and must keep rows 16-byte aligned;
+ *    d_in and d_out must be multiples of 8.  Otherwise MARLAAS_EALIGN.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    marlaas_lora_fwd / marlaas_lora_bwd only enqueue work on it and return;
+ *    marlaas_segmap_build enqueues, then waits for its own kernels.
+ *  - Argument errors are reported synchronously as negative status codes with a
+ *    message retrievable by marlaas_last_error(); HIP failures map to
+ *    MARLAAS_EHIP.  No C++ exception crosses this boundary.
+ *  - A ctx may be used by one host thread at a time.
+ */
+#ifndef MARLAAS_LORA_H
+#define MARLAAS_LORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct marlaas_ctx marlaas_ctx;       /* device id, workspace, last error text */
+typedef struct marlaas_segmap marlaas_segmap; /* token grouping by adapter (device + host copies) */
+
+typedef enum {
+  MARLAAS_OK = 0,
+  MARLAAS_EINVAL = -1,       /* null pointer, negative size, bad enum, bad token id */
+  MARLAAS_ESHAPE = -2,       /* sizes inconsistent with each other or with the segmap */
+  MARLAAS_EALIGN = -3,       /* pointer / leading dimension / feature size alignment */
+  MARLAAS_ENOMEM = -4,       /* workspace missing or too small, or allocation failed */
+  MARLAAS_EHIP = -5,         /* a HIP runtime call failed */
+  MARLAAS_EUNSUPPORTED = -6  /* valid request this build does not implement */
+} marlaas_status;
+
+typedef enum { MARLAAS_BF16 = 0, MARLAAS_F32 = 1 } marlaas_dtype;
+
+/* Storage orientation of the weights.
+ *   MARLAAS_LAYOUT_MATH  : W[d_in,d_out], A_t[d_in,r_t], B_t[r_t,d_out]
+ *   MARLAAS_LAYOUT_TORCH : W[d_out,d_in], A_t[r_t,d_in], B_t[d_out,r_t]  (nn.Linear / PEFT)
+ * Gradients dA_t, dB_t are written in the same orientation as A_t, B_t. */
+typedef enum { MARLAAS_LAYOUT_MATH = 0, MARLAAS_LAYOUT_TORCH = 1 } marlaas_layout;
+
+#define MARLAAS_MAX_RANK 128
+#define MARLAAS_MAX_ADAPTERS 4096
+
+typedef struct {
+  int64_t T;             /* tokens (rows of x); 0 is a legal no-op */
+  int64_t d_in;          /* K */
+  int64_t d_out;         /* N */
+  int32_t n_adapters;    /* 0 .. MARLAAS_MAX_ADAPTERS */
+  int32_t in_dtype;      /* marlaas_dtype of x, W, A_t, B_t, dY */
+  int32_t out_dtype;     /* marlaas_dtype of y, dX (dA_t, dB_t are always fp32) */
+  int32_t layout;        /* marlaas_layout */
+  const void* x;         /* [T, d_in], leading dimension ldx */
+  int64_t ldx;
+  const void* W;         /* math: [d_in, d_out]; torch: [d_out, d_in]; leading dimension ldw */
+  int64_t ldw;
+  const void* const* A;  /* HOST array of n_adapters device pointers, each dense (no padding) */
+  const void* const* B;  /* HOST array of n_adapters device pointers, each dense */
+  const int32_t* ranks;  /* HOST int32[n_adapters], 1 .. MARLAAS_MAX_RANK */
+  const float* scales;   /* HOST float[n_adapters], s_t (= alpha / r_t) */
+  const marlaas_segmap* map; /* grouping of the T tokens by adapter, see marlaas_segmap_build */
+} marlaas_lora_desc;
+
+/* Create a context bound to HIP device `device`.  *out is NULL on failure. */
+int marlaas_create(marlaas_ctx** out, int device);
+void marlaas_destroy(marlaas_ctx* ctx);
+
+/* Static text for a status code; per-context detail of the last failure. */
+const char* marlaas_strerror(int status);
+const char* marlaas_last_error(const marlaas_ctx* ctx);
+
+/*
+ * Group tokens by adapter (the token->adapter map of a mixed-tenant batch,
+ * Sec. 4.5).  token_adapter is a device int32[T]; -1 means "base weight only".
+ * Builds, by a stable counting sort on the GPU: counts[n+1] (slot n = tokens
+ * with id -1), seg_off[n+2] (exclusive prefix sums) and perm[T] (token indices,
+ * grouped by adapter, original order kept inside each group, id -1 last).
+ * Ids outside [-1, n_adapters) give MARLAAS_EINVAL and *out = NULL.  The call
+ * waits for its kernels (it reads the counts back to plan launches); build the
+ * map once per batch and reuse it for every layer and for forward + backward.
+ * The map owns its device memory (hipMalloc) until marlaas_segmap_destroy.
+ */
+int marlaas_segmap_build(marlaas_ctx* ctx, const int32_t* token_adapter, int64_t T,
+                         int32_t n_adapters, void* stream, marlaas_segmap** out);
+void marlaas_segmap_destroy(marlaas_segmap* map);
+/* Copy the map to HOST buffers (either may be NULL): perm int32[T],
+ * seg_off int32[n_adapters + 2].  Waits for the copy. */
+int marlaas_segmap_export(const marlaas_segmap* map, int32_t* perm, int32_t* seg_off);
+
+/*
+ * Scratch memory.  The hot path allocates nothing: the caller hands over one
+ * device buffer (e.g. a torch tensor) that must stay alive and unused by others
+ * while calls on this ctx are in flight.  marlaas_workspace_bytes returns the
+ * size needed by marlaas_lora_fwd (want_bwd = 0) or by fwd and bwd
+ * (want_bwd = 1) for this descriptor (only sizes, ranks, dtypes and map are
+ * read), or 0 if the descriptor is invalid.
+ */
+size_t marlaas_workspace_bytes(const marlaas_lora_desc* desc, int want_bwd);
+int marlaas_set_workspace(marlaas_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/*
+ * Forward: y[T, d_out] (out_dtype, leading dimension ldy) = x W + s_t (x A_t) B_t.
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; the
+ * intermediate u = x A_t is kept in fp32 and enters the second product as a
+ * two-term bf16 split, so no intermediate is rounded to bf16.  fp32 inputs use
+ * fp32 arithmetic throughout.
+ * u_save (nullable): device fp32 [T, marlaas_u_stride(desc)]; receives
+ * s_t (x A_t) per token in the grouped order of the map, for reuse by
+ * marlaas_lora_bwd (its content is otherwise opaque).
+ */
+int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, void* y, int64_t ldy,
+                     void* u_save, void* stream);
+
+/*
+ * Backward for a loss with dL/dy = dY[T, d_out] (in_dtype, leading dimension lddy):
+ *   dX[T, d_in] (out_dtype, lddx) = dY W^T + v A_t^T,   v = s_t dY B_t^T
+ *   dA_t = sum_{i in seg(t)} x_i^T v_i,   dB_t = s_t sum_{i in seg(t)} (x_i A_t)^T dY_i
+ * dA, dB: HOST arrays of n_adapters device fp32 pointers, each shaped like
+ * A_t / B_t (dense).  accumulate = 0 overwrites them (an adapter without tokens
+ * gets zeros), accumulate = 1 adds to their contents.  dX may be NULL (skip),
+ * and dA and dB may both be NULL (skip).  u_saved: what marlaas_lora_fwd wrote
+ * to u_save for the same descriptor, or NULL to recompute it.
+ */
+int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, const void* dY, int64_t lddy,
+                     const void* u_saved, void* dX, int64_t lddx, void* const* dA,
+                     void* const* dB, int accumulate, void* stream);
+
+/* Row stride (in floats) of u_save: the largest rank rounded up to 16; 0 if invalid. */
+int64_t marlaas_u_stride(const marlaas_lora_desc* desc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MARLAAS_LORA_H */

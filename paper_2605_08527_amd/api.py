@@ -1,0 +1,243 @@
+"""Python binding of libmarlaas_lora.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+include/marlaas_lora.h).  Tensors are torch CUDA tensors used purely as device
+memory; all arithmetic happens inside the HIP library.  There is no fallback:
+if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmarlaas_lora.so")
+
+MARLAAS_BF16, MARLAAS_F32 = 0, 1
+MARLAAS_LAYOUT_MATH, MARLAAS_LAYOUT_TORCH = 0, 1
+MARLAAS_OK = 0
+
+EXPORTS = [
+    "marlaas_create", "marlaas_destroy", "marlaas_strerror", "marlaas_last_error",
+    "marlaas_segmap_build", "marlaas_segmap_destroy", "marlaas_segmap_export",
+    "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd",
+    "marlaas_u_stride",
+]
+
+
+class marlaas_lora_desc(ctypes.Structure):
+    _fields_ = [
+        ("T", ctypes.c_int64), ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64),
+        ("n_adapters", ctypes.c_int32), ("in_dtype", ctypes.c_int32),
+        ("out_dtype", ctypes.c_int32), ("layout", ctypes.c_int32),
+        ("x", ctypes.c_void_p), ("ldx", ctypes.c_int64),
+        ("W", ctypes.c_void_p), ("ldw", ctypes.c_int64),
+        ("A", ctypes.POINTER(ctypes.c_void_p)), ("B", ctypes.POINTER(ctypes.c_void_p)),
+        ("ranks", ctypes.POINTER(ctypes.c_int32)), ("scales", ctypes.POINTER(ctypes.c_float)),
+        ("map", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load():
+    """dlopen the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("%s is missing: run paper_2605_08527_amd/build.py (there is no fallback path)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.marlaas_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int]
+    lib.marlaas_create.restype = ctypes.c_int
+    lib.marlaas_destroy.argtypes = [vp]
+    lib.marlaas_destroy.restype = None
+    lib.marlaas_strerror.argtypes = [ctypes.c_int]
+    lib.marlaas_strerror.restype = ctypes.c_char_p
+    lib.marlaas_last_error.argtypes = [vp]
+    lib.marlaas_last_error.restype = ctypes.c_char_p
+    lib.marlaas_segmap_build.argtypes = [vp, vp, i64, i32, vp, ctypes.POINTER(vp)]
+    lib.marlaas_segmap_build.restype = ctypes.c_int
+    lib.marlaas_segmap_destroy.argtypes = [vp]
+    lib.marlaas_segmap_destroy.restype = None
+    lib.marlaas_segmap_export.argtypes = [vp, vp, vp]
+    lib.marlaas_segmap_export.restype = ctypes.c_int
+    lib.marlaas_workspace_bytes.argtypes = [ctypes.POINTER(marlaas_lora_desc), ctypes.c_int]
+    lib.marlaas_workspace_bytes.restype = ctypes.c_size_t
+    lib.marlaas_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
+    lib.marlaas_set_workspace.restype = ctypes.c_int
+    lib.marlaas_lora_fwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp]
+    lib.marlaas_lora_fwd.restype = ctypes.c_int
+    lib.marlaas_lora_bwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
+                                     ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp]
+    lib.marlaas_lora_bwd.restype = ctypes.c_int
+    lib.marlaas_u_stride.argtypes = [ctypes.POINTER(marlaas_lora_desc)]
+    lib.marlaas_u_stride.restype = i64
+    _lib = lib
+    return lib
+
+
+class MarlaasError(RuntimeError):
+    def __init__(self, status, detail):
+        self.status = status
+        text = load().marlaas_strerror(status).decode()
+        super().__init__("marlaas status %d (%s): %s" % (status, text, detail))
+
+
+def _check(ctx, status):
+    if status != MARLAAS_OK:
+        detail = load().marlaas_last_error(ctx.handle).decode() if ctx is not None else ""
+        raise MarlaasError(status, detail)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _dtype_flag(dt):
+    if dt == torch.bfloat16:
+        return MARLAAS_BF16
+    if dt == torch.float32:
+        return MARLAAS_F32
+    raise TypeError("only bfloat16 and float32 tensors are supported, got %s" % dt)
+
+
+class Context:
+    def __init__(self, device=0):
+        self.handle = ctypes.c_void_p()
+        self.workspace = None
+        st = load().marlaas_create(ctypes.byref(self.handle), int(device))
+        if st != MARLAAS_OK:
+            raise MarlaasError(st, "marlaas_create(device=%d)" % device)
+
+    def close(self):
+        if self.handle:
+            load().marlaas_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def marlaas_create(device=0):
+    return Context(device)
+
+
+def marlaas_destroy(ctx):
+    ctx.close()
+
+
+class Segmap:
+    def __init__(self, handle, T, n_adapters):
+        self.handle, self.T, self.n_adapters = handle, T, n_adapters
+
+    def close(self):
+        if self.handle:
+            load().marlaas_segmap_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def marlaas_segmap_build(ctx, token_adapter, n_adapters, stream=None):
+    """token_adapter: int32 CUDA tensor [T]."""
+    assert token_adapter.dtype == torch.int32 and token_adapter.is_cuda and token_adapter.is_contiguous()
+    h = ctypes.c_void_p()
+    st = load().marlaas_segmap_build(ctx.handle, _ptr(token_adapter), token_adapter.numel(),
+                                     int(n_adapters), _stream_ptr(stream), ctypes.byref(h))
+    _check(ctx, st)
+    return Segmap(h, token_adapter.numel(), int(n_adapters))
+
+
+def marlaas_segmap_destroy(segmap):
+    segmap.close()
+
+
+def marlaas_segmap_export(segmap):
+    """(perm, seg_off) as numpy int32 arrays."""
+    import numpy as np
+    perm = np.empty(segmap.T, dtype=np.int32)
+    seg_off = np.empty(segmap.n_adapters + 2, dtype=np.int32)
+    st = load().marlaas_segmap_export(segmap.handle, ctypes.c_void_p(perm.ctypes.data),
+                                      ctypes.c_void_p(seg_off.ctypes.data))
+    if st != MARLAAS_OK:
+        raise MarlaasError(st, "marlaas_segmap_export")
+    return perm, seg_off
+
+
+class LoraDesc:
+    """Owns a marlaas_lora_desc and keeps the host arrays it points to alive."""
+
+    def __init__(self, x, W, A, B, ranks, scales, segmap, layout=MARLAAS_LAYOUT_MATH, out_dtype=None):
+        n = len(A)
+        self.tensors = (x, W, list(A), list(B), segmap)
+        self.c = marlaas_lora_desc()
+        T, d_in = x.shape
+        d_out = W.shape[1] if layout == MARLAAS_LAYOUT_MATH else W.shape[0]
+        self.c.T, self.c.d_in, self.c.d_out, self.c.n_adapters = T, d_in, d_out, n
+        self.c.in_dtype = _dtype_flag(x.dtype)
+        self.c.out_dtype = self.c.in_dtype if out_dtype is None else _dtype_flag(out_dtype)
+        self.c.layout = layout
+        self.c.x, self.c.ldx = x.data_ptr(), x.stride(0) if T > 0 else d_in
+        self.c.W, self.c.ldw = W.data_ptr(), W.stride(0)
+        self._A = (ctypes.c_void_p * max(n, 1))(*[a.data_ptr() for a in A])
+        self._B = (ctypes.c_void_p * max(n, 1))(*[b.data_ptr() for b in B])
+        self._ranks = (ctypes.c_int32 * max(n, 1))(*[int(r) for r in ranks])
+        self._scales = (ctypes.c_float * max(n, 1))(*[float(s) for s in scales])
+        self.c.A = ctypes.cast(self._A, ctypes.POINTER(ctypes.c_void_p))
+        self.c.B = ctypes.cast(self._B, ctypes.POINTER(ctypes.c_void_p))
+        self.c.ranks = ctypes.cast(self._ranks, ctypes.POINTER(ctypes.c_int32))
+        self.c.scales = ctypes.cast(self._scales, ctypes.POINTER(ctypes.c_float))
+        self.c.map = segmap.handle
+        self.shape = (T, d_in, d_out, n)
+
+    @property
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def marlaas_workspace_bytes(desc, want_bwd=False):
+    return int(load().marlaas_workspace_bytes(desc.ref, 1 if want_bwd else 0))
+
+
+def marlaas_u_stride(desc):
+    return int(load().marlaas_u_stride(desc.ref))
+
+
+def marlaas_set_workspace(ctx, tensor):
+    """tensor: a CUDA tensor used as scratch (kept alive by the context object), or None."""
+    ctx.workspace = tensor
+    nbytes = tensor.numel() * tensor.element_size() if tensor is not None else 0
+    _check(ctx, load().marlaas_set_workspace(ctx.handle, _ptr(tensor), nbytes))
+
+
+def marlaas_lora_fwd(ctx, desc, y, u_save=None, stream=None):
+    ldy = y.stride(0) if y.shape[0] > 0 else y.shape[1]
+    _check(ctx, load().marlaas_lora_fwd(ctx.handle, desc.ref, _ptr(y), ldy, _ptr(u_save), _stream_ptr(stream)))
+
+
+def marlaas_lora_bwd(ctx, desc, dY, dX=None, dA=None, dB=None, u_saved=None, accumulate=False, stream=None):
+    n = desc.shape[3]
+    pa = pb = None
+    if dA is not None:
+        pa = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in dA])
+        pb = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in dB])
+    lddy = dY.stride(0) if dY.shape[0] > 0 else dY.shape[1]
+    lddx = (dX.stride(0) if dX.shape[0] > 0 else dX.shape[1]) if dX is not None else 0
+    _check(ctx, load().marlaas_lora_bwd(ctx.handle, desc.ref, _ptr(dY), lddy, _ptr(u_saved), _ptr(dX), lddx,
+                                        pa, pb, 1 if accumulate else 0, _stream_ptr(stream)))

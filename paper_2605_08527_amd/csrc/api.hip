@@ -1,0 +1,446 @@
+// Host side of the C ABI: contexts, argument checks, the token grouping
+// object, cached device copies of the per-adapter pointer tables, workspace
+// carving and the order in which the kernels of a forward / backward pass are
+// enqueued.  Nothing here computes on tensors.
+#include "../../include/marlaas_lora.h"
+#include "common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <list>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace marlaas;
+
+struct TableSlot {
+  std::string key;       // raw bytes of the host-side table
+  void* dev = nullptr;
+};
+
+struct marlaas_ctx {
+  int device = 0;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  std::string err;
+  std::list<TableSlot> tables;   // most recently used first
+};
+
+struct marlaas_segmap {
+  int device = 0;
+  int64_t T = 0;
+  int32_t n = 0;
+  int32_t* perm_dev = nullptr;      // [T] grouped order (always built)
+  int32_t* seg_off_dev = nullptr;   // [n + 2]
+  std::vector<int32_t> seg_off;     // host copy
+  bool identity = false;            // ids were already grouped: kernels skip the gather
+  int max_seg = 0;                  // largest adapter segment
+  int64_t T_lora = 0;               // tokens that have an adapter
+};
+
+static const size_t TABLE_CACHE_SLOTS = 512;
+static const size_t WS_ALIGN = 256;
+
+static int fail(marlaas_ctx* ctx, int status, const char* fmt, ...) {
+  if (ctx) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    ctx->err = buf;
+  }
+  return status;
+}
+
+#define HIP_TRY(ctx, expr)                                                          \
+  do {                                                                              \
+    hipError_t _e = (expr);                                                         \
+    if (_e != hipSuccess)                                                           \
+      return fail((ctx), MARLAAS_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
+  } while (0)
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+extern "C" const char* marlaas_strerror(int status) {
+  switch (status) {
+    case MARLAAS_OK: return "ok";
+    case MARLAAS_EINVAL: return "invalid argument";
+    case MARLAAS_ESHAPE: return "inconsistent shapes";
+    case MARLAAS_EALIGN: return "misaligned pointer, leading dimension or feature size";
+    case MARLAAS_ENOMEM: return "workspace missing or too small, or allocation failed";
+    case MARLAAS_EHIP: return "HIP runtime error";
+    case MARLAAS_EUNSUPPORTED: return "unsupported request";
+    default: return "unknown status";
+  }
+}
+
+extern "C" const char* marlaas_last_error(const marlaas_ctx* ctx) {
+  return ctx ? ctx->err.c_str() : "null context";
+}
+
+extern "C" int marlaas_create(marlaas_ctx** out, int device) {
+  if (!out) return MARLAAS_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return MARLAAS_EHIP;
+  marlaas_ctx* ctx = new (std::nothrow) marlaas_ctx();
+  if (!ctx) return MARLAAS_ENOMEM;
+  ctx->device = device;
+  *out = ctx;
+  return MARLAAS_OK;
+}
+
+extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->device);
+  for (auto& s : ctx->tables) (void)hipFree(s.dev);
+  delete ctx;
+}
+
+// Device copy of a small host table, cached by content so that the steady
+// state (the same layers called every step) uploads nothing.
+static int cached_table(marlaas_ctx* ctx, const void* host, size_t bytes, const void** dev) {
+  std::string key((const char*)host, bytes);
+  for (auto it = ctx->tables.begin(); it != ctx->tables.end(); ++it) {
+    if (it->key == key) {
+      ctx->tables.splice(ctx->tables.begin(), ctx->tables, it);
+      *dev = ctx->tables.front().dev;
+      return MARLAAS_OK;
+    }
+  }
+  if (ctx->tables.size() >= TABLE_CACHE_SLOTS) {
+    HIP_TRY(ctx, hipDeviceSynchronize());   // a kernel in flight may still read the victim
+    (void)hipFree(ctx->tables.back().dev);
+    ctx->tables.pop_back();
+  }
+  TableSlot s;
+  s.key.swap(key);
+  HIP_TRY(ctx, hipMalloc(&s.dev, bytes));
+  hipError_t e = hipMemcpy(s.dev, host, bytes, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(s.dev);
+    return fail(ctx, MARLAAS_EHIP, "table upload failed: %s", hipGetErrorString(e));
+  }
+  ctx->tables.push_front(std::move(s));
+  *dev = ctx->tables.front().dev;
+  return MARLAAS_OK;
+}
+
+// ------------------------------------------------------------------ segmap
+extern "C" int marlaas_segmap_build(marlaas_ctx* ctx, const int32_t* token_adapter, int64_t T,
+                                    int32_t n_adapters, void* stream, marlaas_segmap** out) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!out) return fail(ctx, MARLAAS_EINVAL, "segmap_build: out is null");
+  *out = nullptr;
+  if (T < 0 || T > 0x7fffffff - 4096) return fail(ctx, MARLAAS_EINVAL, "segmap_build: T=%lld out of range", (long long)T);
+  if (n_adapters < 0 || n_adapters > MARLAAS_MAX_ADAPTERS)
+    return fail(ctx, MARLAAS_EINVAL, "segmap_build: n_adapters=%d out of range", n_adapters);
+  if (T > 0 && !token_adapter) return fail(ctx, MARLAAS_EINVAL, "segmap_build: token_adapter is null");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = (hipStream_t)stream;
+  marlaas_segmap* m = new (std::nothrow) marlaas_segmap();
+  if (!m) return fail(ctx, MARLAAS_ENOMEM, "segmap_build: host allocation failed");
+  m->device = ctx->device; m->T = T; m->n = n_adapters;
+  const int nblk = segmap_blocks(T);
+  int32_t* block_hist = nullptr;
+  int32_t* flags = nullptr;
+  int status = MARLAAS_OK;
+  int32_t hflags[2] = {0, 0};
+  m->seg_off.assign((size_t)n_adapters + 2, 0);
+  hipError_t e = hipSuccess;
+  do {
+    if ((e = hipMalloc((void**)&m->perm_dev, sizeof(int32_t) * (size_t)(T > 0 ? T : 1))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->seg_off_dev, sizeof(int32_t) * ((size_t)n_adapters + 2))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&block_hist, sizeof(int32_t) * (size_t)(nblk > 0 ? nblk : 1) * ((size_t)n_adapters + 1))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&flags, 2 * sizeof(int32_t))) != hipSuccess) break;
+    if ((e = launch_segmap(token_adapter, T, n_adapters, m->perm_dev, m->seg_off_dev, block_hist, flags, st)) != hipSuccess) break;
+    if ((e = hipMemcpyAsync(hflags, flags, sizeof hflags, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
+    if ((e = hipMemcpyAsync(m->seg_off.data(), m->seg_off_dev, sizeof(int32_t) * m->seg_off.size(), hipMemcpyDeviceToHost, st)) != hipSuccess) break;
+    e = hipStreamSynchronize(st);
+  } while (0);
+  (void)hipFree(block_hist);
+  (void)hipFree(flags);
+  if (e != hipSuccess) status = fail(ctx, MARLAAS_EHIP, "segmap_build: %s", hipGetErrorString(e));
+  else if (hflags[0]) status = fail(ctx, MARLAAS_EINVAL, "segmap_build: token id outside [-1, %d)", n_adapters);
+  if (status != MARLAAS_OK) { marlaas_segmap_destroy(m); return status; }
+  m->identity = hflags[1] == 0;
+  for (int t = 0; t < n_adapters; ++t) {
+    int len = m->seg_off[t + 1] - m->seg_off[t];
+    if (len > m->max_seg) m->max_seg = len;
+  }
+  m->T_lora = m->seg_off[n_adapters];
+  *out = m;
+  return MARLAAS_OK;
+}
+
+extern "C" void marlaas_segmap_destroy(marlaas_segmap* map) {
+  if (!map) return;
+  (void)hipSetDevice(map->device);
+  (void)hipFree(map->perm_dev);
+  (void)hipFree(map->seg_off_dev);
+  delete map;
+}
+
+extern "C" int marlaas_segmap_export(const marlaas_segmap* map, int32_t* perm, int32_t* seg_off) {
+  if (!map) return MARLAAS_EINVAL;
+  if (seg_off) memcpy(seg_off, map->seg_off.data(), sizeof(int32_t) * map->seg_off.size());
+  if (perm && map->T > 0) {
+    if (hipSetDevice(map->device) != hipSuccess) return MARLAAS_EHIP;
+    if (hipMemcpy(perm, map->perm_dev, sizeof(int32_t) * (size_t)map->T, hipMemcpyDeviceToHost) != hipSuccess)
+      return MARLAAS_EHIP;
+  }
+  return MARLAAS_OK;
+}
+
+// ------------------------------------------------------------------ descriptor checks
+static int max_rank_of(const marlaas_lora_desc* d) {
+  int mr = 0;
+  for (int t = 0; t < d->n_adapters; ++t) if (d->ranks[t] > mr) mr = d->ranks[t];
+  return mr;
+}
+
+static int check_sizes(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
+  if (!d) return fail(ctx, MARLAAS_EINVAL, "descriptor is null");
+  if (d->T < 0 || d->d_in <= 0 || d->d_out <= 0) return fail(ctx, MARLAAS_EINVAL, "negative or zero size");
+  if (d->T > 0x7fffffff - 4096 || d->d_in > (1 << 24) || d->d_out > (1 << 24))
+    return fail(ctx, MARLAAS_EINVAL, "size too large");
+  if (d->n_adapters < 0 || d->n_adapters > MARLAAS_MAX_ADAPTERS) return fail(ctx, MARLAAS_EINVAL, "n_adapters out of range");
+  if (d->in_dtype != MARLAAS_BF16 && d->in_dtype != MARLAAS_F32) return fail(ctx, MARLAAS_EINVAL, "bad in_dtype");
+  if (d->out_dtype != MARLAAS_BF16 && d->out_dtype != MARLAAS_F32) return fail(ctx, MARLAAS_EINVAL, "bad out_dtype");
+  if (d->layout != MARLAAS_LAYOUT_MATH && d->layout != MARLAAS_LAYOUT_TORCH) return fail(ctx, MARLAAS_EINVAL, "bad layout");
+  if ((d->d_in & 7) || (d->d_out & 7)) return fail(ctx, MARLAAS_EALIGN, "d_in and d_out must be multiples of 8");
+  if (d->n_adapters > 0) {
+    if (!d->ranks || !d->scales) return fail(ctx, MARLAAS_EINVAL, "ranks / scales are null");
+    for (int t = 0; t < d->n_adapters; ++t)
+      if (d->ranks[t] < 1 || d->ranks[t] > MARLAAS_MAX_RANK)
+        return fail(ctx, MARLAAS_EINVAL, "rank of adapter %d is %d, must be 1..%d", t, d->ranks[t], MARLAAS_MAX_RANK);
+  }
+  if (!d->map) return fail(ctx, MARLAAS_EINVAL, "segment map is null");
+  if (d->map->T != d->T || d->map->n != d->n_adapters)
+    return fail(ctx, MARLAAS_ESHAPE, "segment map was built for T=%lld, n=%d", (long long)d->map->T, d->map->n);
+  return MARLAAS_OK;
+}
+
+extern "C" int64_t marlaas_u_stride(const marlaas_lora_desc* d) {
+  if (!d || d->n_adapters < 0 || d->n_adapters > MARLAAS_MAX_ADAPTERS) return 0;
+  if (d->n_adapters == 0) return 16;
+  if (!d->ranks) return 0;
+  int mr = max_rank_of(d);
+  if (mr < 1 || mr > MARLAAS_MAX_RANK) return 0;
+  return (mr + 15) & ~15;
+}
+
+struct WsPlan {
+  size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;
+};
+
+static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
+  WsPlan p;
+  const size_t rs = (size_t)marlaas_u_stride(d);
+  const size_t uv = align_up((size_t)(d->T > 0 ? d->T : 1) * rs * sizeof(float), WS_ALIGN);
+  size_t off = 0;
+  p.u_off = off; off += uv;
+  if (want_bwd) {
+    p.v_off = off; off += uv;
+    if (d->in_dtype == MARLAAS_BF16) {
+      const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs);
+      const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs);
+      p.part_bytes = align_up(pa > pb ? pa : pb, WS_ALIGN);
+      p.part_off = off; off += p.part_bytes;
+    }
+  }
+  p.total = off;
+  return p;
+}
+
+extern "C" size_t marlaas_workspace_bytes(const marlaas_lora_desc* d, int want_bwd) {
+  if (check_sizes(nullptr, d) != MARLAAS_OK) return 0;
+  return plan_workspace(d, want_bwd).total;
+}
+
+extern "C" int marlaas_set_workspace(marlaas_ctx* ctx, void* dev_ptr, size_t bytes) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (dev_ptr && ((uintptr_t)dev_ptr & (WS_ALIGN - 1)))
+    return fail(ctx, MARLAAS_EALIGN, "workspace must be %zu-byte aligned", WS_ALIGN);
+  ctx->ws = dev_ptr;
+  ctx->ws_bytes = dev_ptr ? bytes : 0;
+  return MARLAAS_OK;
+}
+
+static int check_tensors(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
+  const int64_t esz = d->in_dtype == MARLAAS_BF16 ? 2 : 4;
+  if (d->T > 0 && !d->x) return fail(ctx, MARLAAS_EINVAL, "x is null");
+  if (!d->W) return fail(ctx, MARLAAS_EINVAL, "W is null");
+  if (!aligned16(d->x) || !aligned16(d->W)) return fail(ctx, MARLAAS_EALIGN, "x and W must be 16-byte aligned");
+  if (d->ldx < d->d_in || (d->ldx * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldx=%lld", (long long)d->ldx);
+  const int64_t wcols = d->layout == MARLAAS_LAYOUT_MATH ? d->d_out : d->d_in;
+  if (d->ldw < wcols || (d->ldw * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldw=%lld", (long long)d->ldw);
+  if (d->n_adapters > 0) {
+    if (!d->A || !d->B) return fail(ctx, MARLAAS_EINVAL, "A / B pointer arrays are null");
+    for (int t = 0; t < d->n_adapters; ++t) {
+      if (!d->A[t] || !d->B[t]) return fail(ctx, MARLAAS_EINVAL, "adapter %d has a null factor", t);
+      if (!aligned16(d->A[t]) || !aligned16(d->B[t])) return fail(ctx, MARLAAS_EALIGN, "adapter %d factors must be 16-byte aligned", t);
+    }
+  }
+  return MARLAAS_OK;
+}
+
+static int adapter_table(marlaas_ctx* ctx, const marlaas_lora_desc* d, const AdapterEntry** dev) {
+  *dev = nullptr;
+  if (d->n_adapters == 0) return MARLAAS_OK;
+  std::vector<AdapterEntry> host((size_t)d->n_adapters);
+  memset(host.data(), 0, host.size() * sizeof(AdapterEntry));
+  for (int t = 0; t < d->n_adapters; ++t) {
+    host[t].A = d->A[t]; host[t].B = d->B[t]; host[t].rank = d->ranks[t]; host[t].scale = d->scales[t];
+  }
+  return cached_table(ctx, host.data(), host.size() * sizeof(AdapterEntry), (const void**)dev);
+}
+
+// ------------------------------------------------------------------ forward
+extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy,
+                                void* u_save, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  int rc = check_sizes(ctx, d);
+  if (rc != MARLAAS_OK) return rc;
+  if (d->T == 0) return MARLAAS_OK;
+  if ((rc = check_tensors(ctx, d)) != MARLAAS_OK) return rc;
+  const int64_t osz = d->out_dtype == MARLAAS_BF16 ? 2 : 4;
+  if (!y) return fail(ctx, MARLAAS_EINVAL, "y is null");
+  if (!aligned16(y) || ldy < d->d_out || (ldy * osz) % 16) return fail(ctx, MARLAAS_EALIGN, "y / ldy");
+  if (u_save && !aligned16(u_save)) return fail(ctx, MARLAAS_EALIGN, "u_save must be 16-byte aligned");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = (hipStream_t)stream;
+  const marlaas_segmap* map = d->map;
+  const int rs = (int)marlaas_u_stride(d);
+  float* u = (float*)u_save;
+  const bool lora = d->n_adapters > 0 && map->T_lora > 0;
+  if (lora && !u) {
+    WsPlan p = plan_workspace(d, 0);
+    if (!ctx->ws || ctx->ws_bytes < p.total)
+      return fail(ctx, MARLAAS_ENOMEM, "forward needs %zu workspace bytes, have %zu", p.total, ctx->ws_bytes);
+    u = (float*)((char*)ctx->ws + p.u_off);
+  }
+  const AdapterEntry* table = nullptr;
+  if ((rc = adapter_table(ctx, d, &table)) != MARLAAS_OK) return rc;
+  const int32_t* perm = map->identity ? nullptr : map->perm_dev;
+  // forward contracts over d_in: math W[d_in,d_out] is [contraction, output] (NN), torch is NT;
+  // A_t follows W for the shrink, B_t follows W for the expand.
+  const int form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
+  const int out_f32 = d->out_dtype == MARLAAS_F32;
+  if (d->in_dtype == MARLAAS_BF16) {
+    if (lora)
+      HIP_TRY(ctx, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
+                                      map->max_seg, table, 0, form, u, rs, map->T_lora, st));
+    HIP_TRY(ctx, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
+                                  d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
+                                  rs, y, ldy, out_f32, st));
+  } else {
+    if (lora)
+      HIP_TRY(ctx, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
+                                     table, 0, form, u, rs, map->T_lora, st));
+    HIP_TRY(ctx, launch_gemm_f32((const float*)d->x, d->ldx, (const float*)d->W, d->ldw, form, d->T, d->d_in,
+                                 d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
+                                 rs, y, ldy, out_f32, st));
+  }
+  return MARLAAS_OK;
+}
+
+// ------------------------------------------------------------------ backward
+extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY, int64_t lddy,
+                                const void* u_saved, void* dX, int64_t lddx, void* const* dA,
+                                void* const* dB, int accumulate, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  int rc = check_sizes(ctx, d);
+  if (rc != MARLAAS_OK) return rc;
+  const bool want_grads = dA != nullptr || dB != nullptr;
+  if (want_grads && (!dA || !dB)) return fail(ctx, MARLAAS_EINVAL, "dA and dB must both be given or both be null");
+  if (accumulate != 0 && accumulate != 1) return fail(ctx, MARLAAS_EINVAL, "accumulate must be 0 or 1");
+  if ((rc = check_tensors(ctx, d)) != MARLAAS_OK) return rc;
+  const int64_t esz = d->in_dtype == MARLAAS_BF16 ? 2 : 4;
+  const int64_t osz = d->out_dtype == MARLAAS_BF16 ? 2 : 4;
+  if (d->T > 0) {
+    if (!dY) return fail(ctx, MARLAAS_EINVAL, "dY is null");
+    if (!aligned16(dY) || lddy < d->d_out || (lddy * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "dY / lddy");
+    if (dX && (!aligned16(dX) || lddx < d->d_in || (lddx * osz) % 16)) return fail(ctx, MARLAAS_EALIGN, "dX / lddx");
+    if (u_saved && !aligned16(u_saved)) return fail(ctx, MARLAAS_EALIGN, "u_saved must be 16-byte aligned");
+  }
+  if (want_grads)
+    for (int t = 0; t < d->n_adapters; ++t)
+      if (!dA[t] || !dB[t] || !aligned16(dA[t]) || !aligned16(dB[t]))
+        return fail(ctx, MARLAAS_EINVAL, "gradient buffers of adapter %d are null or misaligned", t);
+  if (d->T == 0 && !(want_grads && !accumulate && d->n_adapters > 0)) return MARLAAS_OK;
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = (hipStream_t)stream;
+  const marlaas_segmap* map = d->map;
+  const int rs = (int)marlaas_u_stride(d);
+  const bool lora = d->n_adapters > 0 && map->T_lora > 0;
+  WsPlan p = plan_workspace(d, 1);
+  if (d->n_adapters > 0 && (!ctx->ws || ctx->ws_bytes < p.total))
+    return fail(ctx, MARLAAS_ENOMEM, "backward needs %zu workspace bytes, have %zu", p.total, ctx->ws_bytes);
+  float* u = (float*)u_saved;
+  float* v = d->n_adapters > 0 ? (float*)((char*)ctx->ws + p.v_off) : nullptr;
+  const bool need_u = lora && want_grads && !u;
+  if (need_u) u = (float*)((char*)ctx->ws + p.u_off);
+  const AdapterEntry* table = nullptr;
+  if ((rc = adapter_table(ctx, d, &table)) != MARLAAS_OK) return rc;
+  const GradEntry* grads = nullptr;
+  if (want_grads && d->n_adapters > 0) {
+    std::vector<GradEntry> host((size_t)d->n_adapters);
+    for (int t = 0; t < d->n_adapters; ++t) { host[t].dA = (float*)dA[t]; host[t].dB = (float*)dB[t]; }
+    if ((rc = cached_table(ctx, host.data(), host.size() * sizeof(GradEntry), (const void**)&grads)) != MARLAAS_OK) return rc;
+  }
+  const int32_t* perm = map->identity ? nullptr : map->perm_dev;
+  // forward-side forms (contraction over d_in) and backward-side forms (contraction over d_out)
+  const int fform = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
+  const int bform = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NT : FORM_NN;
+  // gradients keep the orientation of their factor: math dA[d_in,r] / torch dB[d_out,r] are
+  // [wide, r] (NN), math dB[r,d_out] / torch dA[r,d_in] are [r, wide] (NT)
+  const int da_form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
+  const int db_form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NT : FORM_NN;
+  const int out_f32 = d->out_dtype == MARLAAS_F32;
+  float* part = p.part_bytes ? (float*)((char*)ctx->ws + p.part_off) : nullptr;
+  if (d->in_dtype == MARLAAS_BF16) {
+    const bf16_t* x = (const bf16_t*)d->x;
+    const bf16_t* dy = (const bf16_t*)dY;
+    if (need_u)
+      HIP_TRY(ctx, launch_shrink_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+                                      table, 0, fform, u, rs, map->T_lora, st));
+    if (lora && (dX || want_grads))
+      HIP_TRY(ctx, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+                                      table, 1, bform, v, rs, map->T_lora, st));
+    if (dX && d->T > 0)
+      HIP_TRY(ctx, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
+                                    map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
+                                    out_f32, st));
+    if (want_grads && d->n_adapters > 0) {
+      HIP_TRY(ctx, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+                                      table, grads, 1, db_form, u, rs, accumulate, part, p.part_bytes, st));
+      HIP_TRY(ctx, launch_reduce_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+                                      table, grads, 0, da_form, v, rs, accumulate, part, p.part_bytes, st));
+    }
+  } else {
+    const float* x = (const float*)d->x;
+    const float* dy = (const float*)dY;
+    if (need_u)
+      HIP_TRY(ctx, launch_shrink_f32(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, table, 0, fform,
+                                     u, rs, map->T_lora, st));
+    if (lora && (dX || want_grads))
+      HIP_TRY(ctx, launch_shrink_f32(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, bform,
+                                     v, rs, map->T_lora, st));
+    if (dX && d->T > 0)
+      HIP_TRY(ctx, launch_gemm_f32(dy, lddy, (const float*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
+                                   map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
+                                   out_f32, st));
+    if (want_grads && d->n_adapters > 0) {
+      HIP_TRY(ctx, launch_reduce_f32(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, table, grads, 1,
+                                     db_form, u, rs, accumulate, st));
+      HIP_TRY(ctx, launch_reduce_f32(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, table, grads, 0,
+                                     da_form, v, rs, accumulate, st));
+    }
+  }
+  return MARLAAS_OK;
+}

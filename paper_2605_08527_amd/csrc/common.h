@@ -1,0 +1,107 @@
+// Shared declarations of the HIP library (host + device side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace marlaas {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+// One adapter as the kernels see it.  `lora_in` multiplies the layer input
+// (A_t in forward, B_t in backward), `lora_out` produces the layer output
+// (B_t in forward, A_t in backward); both are dense, orientation given by the
+// kernel's template form.
+struct AdapterEntry {
+  const void* A;
+  const void* B;
+  int32_t rank;
+  float scale;
+};
+
+struct GradEntry {
+  float* dA;
+  float* dB;
+};
+
+// How a [contraction, output] operand is stored.
+//   FORM_NT: element (k, n) at ptr[n * ld + k]   (contraction index contiguous)
+//   FORM_NN: element (k, n) at ptr[k * ld + n]   (output index contiguous)
+enum { FORM_NT = 0, FORM_NN = 1 };
+
+__device__ __forceinline__ float bf16_bits_to_float(bf16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+// round to nearest even; inputs here are finite
+__device__ __forceinline__ bf16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+// Segment t of the grouped token order is [seg_off[t], seg_off[t+1]).
+// Largest t in [0, n] with seg_off[t] <= m (seg_off has n + 2 entries, last = T).
+__device__ __forceinline__ int segment_of(const int32_t* __restrict__ seg_off, int n, int m) {
+  int lo = 0, hi = n + 1;  // invariant: seg_off[lo] <= m < seg_off[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (seg_off[mid] <= m) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// ---- launchers (implemented in the .hip files; all enqueue on `stream`) ----
+
+struct SegmapDev {
+  int32_t* perm;      // [T] or nullptr when the grouped order is the identity
+  int32_t* seg_off;   // [n + 2]
+};
+
+hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* seg_off,
+                         int32_t* block_hist, int32_t* flags, hipStream_t stream);
+int segmap_blocks(int64_t T);
+
+// u[m, 0..r_stride) = scale_t * sum_c X[perm[m], c] * L_t(c, q), grouped order m.
+// which = 0 uses AdapterEntry::A as L_t, 1 uses ::B.  lora_form: FORM_NN when
+// L_t is stored [C, r_t] (q contiguous), FORM_NT when stored [r_t, C].
+hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
+                              const int32_t* seg_off, int n_adapters, int max_seg,
+                              const AdapterEntry* table, int which, int lora_form, float* u,
+                              int r_stride, int64_t T_lora, hipStream_t stream);
+
+// out[perm[m], :] = Aop[perm[m], :] * Bop + (m in segment t) U[m, :] * L_t
+hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
+                            int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
+                            const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
+                            int which, const float* U, int r_stride, void* out, int64_t ldo,
+                            int out_is_f32, hipStream_t stream);
+
+// out_t(c, q) (+)= sum_{m in seg t} X[perm[m], c] * V[m, q]
+// out_form FORM_NN: out_t[c * r_t + q]; FORM_NT: out_t[q * C + c].
+hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
+                              const int32_t* seg_off, int n_adapters, int max_seg,
+                              const AdapterEntry* table, const GradEntry* grads, int which,
+                              int out_form, const float* V, int r_stride, int accumulate,
+                              float* partials, size_t partial_bytes, hipStream_t stream);
+size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int max_rank);
+
+// fp32 path (plain ALU arithmetic, any shape)
+hipError_t launch_shrink_f32(const float* X, int64_t ldx, int64_t C, const int32_t* perm,
+                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
+                             int which, int lora_form, float* u, int r_stride, int64_t T_lora,
+                             hipStream_t stream);
+hipError_t launch_gemm_f32(const float* Aop, int64_t lda, const float* Bop, int64_t ldb, int form,
+                           int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
+                           const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
+                           int which, const float* U, int r_stride, void* out, int64_t ldo,
+                           int out_is_f32, hipStream_t stream);
+hipError_t launch_reduce_f32(const float* X, int64_t ldx, int64_t C, const int32_t* perm,
+                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
+                             const GradEntry* grads, int which, int out_form, const float* V,
+                             int r_stride, int accumulate, hipStream_t stream);
+
+}  // namespace marlaas

@@ -1,0 +1,336 @@
+// Base GEMM on the bf16 matrix cores with the LoRA expand fused in as extra
+// contraction steps:
+//
+//   out[tok(m), :] = Aop[tok(m), :] * Bop  +  [u_hi(m) | u_lo(m)] * [L_t ; L_t]
+//
+// m runs over tokens grouped by adapter (tok = perm), Bop is the shared frozen
+// base weight (paper Sec. 1 principle (1)), u = s_t * (x A_t) comes from the
+// shrink kernel in fp32 and is split here into two bf16 terms, and L_t is the
+// adapter's output-side factor (B_t in forward, A_t in backward).  Rows of a
+// tile that belong to another adapter are fed zeros for the extra steps, so a
+// tile may straddle any number of segments.
+//
+// Tile: 256 x 256 x 64 per workgroup of 8 waves (2 x 4), each wave 128 x 64 as
+// 4 x 2 MFMA 32x32x16 accumulators; operands staged through LDS in 16-byte
+// units with an XOR swizzle, double-buffered, next tile prefetched in registers.
+#include "common.h"
+
+namespace marlaas {
+
+static constexpr int BM = 256, BN = 256, BK = 64;
+static constexpr int GEMM_THREADS = 512;
+static constexpr int STAGE_BYTES = BM * BK * 2;        // 32 KB per operand per stage
+static constexpr int GEMM_LDS = 4 * STAGE_BYTES + BM * 4;  // 2 stages x 2 operands + token ids
+
+struct GemmArgs {
+  const bf16_t* Aop; int64_t lda;
+  const bf16_t* Bop; int64_t ldb;
+  int64_t T, Kc, Nout;
+  const int32_t* perm;
+  const int32_t* seg_off;
+  int n_adapters;
+  const AdapterEntry* table;
+  int which;               // 0: L_t = entry.A, 1: L_t = entry.B
+  const float* U; int r_stride;
+  void* out; int64_t ldo;
+  int tiles_m, tiles_n;
+};
+
+// LDS byte offset of 16-byte unit `unit` of row `row` in a [rows][64] bf16 tile.
+__device__ __forceinline__ int swz_rowk(int row, int unit) {
+  return row * 128 + ((unit ^ ((row >> 1) & 7)) << 4);
+}
+// LDS byte offset of 16-byte unit `unit` (of 32) of k-row `k` in a [64][256] bf16 tile.
+__device__ __forceinline__ int swz_kn(int k, int unit) {
+  return k * 512 + ((unit ^ ((k & 3) << 2)) << 4);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_frag(const char* base, int off) {
+  return *(const bf16x8*)(base + off);
+}
+
+// 8 consecutive contraction values of column n from a [k][n] tile: two
+// transposing 64-bit reads (each returns 4 consecutive k for this lane's column).
+__device__ __forceinline__ bf16x8 lds_read_frag_tr(const char* base, int off0, int off1) {
+  typedef short4v __attribute__((address_space(3))) * lds_s4;
+  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(base + off0));
+  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(base + off1));
+  union { short s[8]; bf16x8 v; } r;
+  r.s[0] = a[0]; r.s[1] = a[1]; r.s[2] = a[2]; r.s[3] = a[3];
+  r.s[4] = b[0]; r.s[5] = b[1]; r.s[6] = b[2]; r.s[7] = b[3];
+  return r.v;
+}
+
+template <int FORM, bool OUT_F32>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char* As = smem;                       // [2][STAGE_BYTES]
+  char* Bs = smem + 2 * STAGE_BYTES;     // [2][STAGE_BYTES]
+  int32_t* tok_s = (int32_t*)(smem + 4 * STAGE_BYTES);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+
+  // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
+  // tiles; inside a run, groups of 8 row tiles share their column tiles.
+  int tm, tn;
+  {
+    const int G = a.tiles_m * a.tiles_n;
+    const int b = blockIdx.x;
+    const int xcd = b & 7, idx = b >> 3;
+    const int q = G >> 3, rem = G & 7;
+    const int start = xcd * q + (xcd < rem ? xcd : rem);
+    const int bb = start + idx;
+    const int GM = 8;
+    const int per_group = GM * a.tiles_n;
+    const int gid = bb / per_group;
+    const int first_m = gid * GM;
+    const int gsz = (a.tiles_m - first_m) < GM ? (a.tiles_m - first_m) : GM;
+    const int in_g = bb - gid * per_group;
+    tm = first_m + in_g % gsz;
+    tn = in_g / gsz;
+  }
+  const int64_t m0 = (int64_t)tm * BM;
+  const int64_t n0 = (int64_t)tn * BN;
+
+  if (tid < BM) {
+    int64_t m = m0 + tid;
+    int32_t tok = -1;
+    if (m < a.T) tok = a.perm ? a.perm[m] : (int32_t)m;
+    tok_s[tid] = tok;
+  }
+  __syncthreads();
+
+  // ---- loader geometry
+  const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
+  const int lr = tid >> 3;       // 0..63
+  const bf16_t* a_ptr[4];
+  for (int i = 0; i < 4; ++i) {
+    int32_t tok = tok_s[lr + 64 * i];
+    a_ptr[i] = a.Aop + (int64_t)(tok < 0 ? 0 : tok) * a.lda + lc * 8;
+  }
+  const bf16_t* b_ptr[4];
+  bool b_ok[4];
+  const int ncu = tid & 31;      // 16-byte unit along n (k-n tiles)
+  const int nkr = tid >> 5;      // 0..15
+  if (FORM == FORM_NT) {
+    for (int i = 0; i < 4; ++i) {
+      int64_t n = n0 + lr + 64 * i;
+      b_ok[i] = n < a.Nout;
+      b_ptr[i] = a.Bop + (b_ok[i] ? n : 0) * a.ldb + lc * 8;
+    }
+  } else {
+    for (int i = 0; i < 4; ++i) {
+      b_ok[i] = (n0 + ncu * 8) < a.Nout;
+      b_ptr[i] = a.Bop + (int64_t)(nkr + 16 * i) * a.ldb + (b_ok[i] ? n0 + ncu * 8 : 0);
+    }
+  }
+
+  f32x16 acc[4][2];
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 2; ++j)
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  uint4 ra[4], rb[4];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  auto load_tile = [&](int64_t k0) {
+    const bool ka = (k0 + lc * 8) < a.Kc;
+    for (int i = 0; i < 4; ++i) ra[i] = ka ? *(const uint4*)(a_ptr[i] + k0) : zero4;
+    if (FORM == FORM_NT) {
+      for (int i = 0; i < 4; ++i) rb[i] = (ka && b_ok[i]) ? *(const uint4*)(b_ptr[i] + k0) : zero4;
+    } else {
+      for (int i = 0; i < 4; ++i) {
+        const bool kb = (k0 + nkr + 16 * i) < a.Kc;
+        rb[i] = (kb && b_ok[i]) ? *(const uint4*)(b_ptr[i] + k0 * a.ldb) : zero4;
+      }
+    }
+  };
+  auto store_tile = [&](int stage) {
+    char* as = As + stage * STAGE_BYTES;
+    char* bs = Bs + stage * STAGE_BYTES;
+    for (int i = 0; i < 4; ++i) *(uint4*)(as + swz_rowk(lr + 64 * i, lc)) = ra[i];
+    if (FORM == FORM_NT) {
+      for (int i = 0; i < 4; ++i) *(uint4*)(bs + swz_rowk(lr + 64 * i, lc)) = rb[i];
+    } else {
+      for (int i = 0; i < 4; ++i) *(uint4*)(bs + swz_kn(nkr + 16 * i, ncu)) = rb[i];
+    }
+  };
+
+  // ---- fragment geometry
+  const int frow = lane & 31;          // row inside a 32-row MFMA tile
+  const int fk = lane >> 5;            // which 8-wide half of the 16-wide k step
+  const int g16 = lane >> 4, i16 = lane & 15;
+
+  auto mma_steps = [&](int stage, int ksteps) {
+    const char* as = As + stage * STAGE_BYTES;
+    const char* bs = Bs + stage * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks < ksteps) {
+        bf16x8 af[4], bfr[2];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+          af[mt] = lds_read_frag(as, swz_rowk(wm * 128 + mt * 32 + frow, ks * 2 + fk));
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          if (FORM == FORM_NT) {
+            bfr[nt] = lds_read_frag(bs, swz_rowk(wn * 64 + nt * 32 + frow, ks * 2 + fk));
+          } else {
+            const int ncol = wn * 64 + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
+            const int kb = ks * 16 + (g16 >> 1) * 8 + (i16 >> 2);
+            bfr[nt] = lds_read_frag_tr(bs, swz_kn(kb, ncol >> 3) + (ncol & 7) * 2,
+                                       swz_kn(kb + 4, ncol >> 3) + (ncol & 7) * 2);
+          }
+        }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- main loop over the contraction dimension
+  const int64_t ktiles = (a.Kc + BK - 1) / BK;
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  for (int64_t kt = 0; kt < ktiles; ++kt) {
+    const int stage = (int)(kt & 1);
+    if (kt + 1 < ktiles) load_tile((kt + 1) * BK);
+    mma_steps(stage, 4);
+    if (kt + 1 < ktiles) store_tile(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- LoRA expand as extra contraction steps, one adapter segment at a time
+  if (a.n_adapters > 0 && a.U != nullptr) {
+    const int64_t T_lora = a.seg_off[a.n_adapters];
+    const int64_t m_end = (m0 + BM) < T_lora ? (m0 + BM) : T_lora;
+    if (m0 < m_end) {
+      int t = segment_of(a.seg_off, a.n_adapters, (int)m0);
+      while (t < a.n_adapters && (int64_t)a.seg_off[t] < m_end) {
+        const int64_t lo = a.seg_off[t] > m0 ? (int64_t)a.seg_off[t] : m0;
+        const int64_t hi = (int64_t)a.seg_off[t + 1] < m_end ? (int64_t)a.seg_off[t + 1] : m_end;
+        if (hi > lo) {
+          const AdapterEntry e = a.table[t];
+          const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
+          const int r = e.rank;
+          const int r_pad = (r + 15) & ~15;
+          const int kext = 2 * r_pad;
+          for (int kc = 0; kc < kext; kc += BK) {
+            // A side: [u_hi | u_lo] of the rows of this segment, zeros elsewhere
+            const int kk0 = kc + lc * 8;
+            const bool second = kk0 >= r_pad;
+            const int q0 = kk0 - (second ? r_pad : 0);
+            for (int i = 0; i < 4; ++i) {
+              const int64_t m = m0 + lr + 64 * i;
+              uint4 pk = zero4;
+              if (kk0 < kext && m >= lo && m < hi) {
+                const float4* up = (const float4*)(a.U + m * a.r_stride + q0);
+                float4 f0 = up[0], f1 = up[1];
+                float f[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
+                bf16_t o[8];
+                for (int j = 0; j < 8; ++j) {
+                  bf16_t h = float_to_bf16_bits(f[j]);
+                  o[j] = second ? float_to_bf16_bits(f[j] - bf16_bits_to_float(h)) : h;
+                }
+                pk.x = o[0] | ((uint32_t)o[1] << 16); pk.y = o[2] | ((uint32_t)o[3] << 16);
+                pk.z = o[4] | ((uint32_t)o[5] << 16); pk.w = o[6] | ((uint32_t)o[7] << 16);
+              }
+              *(uint4*)(As + swz_rowk(lr + 64 * i, lc)) = pk;
+            }
+            // B side: L_t stacked twice along the contraction
+            if (FORM == FORM_NT) {
+              for (int i = 0; i < 4; ++i) {
+                const int64_t n = n0 + lr + 64 * i;
+                uint4 pk = zero4;
+                if (kk0 < kext && n < a.Nout && q0 < r) {
+                  const bf16_t* lp = L + n * r + q0;
+                  if ((r & 7) == 0) {
+                    pk = *(const uint4*)lp;
+                  } else {
+                    bf16_t o[8];
+                    for (int j = 0; j < 8; ++j) o[j] = (q0 + j < r) ? lp[j] : (bf16_t)0;
+                    pk.x = o[0] | ((uint32_t)o[1] << 16); pk.y = o[2] | ((uint32_t)o[3] << 16);
+                    pk.z = o[4] | ((uint32_t)o[5] << 16); pk.w = o[6] | ((uint32_t)o[7] << 16);
+                  }
+                }
+                *(uint4*)(Bs + swz_rowk(lr + 64 * i, lc)) = pk;
+              }
+            } else {
+              for (int i = 0; i < 4; ++i) {
+                const int kk = kc + nkr + 16 * i;
+                const int q = kk - (kk >= r_pad ? r_pad : 0);
+                uint4 pk = zero4;
+                if (kk < kext && q < r && (n0 + ncu * 8) < a.Nout)
+                  pk = *(const uint4*)(L + (int64_t)q * a.Nout + n0 + ncu * 8);
+                *(uint4*)(Bs + swz_kn(nkr + 16 * i, ncu)) = pk;
+              }
+            }
+            __syncthreads();
+            const int left = kext - kc;
+            mma_steps(0, left >= BK ? 4 : left / 16);
+            __syncthreads();
+          }
+        }
+        ++t;
+      }
+    }
+  }
+
+  // ---- epilogue: scatter rows back to token order
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = wm * 128 + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int32_t tok = tok_s[row];
+      if (tok < 0) continue;
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const int64_t col = n0 + wn * 64 + nt * 32 + (lane & 31);
+        if (col < a.Nout) {
+          if (OUT_F32) ((float*)a.out)[(int64_t)tok * a.ldo + col] = acc[mt][nt][v];
+          else ((bf16_t*)a.out)[(int64_t)tok * a.ldo + col] = float_to_bf16_bits(acc[mt][nt][v]);
+        }
+      }
+    }
+  }
+}
+
+template <int FORM, bool OUT_F32>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
+  static bool attr_set = false;
+  auto kern = gemm_bf16_kernel<FORM, OUT_F32>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int G = a.tiles_m * a.tiles_n;
+  hipLaunchKernelGGL(kern, dim3(G), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
+                            int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
+                            const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
+                            int which, const float* U, int r_stride, void* out, int64_t ldo,
+                            int out_is_f32, hipStream_t stream) {
+  if (T <= 0 || Nout <= 0) return hipSuccess;
+  GemmArgs a;
+  a.Aop = Aop; a.lda = lda; a.Bop = Bop; a.ldb = ldb; a.T = T; a.Kc = Kc; a.Nout = Nout;
+  a.perm = perm; a.seg_off = seg_off; a.n_adapters = n_adapters; a.table = table; a.which = which;
+  a.U = U; a.r_stride = r_stride; a.out = out; a.ldo = ldo;
+  a.tiles_m = (int)((T + BM - 1) / BM);
+  a.tiles_n = (int)((Nout + BN - 1) / BN);
+  if (form == FORM_NT) return out_is_f32 ? launch_one<FORM_NT, true>(a, stream) : launch_one<FORM_NT, false>(a, stream);
+  return out_is_f32 ? launch_one<FORM_NN, true>(a, stream) : launch_one<FORM_NN, false>(a, stream);
+}
+
+}  // namespace marlaas

@@ -1,0 +1,353 @@
+// The low-rank side of the layer on bf16 data: the segmented shrink
+// u = s_t (x A_t)  /  v = s_t (dY B_t^T), and the per-adapter weight-gradient
+// reductions dA_t = sum x_i^T v_i, dB_t = sum u_i^T dY_i.  Only the per-task
+// LoRA parameters are trained (paper Sec. 4.2), so these are the only weight
+// gradients of the layer.  Both kernels read their big operand (x or dY) once
+// and are bound by HBM; the small operand stays in LDS.
+#include "common.h"
+
+namespace marlaas {
+
+// ============================================================== shrink
+static constexpr int SH_THREADS = 256;
+static constexpr int SH_ROWS = 64;     // rows per block (16 per wave)
+static constexpr int SH_KSTG = 256;    // contraction values staged per step
+static constexpr int SH_PITCH = SH_KSTG * 2 + 16;  // bytes per staged L row
+
+struct ShrinkArgs {
+  const bf16_t* X; int64_t ldx; int64_t C;
+  const int32_t* perm; const int32_t* seg_off;
+  const AdapterEntry* table; int which;
+  float* u; int r_stride;
+  int ksplit; int kchunk;   // kchunk is a multiple of SH_KSTG
+};
+
+// grid: x = row blocks of the largest segment * ksplit, y = adapter
+template <int LFORM>
+__global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char Ls[];   // [r_pad][SH_PITCH]
+  const int t = blockIdx.y;
+  const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
+  const int rb = blockIdx.x / a.ksplit, ks = blockIdx.x - rb * a.ksplit;
+  const int row0 = lo + rb * SH_ROWS;
+  if (row0 >= hi) return;
+  const AdapterEntry e = a.table[t];
+  const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
+  const int r = e.rank;
+  const int r_pad = (r + 15) & ~15;
+  const int nqt = r_pad >> 4;
+  const int64_t kbeg = (int64_t)ks * a.kchunk;
+  const int64_t kend = (kbeg + a.kchunk) < a.C ? (kbeg + a.kchunk) : a.C;
+  if (kbeg >= kend) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, li = lane & 15;
+  int m = row0 + wave * 16 + li;
+  if (m >= hi) m = hi - 1;                   // clamped rows are never stored
+  const int64_t tok = a.perm ? a.perm[m] : m;
+  const bf16_t* xrow = a.X + tok * a.ldx;
+
+  f32x4 acc[8];
+  for (int q = 0; q < 8; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  for (int64_t k0 = kbeg; k0 < kend; k0 += SH_KSTG) {
+    // x fragments of this step: lane group g owns 32 consecutive k of every 128
+    uint4 xf[2][4];
+    for (int ms = 0; ms < 2; ++ms)
+      for (int j = 0; j < 4; ++j) {
+        const int64_t k = k0 + ms * 128 + g * 32 + j * 8;
+        xf[ms][j] = k < kend ? *(const uint4*)(xrow + k) : zero4;
+      }
+    __syncthreads();   // previous step's reads of Ls are done
+    if (LFORM == FORM_NT) {          // L_t[q * C + c]
+      const int unit = tid & 31;
+      for (int q = tid >> 5; q < r_pad; q += 8) {
+        const int64_t k = k0 + unit * 8;
+        uint4 v = zero4;
+        if (q < r && k < kend) v = *(const uint4*)(L + (int64_t)q * a.C + k);
+        *(uint4*)(Ls + q * SH_PITCH + unit * 16) = v;
+      }
+    } else {                          // L_t[c * r + q]
+      const int64_t k = k0 + tid;
+      const bool ok = k < kend;
+      const bf16_t* lp = L + k * r;
+      if ((r & 7) == 0) {
+        for (int q0 = 0; q0 < r_pad; q0 += 8) {
+          uint4 v = (ok && q0 < r) ? *(const uint4*)(lp + q0) : zero4;
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+          for (int j = 0; j < 8; ++j)
+            *(bf16_t*)(Ls + (q0 + j) * SH_PITCH + tid * 2) = (bf16_t)(w[j >> 1] >> ((j & 1) * 16));
+        }
+      } else {
+        for (int q = 0; q < r_pad; ++q)
+          *(bf16_t*)(Ls + q * SH_PITCH + tid * 2) = (ok && q < r) ? lp[q] : (bf16_t)0;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ms = 0; ms < 2; ++ms)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        union { uint4 u; bf16x8 v; } xa; xa.u = xf[ms][j];
+        const int koff = (ms * 128 + g * 32 + j * 8) * 2;
+#pragma unroll
+        for (int qt = 0; qt < 8; ++qt)
+          if (qt < nqt) {
+            bf16x8 b = *(const bf16x8*)(Ls + (qt * 16 + li) * SH_PITCH + koff);
+            acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b, acc[qt], 0, 0, 0);
+          }
+      }
+  }
+  // D layout: row = 4 * (lane / 16) + v, column = lane % 16
+#pragma unroll
+  for (int qt = 0; qt < 8; ++qt)
+    if (qt < nqt)
+      for (int v = 0; v < 4; ++v) {
+        const int mr = row0 + wave * 16 + 4 * g + v;
+        if (mr < hi) {
+          float* up = a.u + (int64_t)mr * a.r_stride + qt * 16 + li;
+          const float val = e.scale * acc[qt][v];
+          if (a.ksplit > 1) atomicAdd(up, val); else *up = val;
+        }
+      }
+}
+
+hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
+                              const int32_t* seg_off, int n_adapters, int max_seg,
+                              const AdapterEntry* table, int which, int lora_form, float* u,
+                              int r_stride, int64_t T_lora, hipStream_t stream) {
+  if (n_adapters <= 0 || max_seg <= 0 || T_lora <= 0) return hipSuccess;
+  ShrinkArgs a;
+  a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
+  a.which = which; a.u = u; a.r_stride = r_stride;
+  const int rb_max = (max_seg + SH_ROWS - 1) / SH_ROWS;
+  const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
+  const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
+  int ksplit = 1;
+  if (real_blocks < 512) {
+    ksplit = (int)((1024 + real_blocks - 1) / real_blocks);
+    if (ksplit > kst) ksplit = kst;
+  }
+  a.kchunk = ((kst + ksplit - 1) / ksplit) * SH_KSTG;
+  ksplit = (int)((C + a.kchunk - 1) / a.kchunk);
+  a.ksplit = ksplit;
+  if (ksplit > 1) {
+    hipError_t e = hipMemsetAsync(u, 0, (size_t)T_lora * r_stride * sizeof(float), stream);
+    if (e != hipSuccess) return e;
+  }
+  const size_t lds = (size_t)r_stride * SH_PITCH;   // r_stride >= every r_pad
+  auto kern = lora_form == FORM_NT ? shrink_bf16_kernel<FORM_NT> : shrink_bf16_kernel<FORM_NN>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, dim3(rb_max * ksplit, n_adapters), dim3(SH_THREADS), lds, stream, a);
+  return hipGetLastError();
+}
+
+// ============================================================== reduce
+static constexpr int RD_THREADS = 256;
+static constexpr int RD_COLS = 256;    // columns of X per block (64 per wave)
+static constexpr int RD_TOK = 64;      // tokens staged per step
+static constexpr int RD_VPITCH = RD_TOK * 2 + 16;   // bytes per row of the transposed V tile
+
+struct ReduceArgs {
+  const bf16_t* X; int64_t ldx; int64_t C;
+  const int32_t* perm; const int32_t* seg_off;
+  const AdapterEntry* table; const GradEntry* grads; int which;   // 0: write dA, 1: write dB
+  const float* V; int r_stride;
+  int accumulate;
+  int slabs; int tchunk; int chunks_max;   // tchunk multiple of RD_TOK
+  float* partials;                         // [adapter][chunk][C][r_stride] when chunks_max > 1
+};
+
+// LDS byte offset of 16-byte unit `unit` (of 32) of token row `tk` in the [64][256] X tile.
+__device__ __forceinline__ int swz_tokc(int tk, int unit) {
+  const int f = (tk & 3) | (((tk >> 3) & 1) << 2);
+  return tk * 512 + ((unit ^ (f << 1)) << 4);
+}
+
+// grid: x = slabs * chunks_max, y = adapter
+template <int OFORM>
+__global__ __launch_bounds__(RD_THREADS) void reduce_bf16_kernel(ReduceArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char rsm[];
+  char* Xs = rsm;                               // [RD_TOK][RD_COLS] bf16, swizzled
+  char* Vt = rsm + RD_TOK * RD_COLS * 2;        // [2][r_pad][RD_VPITCH]: hi, lo, transposed
+  const int t = blockIdx.y;
+  const int slab = blockIdx.x % a.slabs, ch = blockIdx.x / a.slabs;
+  const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
+  const int beg = lo + ch * a.tchunk;
+  const bool empty = beg >= hi;
+  if (empty && !(ch == 0 && a.chunks_max == 1 && !a.accumulate)) return;  // empty adapter: write zeros
+  const int end = (beg + a.tchunk) < hi ? (beg + a.tchunk) : hi;
+  const AdapterEntry e = a.table[t];
+  const int r = e.rank, r_pad = (r + 15) & ~15, nqt = r_pad >> 4;
+  const int64_t c0 = (int64_t)slab * RD_COLS;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, li = lane & 15;
+  f32x4 acc[4][8];
+  for (int i = 0; i < 4; ++i)
+    for (int q = 0; q < 8; ++q) acc[i][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  const int xu = tid & 31, xr = tid >> 5;     // X loader: unit along c, token row (+8 per step)
+  const bool col_ok = (c0 + xu * 8) < a.C;
+  const int vtok = tid & 63, vq0 = tid >> 6;  // V loader: token, first q (+4 per step)
+
+  for (int s = beg; s < end; s += RD_TOK) {
+    uint4 xv[8];
+    for (int i = 0; i < 8; ++i) {
+      const int m = s + xr + 8 * i;
+      xv[i] = zero4;
+      if (m < end && col_ok) {
+        const int64_t tok = a.perm ? a.perm[m] : m;
+        xv[i] = *(const uint4*)(a.X + tok * a.ldx + c0 + xu * 8);
+      }
+    }
+    __syncthreads();
+    for (int i = 0; i < 8; ++i) *(uint4*)(Xs + swz_tokc(xr + 8 * i, xu)) = xv[i];
+    {
+      const int m = s + vtok;
+      const float* vp = a.V + (int64_t)m * a.r_stride;
+      for (int q = vq0; q < r_pad; q += 4) {
+        const float f = (m < end && q < r) ? vp[q] : 0.f;
+        const bf16_t h = float_to_bf16_bits(f);
+        const bf16_t l = float_to_bf16_bits(f - bf16_bits_to_float(h));
+        *(bf16_t*)(Vt + q * RD_VPITCH + vtok * 2) = h;
+        *(bf16_t*)(Vt + (r_pad + q) * RD_VPITCH + vtok * 2) = l;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kstep = 0; kstep < 2; ++kstep) {
+      bf16x8 xa[4];
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        // lanes of group g need tokens kstep*32 + g*8 + 0..7 of column wave*64 + ct*16 + li
+        typedef short4v __attribute__((address_space(3))) * lds_s4;
+        const int col = wave * 64 + ct * 16 + 4 * (li & 3);
+        const int tk = kstep * 32 + g * 8 + (li >> 2);
+        short4v p0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Xs + swz_tokc(tk, col >> 3) + (col & 7) * 2));
+        short4v p1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Xs + swz_tokc(tk + 4, col >> 3) + (col & 7) * 2));
+        union { short s[8]; bf16x8 v; } u;
+        u.s[0] = p0[0]; u.s[1] = p0[1]; u.s[2] = p0[2]; u.s[3] = p0[3];
+        u.s[4] = p1[0]; u.s[5] = p1[1]; u.s[6] = p1[2]; u.s[7] = p1[3];
+        xa[ct] = u.v;
+      }
+#pragma unroll
+      for (int qt = 0; qt < 8; ++qt)
+        if (qt < nqt) {
+          const int voff = (kstep * 32 + g * 8) * 2;
+          bf16x8 vh = *(const bf16x8*)(Vt + (qt * 16 + li) * RD_VPITCH + voff);
+          bf16x8 vl = *(const bf16x8*)(Vt + (r_pad + qt * 16 + li) * RD_VPITCH + voff);
+#pragma unroll
+          for (int ct = 0; ct < 4; ++ct) {
+            acc[ct][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[ct], vh, acc[ct][qt], 0, 0, 0);
+            acc[ct][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[ct], vl, acc[ct][qt], 0, 0, 0);
+          }
+        }
+    }
+  }
+  // D layout: row (column c of X) = 4 * (lane / 16) + v, column (q) = lane % 16
+  float* outp = a.which ? a.grads[t].dB : a.grads[t].dA;
+  float* part = a.chunks_max > 1
+      ? a.partials + ((int64_t)t * a.chunks_max + ch) * a.C * a.r_stride : nullptr;
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int qt = 0; qt < 8; ++qt)
+      if (qt < nqt)
+        for (int v = 0; v < 4; ++v) {
+          const int64_t c = c0 + wave * 64 + ct * 16 + 4 * g + v;
+          const int q = qt * 16 + li;
+          if (c < a.C && q < r) {
+            if (part) {
+              part[c * a.r_stride + q] = acc[ct][qt][v];
+            } else {
+              float* o = outp + (OFORM == FORM_NN ? c * r + q : (int64_t)q * a.C + c);
+              *o = a.accumulate ? *o + acc[ct][qt][v] : acc[ct][qt][v];
+            }
+          }
+        }
+}
+
+// out_t (+)= sum over the chunks of adapter t, in chunk order
+template <int OFORM>
+__global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
+  const int t = blockIdx.y;
+  const AdapterEntry e = a.table[t];
+  const int r = e.rank;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= a.C * r) return;
+  const int64_t c = idx / r;
+  const int q = (int)(idx - c * r);
+  const int len = a.seg_off[t + 1] - a.seg_off[t];
+  const int nch = (len + a.tchunk - 1) / a.tchunk;
+  float sum = 0.f;
+  for (int ch = 0; ch < nch; ++ch)
+    sum += a.partials[(((int64_t)t * a.chunks_max + ch) * a.C + c) * a.r_stride + q];
+  float* outp = a.which ? a.grads[t].dB : a.grads[t].dA;
+  float* o = outp + (OFORM == FORM_NN ? c * r + q : (int64_t)q * a.C + c);
+  *o = a.accumulate ? *o + sum : sum;
+}
+
+static void reduce_plan(int64_t C, int n_adapters, int max_seg, int* tchunk, int* chunks_max) {
+  const int slabs = (int)((C + RD_COLS - 1) / RD_COLS);
+  const int64_t base = (int64_t)slabs * n_adapters;
+  *tchunk = ((max_seg + RD_TOK - 1) / RD_TOK) * RD_TOK;
+  *chunks_max = 1;
+  if (*tchunk < RD_TOK) *tchunk = RD_TOK;
+  if (base < 256 && max_seg > 1024) {
+    int want = (int)((512 + base - 1) / base);
+    int tc = (max_seg + want - 1) / want;
+    if (tc < 512) tc = 512;
+    tc = ((tc + RD_TOK - 1) / RD_TOK) * RD_TOK;
+    *tchunk = tc;
+    *chunks_max = (max_seg + tc - 1) / tc;
+  }
+}
+
+size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int r_stride) {
+  int tc, cm;
+  reduce_plan(C, n_adapters, max_seg, &tc, &cm);
+  if (cm <= 1) return 0;
+  return (size_t)n_adapters * cm * C * r_stride * sizeof(float);
+}
+
+hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
+                              const int32_t* seg_off, int n_adapters, int max_seg,
+                              const AdapterEntry* table, const GradEntry* grads, int which,
+                              int out_form, const float* V, int r_stride, int accumulate,
+                              float* partials, size_t partial_bytes, hipStream_t stream) {
+  if (n_adapters <= 0) return hipSuccess;
+  ReduceArgs a;
+  a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
+  a.grads = grads; a.which = which; a.V = V; a.r_stride = r_stride; a.accumulate = accumulate;
+  a.slabs = (int)((C + RD_COLS - 1) / RD_COLS);
+  reduce_plan(C, n_adapters, max_seg, &a.tchunk, &a.chunks_max);
+  if (a.chunks_max > 1 &&
+      (partials == nullptr || partial_bytes < (size_t)n_adapters * a.chunks_max * C * r_stride * sizeof(float))) {
+    a.chunks_max = 1;   // no room for partial sums: one block walks the whole segment
+    a.tchunk = ((max_seg + RD_TOK - 1) / RD_TOK) * RD_TOK;
+    if (a.tchunk < RD_TOK) a.tchunk = RD_TOK;
+  }
+  a.partials = partials;
+  const size_t lds = (size_t)RD_TOK * RD_COLS * 2 + (size_t)2 * r_stride * RD_VPITCH;
+  auto kern = out_form == FORM_NN ? reduce_bf16_kernel<FORM_NN> : reduce_bf16_kernel<FORM_NT>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, dim3(a.slabs * a.chunks_max, n_adapters), dim3(RD_THREADS), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.chunks_max > 1) {
+    auto fin = out_form == FORM_NN ? reduce_finalize_kernel<FORM_NN> : reduce_finalize_kernel<FORM_NT>;
+    hipLaunchKernelGGL(fin, dim3((unsigned)((C * r_stride + 255) / 256), n_adapters), dim3(256), 0, stream, a);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace marlaas

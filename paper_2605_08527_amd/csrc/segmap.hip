@@ -1,0 +1,129 @@
+// Token grouping by adapter: a stable counting sort in three small kernels.
+// The mixed-tenant batch carries one adapter id per token (paper Sec. 4.5,
+// cross-task batching of rollouts); every later kernel works on tokens grouped
+// by adapter, so this map is built once per batch and reused by all layers.
+#include "common.h"
+
+namespace marlaas {
+
+static constexpr int SEG_THREADS = 256;
+static constexpr int SEG_CHUNK = 2048;  // tokens per block
+
+int segmap_blocks(int64_t T) { return (int)((T + SEG_CHUNK - 1) / SEG_CHUNK); }
+
+// bucket n collects tokens with id -1; flags[0] |= 1 on an id outside [-1, n),
+// flags[1] |= 1 when the ids are not already grouped in bucket order.
+__global__ __launch_bounds__(SEG_THREADS) void segmap_hist(const int32_t* __restrict__ ids,
+                                                           int64_t T, int n,
+                                                           int32_t* __restrict__ block_hist,
+                                                           int32_t* __restrict__ flags) {
+  extern __shared__ int32_t hist[];
+  for (int b = threadIdx.x; b <= n; b += SEG_THREADS) hist[b] = 0;
+  __syncthreads();
+  int64_t base = (int64_t)blockIdx.x * SEG_CHUNK;
+  bool bad = false, unsorted = false;
+  for (int j = threadIdx.x; j < SEG_CHUNK; j += SEG_THREADS) {
+    int64_t i = base + j;
+    if (i >= T) break;
+    int id = ids[i];
+    if (id < -1 || id >= n) { bad = true; continue; }
+    int b = id < 0 ? n : id;
+    atomicAdd(&hist[b], 1);
+    if (i + 1 < T) {
+      int nx = ids[i + 1];
+      int bn = nx < 0 ? n : nx;
+      if (bn < b) unsorted = true;
+    }
+  }
+  if (bad) atomicOr(&flags[0], 1);
+  if (unsorted) atomicOr(&flags[1], 1);
+  __syncthreads();
+  for (int b = threadIdx.x; b <= n; b += SEG_THREADS)
+    block_hist[(int64_t)blockIdx.x * (n + 1) + b] = hist[b];
+}
+
+// One block.  seg_off[b] = exclusive prefix of bucket totals (n + 2 entries);
+// block_hist[blk][b] is replaced by the first output slot of block blk in bucket b.
+__global__ __launch_bounds__(1024) void segmap_scan(int32_t* __restrict__ block_hist, int nblk,
+                                                    int n, int32_t* __restrict__ seg_off) {
+  extern __shared__ int32_t total[];
+  for (int b = threadIdx.x; b <= n; b += blockDim.x) {
+    int run = 0;
+    for (int k = 0; k < nblk; ++k) {
+      int c = block_hist[(int64_t)k * (n + 1) + b];
+      block_hist[(int64_t)k * (n + 1) + b] = run;
+      run += c;
+    }
+    total[b] = run;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int b = 0; b <= n; ++b) {
+      int c = total[b];
+      total[b] = run;
+      seg_off[b] = run;
+      run += c;
+    }
+    seg_off[n + 1] = run;
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b <= n; b += blockDim.x) {
+    int off = total[b];
+    for (int k = 0; k < nblk; ++k) block_hist[(int64_t)k * (n + 1) + b] += off;
+  }
+}
+
+// Stable scatter: tokens are taken 256 at a time in index order; inside such a
+// group a token's slot is the bucket cursor plus the number of earlier tokens
+// of the group with the same bucket.
+__global__ __launch_bounds__(SEG_THREADS) void segmap_scatter(const int32_t* __restrict__ ids,
+                                                              int64_t T, int n,
+                                                              const int32_t* __restrict__ block_base,
+                                                              int32_t* __restrict__ perm) {
+  extern __shared__ int32_t smem[];
+  int32_t* cursor = smem;              // [n + 1]
+  int32_t* grp = smem + (n + 1);       // [SEG_THREADS]
+  for (int b = threadIdx.x; b <= n; b += SEG_THREADS)
+    cursor[b] = block_base[(int64_t)blockIdx.x * (n + 1) + b];
+  int64_t base = (int64_t)blockIdx.x * SEG_CHUNK;
+  for (int g = 0; g < SEG_CHUNK / SEG_THREADS; ++g) {
+    int64_t i = base + (int64_t)g * SEG_THREADS + threadIdx.x;
+    int b = -1;
+    if (i < T) {
+      int id = ids[i];
+      if (id >= -1 && id < n) b = id < 0 ? n : id;
+    }
+    __syncthreads();  // cursor updates of the previous group are visible, grp is free
+    grp[threadIdx.x] = b;
+    __syncthreads();
+    int before = 0, after = 0;
+    if (b >= 0) {
+      for (int j = 0; j < (int)threadIdx.x; ++j) before += (grp[j] == b);
+      for (int j = threadIdx.x + 1; j < SEG_THREADS; ++j) after += (grp[j] == b);
+      perm[cursor[b] + before] = (int32_t)i;
+    }
+    __syncthreads();  // every slot of this group has been read from cursor
+    if (b >= 0 && after == 0) cursor[b] += before + 1;
+  }
+}
+
+hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* seg_off,
+                         int32_t* block_hist, int32_t* flags, hipStream_t stream) {
+  int nblk = segmap_blocks(T);
+  hipError_t e = hipMemsetAsync(flags, 0, 2 * sizeof(int32_t), stream);
+  if (e != hipSuccess) return e;
+  if (nblk > 0) {
+    hipLaunchKernelGGL(segmap_hist, dim3(nblk), dim3(SEG_THREADS), (n + 1) * sizeof(int32_t),
+                       stream, ids, T, n, block_hist, flags);
+  }
+  hipLaunchKernelGGL(segmap_scan, dim3(1), dim3(1024), (n + 1) * sizeof(int32_t), stream,
+                     block_hist, nblk, n, seg_off);
+  if (nblk > 0) {
+    hipLaunchKernelGGL(segmap_scatter, dim3(nblk), dim3(SEG_THREADS),
+                       (n + 1 + SEG_THREADS) * sizeof(int32_t), stream, ids, T, n, block_hist, perm);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace marlaas

@@ -1,0 +1,78 @@
+"""Glue for the GPU parity tests: move a numpy workload to the device, run the
+HIP library through its binding, and bring the results back as numpy."""
+import numpy as np
+import torch
+
+from paper_2605_08527_amd import api
+from paper_2605_08527_amd import workloads as wl
+
+TOL_MAX, TOL_MEAN = 1e-2, 1e-3   # floored relative error vs the fp64 oracle (bf16 in, fp32 accumulate)
+
+
+def to_dev(a):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t):
+    if t.dtype == torch.bfloat16:
+        return wl.bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+class HipLayer:
+    """One workload resident on the GPU with its context, map and descriptor."""
+
+    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None):
+        self.w = w
+        self.ctx = ctx or api.marlaas_create(0)
+        self.x, self.W = to_dev(w["x"]), to_dev(w["W"])
+        self.A = [to_dev(a) for a in w["A"]]
+        self.B = [to_dev(b) for b in w["B"]]
+        self.ids = torch.from_numpy(np.ascontiguousarray(w["ids"], dtype=np.int32)).cuda()
+        self.dY = to_dev(w["dY"]) if w.get("dY") is not None else None
+        self.n = len(self.A)
+        self.map = api.marlaas_segmap_build(self.ctx, self.ids, self.n)
+        self.desc = api.LoraDesc(self.x, self.W, self.A, self.B, w["ranks"], w["scales"], self.map,
+                                 layout=w["layout"], out_dtype=out_dtype)
+        self.out_dtype = out_dtype
+        nbytes = api.marlaas_workspace_bytes(self.desc, want_bwd)
+        self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        api.marlaas_set_workspace(self.ctx, self.ws)
+        self.T, self.K, self.N = self.desc.shape[:3]
+
+    def fwd(self, save_u=False):
+        y = torch.full((self.T, self.N), float("nan"), dtype=self.out_dtype, device="cuda")
+        u = None
+        if save_u:
+            u = torch.zeros((max(self.T, 1), api.marlaas_u_stride(self.desc)), dtype=torch.float32, device="cuda")
+        api.marlaas_lora_fwd(self.ctx, self.desc, y, u_save=u)
+        torch.cuda.synchronize()
+        return y, u
+
+    def bwd(self, u_saved=None, accumulate=False, init=None, want_dX=True, want_grads=True):
+        dX = torch.full((self.T, self.K), float("nan"), dtype=self.out_dtype, device="cuda") if want_dX else None
+        dA = dB = None
+        if want_grads:
+            fill = float("nan") if init is None else init
+            dA = [torch.full(tuple(a.shape), fill, dtype=torch.float32, device="cuda") for a in self.A]
+            dB = [torch.full(tuple(b.shape), fill, dtype=torch.float32, device="cuda") for b in self.B]
+        api.marlaas_lora_bwd(self.ctx, self.desc, self.dY, dX=dX, dA=dA, dB=dB, u_saved=u_saved,
+                             accumulate=accumulate)
+        torch.cuda.synchronize()
+        return dX, dA, dB
+
+
+def oracle_grads_in_layout(dA, dB, layout):
+    """Oracle gradients are in math orientation; transpose for the torch layout."""
+    if layout == 1:
+        return [a.T for a in dA], [b.T for b in dB]
+    return dA, dB
+
+
+def assert_close(got, ref, what, tol_max=TOL_MAX, tol_mean=TOL_MEAN):
+    mx, mean, nrm = wl.rel_err_stats(got, ref)
+    assert np.all(np.isfinite(got)), "%s has non-finite values" % what
+    assert mx <= tol_max and mean <= tol_mean, "%s: max rel %.3e mean rel %.3e norm %.3e" % (what, mx, mean, nrm)
+    return mx, mean

@@ -1,0 +1,190 @@
+"""GPU parity: the HIP library (through the C ABI) against the fp64 oracle,
+element by element, on the same seeded inputs.  Tolerance: floored relative
+error max <= 1e-2 and mean <= 1e-3 per output tensor (bf16 inputs, fp32
+accumulation); fp32 outputs of the fp32 path are held to 1e-4 / 1e-5."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_08527_amd import api
+from paper_2605_08527_amd import workloads as wl
+from helpers import HipLayer, assert_close, oracle_grads_in_layout, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_all(oracle, w, bwd):
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    y = oracle.fwd(*args, layout=w["layout"])
+    if not bwd:
+        return y, None, None, None
+    dX, dA, dB = oracle.bwd(*args, w["dY"], layout=w["layout"])
+    dA, dB = oracle_grads_in_layout(dA, dB, w["layout"])
+    return y, dX, dA, dB
+
+
+def _check_layer(oracle, w, bwd, out_dtype=torch.float32, tol=(1e-2, 1e-3), tag=""):
+    y_ref, dX_ref, dA_ref, dB_ref = _oracle_all(oracle, w, bwd)
+    L = HipLayer(w, out_dtype=out_dtype, want_bwd=bwd)
+    y, u = L.fwd(save_u=bwd)
+    stats = {"y": assert_close(to_host(y), y_ref, tag + " y", *tol)}
+    if bwd:
+        for saved in (u, None):      # with the saved intermediate, then recomputing it
+            dX, dA, dB = L.bwd(u_saved=saved)
+            stats["dX"] = assert_close(to_host(dX), dX_ref, tag + " dX", *tol)
+            for t in range(L.n):
+                assert_close(to_host(dA[t]), dA_ref[t], tag + " dA[%d]" % t, *tol)
+                assert_close(to_host(dB[t]), dB_ref[t], tag + " dB[%d]" % t, *tol)
+    return stats
+
+
+# ------------------------------------------------------------------ segment map
+@pytest.mark.parametrize("T,n,neg", [(0, 4, False), (1, 1, False), (64, 4, False), (256, 32, True),
+                                     (5000, 7, True), (16896, 64, False), (70000, 300, True)])
+def test_segmap_matches_stable_argsort(T, n, neg):
+    rng = np.random.default_rng(T + n)
+    ids = rng.integers(-1 if neg else 0, n, size=T).astype(np.int32)
+    if n > 2:
+        ids[ids == 1] = 0        # adapter 1 stays empty
+    ctx = api.marlaas_create(0)
+    m = api.marlaas_segmap_build(ctx, torch.from_numpy(ids).cuda(), n)
+    perm, seg_off = api.marlaas_segmap_export(m)
+    key = np.where(ids < 0, n, ids)
+    assert np.array_equal(perm, np.argsort(key, kind="stable").astype(np.int32))
+    counts = np.bincount(key, minlength=n + 1)
+    assert np.array_equal(seg_off, np.concatenate([[0], np.cumsum(counts)]).astype(np.int32))
+
+
+def test_segmap_rejects_bad_ids():
+    ctx = api.marlaas_create(0)
+    for bad in (4, -2):
+        ids = torch.tensor([0, 1, bad, 3], dtype=torch.int32, device="cuda")
+        with pytest.raises(api.MarlaasError) as e:
+            api.marlaas_segmap_build(ctx, ids, 4)
+        assert e.value.status == -1
+
+
+# ------------------------------------------------------------------ config 0 (fp32)
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config0_fp32(oracle, layout, seed):
+    w = wl.make_config(0, seed=seed, layout=layout, want_dY=True)
+    _check_layer(oracle, w, bwd=True, tol=(1e-4, 1e-5), tag="cfg0")
+
+
+# ------------------------------------------------------------------ bf16 configs, reduced sizes
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("cfg,scale", [(1, 0.25), (2, 0.05), (3, 0.03), (4, 0.08)])
+def test_bf16_configs_scaled(oracle, cfg, scale, layout):
+    w = wl.make_config(cfg, seed=cfg, scale=scale, layout=layout, want_dY=True)
+    _check_layer(oracle, w, bwd=True, tag="cfg%d@%g" % (cfg, scale))
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_bf16_output_dtype(oracle, layout):
+    """bf16 outputs: the final rounding alone costs up to 2^-9 relative, so the
+    mean bound is the one of the metric with that floor added."""
+    w = wl.make_config(4, seed=7, scale=0.05, layout=layout, want_dY=True)
+    _check_layer(oracle, w, bwd=True, out_dtype=torch.bfloat16, tol=(1e-2, 2.5e-3), tag="bf16out")
+
+
+# ------------------------------------------------------------------ config 1 at full size
+@pytest.mark.parametrize("layout", [0, 1])
+def test_config1_full(oracle, layout):
+    w = wl.make_config(1, seed=0, layout=layout)
+    _check_layer(oracle, w, bwd=False, tag="cfg1")
+
+
+# ------------------------------------------------------------------ ragged shapes and odd ranks
+@pytest.mark.parametrize("layout", [0, 1])
+def test_ragged_shapes_and_ranks(oracle, layout):
+    rng = np.random.default_rng(5)
+    ranks = [1, 5, 12, 100, 128, 16, 7]
+    T = 777
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    ids[ids == 5] = 2    # adapter 5 empty
+    w = wl.make_layer(13, T, 520, 328, ranks, [2.0, 0.5, 1.0, 0.25, 0.125, 1.0, 3.0], ids,
+                      dtype="bf16", layout=layout, want_dY=True)
+    _check_layer(oracle, w, bwd=True, tag="ragged")
+
+
+def test_no_adapters_and_all_base_tokens(oracle):
+    w = wl.make_layer(3, 300, 256, 512, [], [], np.full(300, -1, np.int32), dtype="bf16", want_dY=True)
+    L = HipLayer(w, want_bwd=True)
+    y, _ = L.fwd()
+    y_ref = oracle.fwd(w["x"], w["W"], [], [], [], [], w["ids"])
+    assert_close(to_host(y), y_ref, "n=0 y")
+    dX, _, _ = L.bwd(want_grads=False)
+    dX_ref, _, _ = oracle.bwd(w["x"], w["W"], [], [], [], [], w["ids"], w["dY"])
+    assert_close(to_host(dX), dX_ref, "n=0 dX")
+    # adapters exist but every token is base-only: gradients must be zero, y unchanged
+    w2 = wl.make_layer(3, 300, 256, 512, [8, 16], [2.0, 2.0], np.full(300, -1, np.int32), dtype="bf16", want_dY=True)
+    L2 = HipLayer(w2, want_bwd=True)
+    y2, _ = L2.fwd()
+    assert torch.equal(y2, y)
+    _, dA, dB = L2.bwd()
+    assert all(float(g.abs().max()) == 0.0 for g in dA + dB)
+
+
+def test_zero_B_is_bitwise_base_only():
+    """With B_t = 0 the fused extra steps add exact zeros: y must equal the
+    base-only result bit for bit."""
+    w = wl.make_config(4, seed=1, scale=0.05)
+    w0 = dict(w, B=[np.zeros_like(b) for b in w["B"]])
+    wb = dict(w, ids=np.full_like(w["ids"], -1))
+    y0, _ = HipLayer(w0).fwd()
+    yb, _ = HipLayer(wb).fwd()
+    assert torch.equal(y0, yb)
+
+
+def test_permutation_equivariance_on_gpu():
+    w = wl.make_config(4, seed=2, scale=0.04, want_dY=True)
+    perm = np.random.default_rng(0).permutation(w["T"])
+    wp = dict(w, x=np.ascontiguousarray(w["x"][perm]), dY=np.ascontiguousarray(w["dY"][perm]), ids=w["ids"][perm])
+    L, Lp = HipLayer(w, want_bwd=True), HipLayer(wp, want_bwd=True)
+    y, _ = L.fwd()
+    yp, _ = Lp.fwd()
+    assert_close(to_host(yp), to_host(y)[perm], "perm y", 1e-5, 1e-6)
+
+
+def test_accumulate_and_empty_tokens(oracle):
+    w = wl.make_config(4, seed=3, scale=0.04, want_dY=True)
+    L = HipLayer(w, want_bwd=True)
+    _, dA0, dB0 = L.bwd(want_dX=False)
+    _, dA1, dB1 = L.bwd(want_dX=False, accumulate=True, init=1.0)
+    for a0, a1 in zip(dA0 + dB0, dA1 + dB1):
+        assert float((a1 - 1.0 - a0).abs().max()) <= 1e-5 * max(1.0, float(a0.abs().max()))
+    # T = 0: forward is a no-op, backward zero-fills the gradients
+    w0 = wl.make_layer(1, 0, 64, 64, [8], [1.0], np.zeros(0, np.int32), dtype="bf16", want_dY=True)
+    L0 = HipLayer(w0, want_bwd=True)
+    L0.fwd()
+    _, dA, dB = L0.bwd()
+    assert float(dA[0].abs().max()) == 0.0 and float(dB[0].abs().max()) == 0.0
+
+
+def test_argument_errors_are_reported():
+    w = wl.make_layer(1, 32, 64, 64, [8], [1.0], np.zeros(32, np.int32), dtype="bf16")
+    L = HipLayer(w)
+    y = torch.empty((32, 64), dtype=torch.float32, device="cuda")
+    lib = api.load()
+    ok = L.desc.c
+    def status(**kw):
+        import copy, ctypes
+        c = api.marlaas_lora_desc.from_buffer_copy(ok)
+        for k, v in kw.items():
+            setattr(c, k, v)
+        return lib.marlaas_lora_fwd(L.ctx.handle, ctypes.byref(c), y.data_ptr(), 64, None,
+                                    torch.cuda.current_stream().cuda_stream)
+    assert status() == 0
+    assert status(x=None) == -1
+    assert status(d_in=60) == -3
+    assert status(x=ok.x + 2) == -3
+    assert status(ldx=32) == -3
+    assert status(T=31) == -2
+    assert status(in_dtype=7) == -1
+    bad_rank = (api.ctypes.c_int32 * 1)(0)
+    assert status(ranks=api.ctypes.cast(bad_rank, api.ctypes.POINTER(api.ctypes.c_int32))) == -1
+    api.marlaas_set_workspace(L.ctx, None)
+    assert status() == -4
+    assert b"workspace" in lib.marlaas_last_error(L.ctx.handle)
+    torch.cuda.synchronize()

@@ -1,0 +1,76 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its argument-free entry points behave (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+
+from paper_2605_08527_amd import api
+from paper_2605_08527_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "marlaas_lora.h")).read()
+    declared = set(re.findall(r"\b(marlaas_[a-z_]+)\s*\(", header))
+    assert declared == set(api.EXPORTS), declared ^ set(api.EXPORTS)
+    lib = api.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_strerror_and_null_arguments():
+    lib = api.load()
+    assert lib.marlaas_strerror(0) == b"ok"
+    assert b"align" in lib.marlaas_strerror(-3)
+    assert lib.marlaas_strerror(-99) == b"unknown status"
+    assert lib.marlaas_workspace_bytes(None, 0) == 0
+    assert lib.marlaas_u_stride(None) == 0
+    assert lib.marlaas_create(None, 0) == -1
+    assert lib.marlaas_last_error(None) == b"null context"
+    lib.marlaas_destroy(None)
+    lib.marlaas_segmap_destroy(None)
+
+
+def test_desc_struct_matches_header_field_order():
+    header = open(os.path.join(ROOT, "include", "marlaas_lora.h")).read()
+    body = header[header.index("typedef struct {"):header.index("} marlaas_lora_desc;")]
+    names = re.findall(r"\b(\w+);", body)
+    assert names == [f[0] for f in api.marlaas_lora_desc._fields_]
+
+
+def test_bf16_rounding_is_nearest_even():
+    f = np.array([1.0, 1.00390625, 1.01171875, -2.5, 3.14159, 1e-3], dtype=np.float32)
+    bits = wl.f32_to_bf16_bits(f)
+    back = wl.bf16_bits_to_f32(bits)
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7: even mantissa wins
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.015625 and back[3] == -2.5
+    assert np.all(np.abs(back - f) <= np.abs(f) * 2.0 ** -8)
+
+
+def test_workloads_are_reproducible_and_shaped():
+    for cfg in range(5):
+        sh, ranks, scales, ids = wl.config_ids(cfg, 0)
+        sh2, ranks2, scales2, ids2 = wl.config_ids(cfg, 0)
+        assert np.array_equal(ids, ids2) and np.array_equal(ranks, ranks2)
+        assert ids.shape == (sh["T"],) and ids.min() >= 0 and ids.max() < sh["n"]
+    assert wl.config_shape(2)["T"] == 40960 and wl.config_shape(3)["T"] == 262144
+    assert wl.config_shape(4)["T"] == 16896
+    _, _, _, ids = wl.config_ids(2, 0)
+    assert np.all(np.diff(ids) >= 0) and len(np.unique(ids)) == 32
+    _, _, _, ids = wl.config_ids(4, 0)
+    assert np.any(np.diff(ids) < 0)
+    a = wl.make_config(0, seed=3)
+    b = wl.make_config(0, seed=3, layout=wl.TORCH)
+    assert np.array_equal(a["W"].T, b["W"]) and np.array_equal(a["A"][1].T, b["A"][1])
+    cnt = np.bincount(wl.config_ids(1, 0)[3], minlength=32)
+    assert cnt[0] > 4 * max(1, cnt[16])   # Zipf head dominates
+
+
+def test_rel_err_stats_definition():
+    ref = np.array([3.0, -4.0, 0.0, 0.0])          # rms = 2.5
+    got = np.array([3.3, -4.0, 0.25, 0.0])
+    mx, mean, nrm = wl.rel_err_stats(got, ref)
+    assert abs(mx - 0.1) < 1e-12 and abs(mean - (0.1 + 0.1) / 4) < 1e-12
