@@ -145,6 +145,22 @@ int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, const void
                      const void* u_saved, void* dX, int64_t lddx, void* const* dA,
                      void* const* dB, int accumulate, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of
+ * marlaas_lora_fwd / marlaas_lora_bwd on this ctx is bracketed by a pair of HIP
+ * events on the caller's stream (this allocates events: not for production
+ * loops).  marlaas_profile_read waits for the recorded events of one kernel
+ * family and returns their summed duration and count; enabling or disabling
+ * clears the record.
+ */
+typedef enum {
+  MARLAAS_KERNEL_SHRINK = 1,  /* u = s_t x A_t  /  v = s_t dY B_t^T */
+  MARLAAS_KERNEL_GEMM = 2,    /* base product with the fused expand */
+  MARLAAS_KERNEL_REDUCE = 3   /* dA_t / dB_t reductions */
+} marlaas_kernel;
+int marlaas_profile_enable(marlaas_ctx* ctx, int on);
+int marlaas_profile_read(marlaas_ctx* ctx, int kernel, double* total_ms, int64_t* launches);
+
 /* Row stride (in floats) of u_save: the largest rank rounded up to 16; 0 if invalid. */
 int64_t marlaas_u_stride(const marlaas_lora_desc* desc);
 

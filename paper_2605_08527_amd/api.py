@@ -21,8 +21,9 @@ EXPORTS = [
     "marlaas_create", "marlaas_destroy", "marlaas_strerror", "marlaas_last_error",
     "marlaas_segmap_build", "marlaas_segmap_destroy", "marlaas_segmap_export",
     "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd",
-    "marlaas_u_stride",
+    "marlaas_u_stride", "marlaas_profile_enable", "marlaas_profile_read",
 ]
+MARLAAS_KERNEL_SHRINK, MARLAAS_KERNEL_GEMM, MARLAAS_KERNEL_REDUCE = 1, 2, 3
 
 
 class marlaas_lora_desc(ctypes.Structure):
@@ -75,6 +76,10 @@ def load():
     lib.marlaas_lora_bwd.restype = ctypes.c_int
     lib.marlaas_u_stride.argtypes = [ctypes.POINTER(marlaas_lora_desc)]
     lib.marlaas_u_stride.restype = i64
+    lib.marlaas_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.marlaas_profile_enable.restype = ctypes.c_int
+    lib.marlaas_profile_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.marlaas_profile_read.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -241,3 +246,14 @@ def marlaas_lora_bwd(ctx, desc, dY, dX=None, dA=None, dB=None, u_saved=None, acc
     lddx = (dX.stride(0) if dX.shape[0] > 0 else dX.shape[1]) if dX is not None else 0
     _check(ctx, load().marlaas_lora_bwd(ctx.handle, desc.ref, _ptr(dY), lddy, _ptr(u_saved), _ptr(dX), lddx,
                                         pa, pb, 1 if accumulate else 0, _stream_ptr(stream)))
+
+
+def marlaas_profile_enable(ctx, on):
+    _check(ctx, load().marlaas_profile_enable(ctx.handle, 1 if on else 0))
+
+
+def marlaas_profile_read(ctx, kernel):
+    """(total milliseconds, launches) of one kernel family since profiling was enabled."""
+    ms, cnt = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(ctx, load().marlaas_profile_read(ctx.handle, int(kernel), ctypes.byref(ms), ctypes.byref(cnt)))
+    return ms.value, cnt.value

@@ -26,6 +26,9 @@ struct marlaas_ctx {
   size_t ws_bytes = 0;
   std::string err;
   std::list<TableSlot> tables;   // most recently used first
+  bool profile = false;
+  struct Span { int kernel; hipEvent_t beg, end; };
+  std::vector<Span> spans;       // event pairs recorded while profiling is on
 };
 
 struct marlaas_segmap {
@@ -62,6 +65,22 @@ static int fail(marlaas_ctx* ctx, int status, const char* fmt, ...) {
       return fail((ctx), MARLAAS_EHIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
   } while (0)
 
+// While profiling is on, every kernel launch of a pass is bracketed by a pair of
+// events on the caller's stream so that its duration can be read back.
+struct ProfSpan {
+  marlaas_ctx* ctx; hipStream_t st; hipEvent_t end = nullptr;
+  ProfSpan(marlaas_ctx* c, int kernel, hipStream_t s) : ctx(c), st(s) {
+    if (!c->profile) return;
+    hipEvent_t b = nullptr;
+    if (hipEventCreate(&b) != hipSuccess) return;
+    if (hipEventCreate(&end) != hipSuccess) { (void)hipEventDestroy(b); end = nullptr; return; }
+    (void)hipEventRecord(b, st);
+    c->spans.push_back({kernel, b, end});
+  }
+  ~ProfSpan() { if (end) (void)hipEventRecord(end, st); }
+};
+#define PROFILED(ctx, kernel, st, expr) do { ProfSpan _span((ctx), (kernel), (st)); HIP_TRY((ctx), (expr)); } while (0)
+
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
@@ -94,9 +113,41 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   return MARLAAS_OK;
 }
 
+static void drop_spans(marlaas_ctx* ctx) {
+  for (auto& sp : ctx->spans) { (void)hipEventDestroy(sp.beg); (void)hipEventDestroy(sp.end); }
+  ctx->spans.clear();
+}
+
+extern "C" int marlaas_profile_enable(marlaas_ctx* ctx, int on) {
+  if (!ctx) return MARLAAS_EINVAL;
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  drop_spans(ctx);
+  ctx->profile = on != 0;
+  return MARLAAS_OK;
+}
+
+extern "C" int marlaas_profile_read(marlaas_ctx* ctx, int kernel, double* total_ms, int64_t* launches) {
+  if (!ctx || !total_ms || !launches) return MARLAAS_EINVAL;
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  double sum = 0.0;
+  int64_t cnt = 0;
+  for (auto& sp : ctx->spans) {
+    if (sp.kernel != kernel) continue;
+    HIP_TRY(ctx, hipEventSynchronize(sp.end));
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, sp.beg, sp.end));
+    sum += ms;
+    ++cnt;
+  }
+  *total_ms = sum;
+  *launches = cnt;
+  return MARLAAS_OK;
+}
+
 extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
   if (!ctx) return;
   (void)hipSetDevice(ctx->device);
+  drop_spans(ctx);
   for (auto& s : ctx->tables) (void)hipFree(s.dev);
   delete ctx;
 }
@@ -333,16 +384,16 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
   const int out_f32 = d->out_dtype == MARLAAS_F32;
   if (d->in_dtype == MARLAAS_BF16) {
     if (lora)
-      HIP_TRY(ctx, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
                                       map->max_seg, table, 0, form, u, rs, map->T_lora, st));
-    HIP_TRY(ctx, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
+    PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, st));
   } else {
     if (lora)
-      HIP_TRY(ctx, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
                                      table, 0, form, u, rs, map->T_lora, st));
-    HIP_TRY(ctx, launch_gemm_f32((const float*)d->x, d->ldx, (const float*)d->W, d->ldw, form, d->T, d->d_in,
+    PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_f32((const float*)d->x, d->ldx, (const float*)d->W, d->ldw, form, d->T, d->d_in,
                                  d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                  rs, y, ldy, out_f32, st));
   }
@@ -407,38 +458,38 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     const bf16_t* x = (const bf16_t*)d->x;
     const bf16_t* dy = (const bf16_t*)dY;
     if (need_u)
-      HIP_TRY(ctx, launch_shrink_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, 0, fform, u, rs, map->T_lora, st));
     if (lora && (dX || want_grads))
-      HIP_TRY(ctx, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, 1, bform, v, rs, map->T_lora, st));
     if (dX && d->T > 0)
-      HIP_TRY(ctx, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
+      PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                     out_f32, st));
     if (want_grads && d->n_adapters > 0) {
-      HIP_TRY(ctx, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+      PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, p.part_bytes, st));
-      HIP_TRY(ctx, launch_reduce_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
+      PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 0, da_form, v, rs, accumulate, part, p.part_bytes, st));
     }
   } else {
     const float* x = (const float*)d->x;
     const float* dy = (const float*)dY;
     if (need_u)
-      HIP_TRY(ctx, launch_shrink_f32(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, table, 0, fform,
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, table, 0, fform,
                                      u, rs, map->T_lora, st));
     if (lora && (dX || want_grads))
-      HIP_TRY(ctx, launch_shrink_f32(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, bform,
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, bform,
                                      v, rs, map->T_lora, st));
     if (dX && d->T > 0)
-      HIP_TRY(ctx, launch_gemm_f32(dy, lddy, (const float*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
+      PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_f32(dy, lddy, (const float*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                    map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                    out_f32, st));
     if (want_grads && d->n_adapters > 0) {
-      HIP_TRY(ctx, launch_reduce_f32(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, table, grads, 1,
+      PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_f32(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, table, grads, 1,
                                      db_form, u, rs, accumulate, st));
-      HIP_TRY(ctx, launch_reduce_f32(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, table, grads, 0,
+      PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_f32(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, table, grads, 0,
                                      da_form, v, rs, accumulate, st));
     }
   }

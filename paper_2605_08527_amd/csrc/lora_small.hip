@@ -113,6 +113,12 @@ __global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
       }
 }
 
+// plain fill (a kernel, not a memset node, so that callers may capture the pass in a HIP graph)
+__global__ __launch_bounds__(256) void zero_f32_kernel(float4* p, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, int which, int lora_form, float* u,
@@ -133,8 +139,8 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   ksplit = (int)((C + a.kchunk - 1) / a.kchunk);
   a.ksplit = ksplit;
   if (ksplit > 1) {
-    hipError_t e = hipMemsetAsync(u, 0, (size_t)T_lora * r_stride * sizeof(float), stream);
-    if (e != hipSuccess) return e;
+    const int64_t n4 = T_lora * r_stride / 4;   // r_stride is a multiple of 16
+    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, (float4*)u, n4);
   }
   const size_t lds = (size_t)r_stride * SH_PITCH;   // r_stride >= every r_pad
   auto kern = lora_form == FORM_NT ? shrink_bf16_kernel<FORM_NT> : shrink_bf16_kernel<FORM_NN>;
