@@ -11,15 +11,17 @@
 // tile may straddle any number of segments.
 //
 // Tile: 256 x 256 x 64 per workgroup of 8 waves (2 x 4), each wave 128 x 64 as
-// 4 x 2 MFMA 32x32x16 accumulators; operands staged through LDS in 16-byte
-// units with an XOR swizzle, double-buffered, next tile prefetched in registers.
+// 4 x 2 MFMA 32x32x16 accumulators.  Operand tiles go from global memory
+// straight into LDS (16 bytes per lane, no register staging), two stages, one
+// barrier per k-tile; 16-byte units are XOR-swizzled so that both the DMA
+// writes and the fragment reads are bank-conflict free.
 #include "common.h"
 
 namespace marlaas {
 
 static constexpr int BM = 256, BN = 256, BK = 64;
 static constexpr int GEMM_THREADS = 512;
-static constexpr int STAGE_BYTES = BM * BK * 2;        // 32 KB per operand per stage
+static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB per operand per stage
 static constexpr int GEMM_LDS = 4 * STAGE_BYTES + BM * 4;  // 2 stages x 2 operands + token ids
 
 struct GemmArgs {
@@ -36,6 +38,9 @@ struct GemmArgs {
   int tiles_m, tiles_n;
 };
 
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
 // LDS byte offset of 16-byte unit `unit` of row `row` in a [rows][64] bf16 tile.
 __device__ __forceinline__ int swz_rowk(int row, int unit) {
   return row * 128 + ((unit ^ ((row >> 1) & 7)) << 4);
@@ -45,20 +50,50 @@ __device__ __forceinline__ int swz_kn(int k, int unit) {
   return k * 512 + ((unit ^ ((k & 3) << 2)) << 4);
 }
 
-__device__ __forceinline__ bf16x8 lds_read_frag(const char* base, int off) {
-  return *(const bf16x8*)(base + off);
-}
-
-// 8 consecutive contraction values of column n from a [k][n] tile: two
+// 8 consecutive contraction values of one column from a [k][n] tile: two
 // transposing 64-bit reads (each returns 4 consecutive k for this lane's column).
-__device__ __forceinline__ bf16x8 lds_read_frag_tr(const char* base, int off0, int off1) {
+__device__ __forceinline__ bf16x8 lds_read_frag_tr(const char* p0, const char* p1) {
   typedef short4v __attribute__((address_space(3))) * lds_s4;
-  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(base + off0));
-  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(base + off1));
+  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p0);
+  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p1);
   union { short s[8]; bf16x8 v; } r;
   r.s[0] = a[0]; r.s[1] = a[1]; r.s[2] = a[2]; r.s[3] = a[3];
   r.s[4] = b[0]; r.s[5] = b[1]; r.s[6] = b[2]; r.s[7] = b[3];
   return r.v;
+}
+
+__device__ __forceinline__ uint4 pack8(const bf16_t* o) {
+  uint4 pk;
+  pk.x = o[0] | ((uint32_t)o[1] << 16); pk.y = o[2] | ((uint32_t)o[3] << 16);
+  pk.z = o[4] | ((uint32_t)o[5] << 16); pk.w = o[6] | ((uint32_t)o[7] << 16);
+  return pk;
+}
+
+// One 16-wide contraction step of the wave's 128 x 64 block from LDS stage (as, bs).
+template <int FORM>
+__device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks, int a_off_row,
+                                          int a_swz, int fk, int b_off_row, int b_swz,
+                                          const int (&btr)[2], f32x16 (&acc)[4][2]) {
+  bf16x8 af[4], bfr[2];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+    af[mt] = *(const bf16x8*)(as + a_off_row + mt * (32 * 128) + (((ks * 2 + fk) ^ a_swz) << 4));
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    if (FORM == FORM_NT) {
+      bfr[nt] = *(const bf16x8*)(bs + b_off_row + nt * (32 * 128) + (((ks * 2 + fk) ^ b_swz) << 4));
+    } else {
+      // btr[nt]: byte offset of this lane's (k = kb, column) element for ks = 0; a k-step moves
+      // 16 rows down (the swizzle only depends on k & 3, unchanged by steps of 4)
+      const char* p = bs + btr[nt] + ks * (16 * 512);
+      bfr[nt] = lds_read_frag_tr(p, p + 4 * 512);
+    }
+  }
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
 }
 
 template <int FORM, bool OUT_F32>
@@ -103,107 +138,139 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   }
   __syncthreads();
 
-  // ---- loader geometry
-  const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
-  const int lr = tid >> 3;       // 0..63
-  const bf16_t* a_ptr[4];
-  for (int i = 0; i < 4; ++i) {
-    int32_t tok = tok_s[lr + 64 * i];
-    a_ptr[i] = a.Aop + (int64_t)(tok < 0 ? 0 : tok) * a.lda + lc * 8;
+  // ---- DMA geometry.  One wave instruction moves 64 x 16 B = 1 KB into
+  // consecutive LDS bytes.  Row-k tiles: 8 rows of 128 B per instruction, lane
+  // l writes unit (l & 7) of row (l >> 3) and therefore fetches the global
+  // unit (l & 7) ^ swizzle(row).  Each wave owns 4 instructions per operand.
+  const bf16_t* a_src[4];
+  const bf16_t* b_src[4];
+  int64_t b_step;          // elements to advance b_src per k-tile
+  for (int j = 0; j < 4; ++j) {
+    const int row = wave * 32 + j * 8 + (lane >> 3);
+    const int unit = (lane & 7) ^ ((row >> 1) & 7);
+    const int32_t tok = tok_s[row];
+    a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + unit * 8;
   }
-  const bf16_t* b_ptr[4];
-  bool b_ok[4];
-  const int ncu = tid & 31;      // 16-byte unit along n (k-n tiles)
-  const int nkr = tid >> 5;      // 0..15
   if (FORM == FORM_NT) {
-    for (int i = 0; i < 4; ++i) {
-      int64_t n = n0 + lr + 64 * i;
-      b_ok[i] = n < a.Nout;
-      b_ptr[i] = a.Bop + (b_ok[i] ? n : 0) * a.ldb + lc * 8;
+    for (int j = 0; j < 4; ++j) {
+      const int row = wave * 32 + j * 8 + (lane >> 3);
+      const int unit = (lane & 7) ^ ((row >> 1) & 7);
+      int64_t n = n0 + row;
+      if (n >= a.Nout) n = a.Nout - 1;           // clamped columns are never stored
+      b_src[j] = a.Bop + n * a.ldb + unit * 8;
     }
+    b_step = BK;
   } else {
-    for (int i = 0; i < 4; ++i) {
-      b_ok[i] = (n0 + ncu * 8) < a.Nout;
-      b_ptr[i] = a.Bop + (int64_t)(nkr + 16 * i) * a.ldb + (b_ok[i] ? n0 + ncu * 8 : 0);
+    // k-n tiles: 2 k-rows of 512 B per instruction, lane l writes unit (l & 31) of row (l >> 5)
+    for (int j = 0; j < 4; ++j) {
+      const int k = wave * 8 + j * 2 + (lane >> 5);
+      const int unit = (lane & 31) ^ ((k & 3) << 2);
+      int64_t n = n0 + unit * 8;
+      if (n >= a.Nout) n = a.Nout - 8;
+      b_src[j] = a.Bop + (int64_t)k * a.ldb + n;
     }
+    b_step = (int64_t)BK * a.ldb;
   }
-
-  f32x16 acc[4][2];
-  for (int i = 0; i < 4; ++i)
-    for (int j = 0; j < 2; ++j)
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  uint4 ra[4], rb[4];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-
-  auto load_tile = [&](int64_t k0) {
-    const bool ka = (k0 + lc * 8) < a.Kc;
-    for (int i = 0; i < 4; ++i) ra[i] = ka ? *(const uint4*)(a_ptr[i] + k0) : zero4;
-    if (FORM == FORM_NT) {
-      for (int i = 0; i < 4; ++i) rb[i] = (ka && b_ok[i]) ? *(const uint4*)(b_ptr[i] + k0) : zero4;
-    } else {
-      for (int i = 0; i < 4; ++i) {
-        const bool kb = (k0 + nkr + 16 * i) < a.Kc;
-        rb[i] = (kb && b_ok[i]) ? *(const uint4*)(b_ptr[i] + k0 * a.ldb) : zero4;
-      }
-    }
-  };
-  auto store_tile = [&](int stage) {
-    char* as = As + stage * STAGE_BYTES;
-    char* bs = Bs + stage * STAGE_BYTES;
-    for (int i = 0; i < 4; ++i) *(uint4*)(as + swz_rowk(lr + 64 * i, lc)) = ra[i];
-    if (FORM == FORM_NT) {
-      for (int i = 0; i < 4; ++i) *(uint4*)(bs + swz_rowk(lr + 64 * i, lc)) = rb[i];
-    } else {
-      for (int i = 0; i < 4; ++i) *(uint4*)(bs + swz_kn(nkr + 16 * i, ncu)) = rb[i];
-    }
-  };
+  const int dma_off = wave * 4096;   // this wave's first KB inside an operand stage
 
   // ---- fragment geometry
   const int frow = lane & 31;          // row inside a 32-row MFMA tile
   const int fk = lane >> 5;            // which 8-wide half of the 16-wide k step
-  const int g16 = lane >> 4, i16 = lane & 15;
+  const int a_row = wm * 128 + frow;
+  const int a_off_row = a_row * 128;
+  const int a_swz = (a_row >> 1) & 7;  // rows 32 apart share the swizzle
+  const int b_row = wn * 64 + frow;
+  const int b_off_row = b_row * 128;
+  const int b_swz = (b_row >> 1) & 7;
+  int btr[2];
+  {
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int kb = (g16 >> 1) * 8 + (i16 >> 2);
+    for (int nt = 0; nt < 2; ++nt) {
+      const int ncol = wn * 64 + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
+      btr[nt] = swz_kn(kb, ncol >> 3) + (ncol & 7) * 2;
+    }
+  }
 
-  auto mma_steps = [&](int stage, int ksteps) {
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int64_t nk_full = a.Kc / BK;
+
+  // ---- main loop over full k-tiles: DMA of tile kt+1 overlaps the MFMAs of tile kt
+  if (nk_full > 0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      __builtin_amdgcn_global_load_lds((gptr_t)a_src[j], (lptr_t)(As + dma_off + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)b_src[j], (lptr_t)(Bs + dma_off + j * 1024), 16, 0, 0);
+      a_src[j] += BK; b_src[j] += b_step;
+    }
+  }
+  for (int64_t kt = 0; kt < nk_full; ++kt) {
+    const int stage = (int)(kt & 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of tile kt has landed
+    __syncthreads();                      // everyone's part has; everyone is done with tile kt-1
+    if (kt + 1 < nk_full) {
+      char* an = As + (stage ^ 1) * STAGE_BYTES + dma_off;
+      char* bn = Bs + (stage ^ 1) * STAGE_BYTES + dma_off;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        __builtin_amdgcn_global_load_lds((gptr_t)a_src[j], (lptr_t)(an + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t)b_src[j], (lptr_t)(bn + j * 1024), 16, 0, 0);
+        a_src[j] += BK; b_src[j] += b_step;
+      }
+    }
     const char* as = As + stage * STAGE_BYTES;
     const char* bs = Bs + stage * STAGE_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks < ksteps) {
-        bf16x8 af[4], bfr[2];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-          af[mt] = lds_read_frag(as, swz_rowk(wm * 128 + mt * 32 + frow, ks * 2 + fk));
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          if (FORM == FORM_NT) {
-            bfr[nt] = lds_read_frag(bs, swz_rowk(wn * 64 + nt * 32 + frow, ks * 2 + fk));
-          } else {
-            const int ncol = wn * 64 + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
-            const int kb = ks * 16 + (g16 >> 1) * 8 + (i16 >> 2);
-            bfr[nt] = lds_read_frag_tr(bs, swz_kn(kb, ncol >> 3) + (ncol & 7) * 2,
-                                       swz_kn(kb + 4, ncol >> 3) + (ncol & 7) * 2);
-          }
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+    for (int ks = 0; ks < 4; ++ks)
+      mma_kstep<FORM>(as, bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
+  }
+  __syncthreads();   // all reads of the last tile are done; stage 0 is reused below
+
+  // loader geometry of the register-staged tiles (k tail and LoRA steps)
+  const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
+  const int lr = tid >> 3;       // 0..63
+  const int ncu = tid & 31;      // 16-byte unit along n (k-n tiles)
+  const int nkr = tid >> 5;      // 0..15
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+  // ---- k tail (Kc not a multiple of 64): one masked tile through registers
+  if (nk_full * BK < a.Kc) {
+    const int64_t k0 = nk_full * BK;
+    const bool ka = (k0 + lc * 8) < a.Kc;
+    for (int i = 0; i < 4; ++i) {
+      const int row = lr + 64 * i;
+      const int32_t tok = tok_s[row];
+      uint4 v = zero4;
+      if (ka && tok >= 0) v = *(const uint4*)(a.Aop + (int64_t)tok * a.lda + k0 + lc * 8);
+      *(uint4*)(As + swz_rowk(row, lc)) = v;
+    }
+    if (FORM == FORM_NT) {
+      for (int i = 0; i < 4; ++i) {
+        const int row = lr + 64 * i;
+        uint4 v = zero4;
+        if (ka && (n0 + row) < a.Nout) v = *(const uint4*)(a.Bop + (n0 + row) * a.ldb + k0 + lc * 8);
+        *(uint4*)(Bs + swz_rowk(row, lc)) = v;
+      }
+    } else {
+      for (int i = 0; i < 4; ++i) {
+        const int k = nkr + 16 * i;
+        uint4 v = zero4;
+        if ((k0 + k) < a.Kc && (n0 + ncu * 8) < a.Nout)
+          v = *(const uint4*)(a.Bop + (k0 + k) * a.ldb + n0 + ncu * 8);
+        *(uint4*)(Bs + swz_kn(k, ncu)) = v;
       }
     }
-  };
-
-  // ---- main loop over the contraction dimension
-  const int64_t ktiles = (a.Kc + BK - 1) / BK;
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-  for (int64_t kt = 0; kt < ktiles; ++kt) {
-    const int stage = (int)(kt & 1);
-    if (kt + 1 < ktiles) load_tile((kt + 1) * BK);
-    mma_steps(stage, 4);
-    if (kt + 1 < ktiles) store_tile(stage ^ 1);
+    __syncthreads();
+    const int ksteps = (int)((a.Kc - k0 + 15) / 16);
+    for (int ks = 0; ks < ksteps; ++ks)
+      mma_kstep<FORM>(As, Bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
     __syncthreads();
   }
 
@@ -239,8 +306,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
                   bf16_t h = float_to_bf16_bits(f[j]);
                   o[j] = second ? float_to_bf16_bits(f[j] - bf16_bits_to_float(h)) : h;
                 }
-                pk.x = o[0] | ((uint32_t)o[1] << 16); pk.y = o[2] | ((uint32_t)o[3] << 16);
-                pk.z = o[4] | ((uint32_t)o[5] << 16); pk.w = o[6] | ((uint32_t)o[7] << 16);
+                pk = pack8(o);
               }
               *(uint4*)(As + swz_rowk(lr + 64 * i, lc)) = pk;
             }
@@ -256,8 +322,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
                   } else {
                     bf16_t o[8];
                     for (int j = 0; j < 8; ++j) o[j] = (q0 + j < r) ? lp[j] : (bf16_t)0;
-                    pk.x = o[0] | ((uint32_t)o[1] << 16); pk.y = o[2] | ((uint32_t)o[3] << 16);
-                    pk.z = o[4] | ((uint32_t)o[5] << 16); pk.w = o[6] | ((uint32_t)o[7] << 16);
+                    pk = pack8(o);
                   }
                 }
                 *(uint4*)(Bs + swz_rowk(lr + 64 * i, lc)) = pk;
@@ -274,7 +339,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
             }
             __syncthreads();
             const int left = kext - kc;
-            mma_steps(0, left >= BK ? 4 : left / 16);
+            const int ksteps = left >= BK ? 4 : left / 16;
+            for (int ks = 0; ks < ksteps; ++ks)
+              mma_kstep<FORM>(As, Bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
             __syncthreads();
           }
         }
