@@ -10,19 +10,26 @@
 // tile that belong to another adapter are fed zeros for the extra steps, so a
 // tile may straddle any number of segments.
 //
-// Tile: 256 x 256 x 64 per workgroup of 8 waves (2 x 4), each wave 128 x 64 as
-// 4 x 2 MFMA 32x32x16 accumulators.  Operand tiles go from global memory
-// straight into LDS (16 bytes per lane, no register staging), two stages, one
-// barrier per k-tile; 16-byte units are XOR-swizzled so that both the DMA
-// writes and the fragment reads are bank-conflict free.
+// Tile: 256 x 256 per workgroup of 8 waves (2 x 4), each wave 128 x 64 as
+// 4 x 2 MFMA 32x32x16 accumulators.  The contraction runs in sub-tiles of 32
+// that go from global memory straight into LDS (16 bytes per lane, no register
+// staging) through a ring of four 32 KB slots: a sub-tile is requested three
+// steps before it is used, so HBM latency is covered, and there is one barrier
+// per sub-tile, placed between the two MFMA groups of a step so that the first
+// fragment reads of the next sub-tile overlap the second group.  16-byte units
+// are XOR-swizzled so that DMA writes and fragment reads are bank-conflict free.
 #include "common.h"
 
 namespace marlaas {
 
 static constexpr int BM = 256, BN = 256, BK = 64;
 static constexpr int GEMM_THREADS = 512;
-static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB per operand per stage
-static constexpr int GEMM_LDS = 4 * STAGE_BYTES + BM * 4;  // 2 stages x 2 operands + token ids
+static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB: one 64-wide operand tile (tail / LoRA steps)
+static constexpr int SUBK = 32;                            // contraction values per ring slot
+static constexpr int SLOT_BYTES = 2 * BM * SUBK * 2;       // 32 KB: A part then B part
+static constexpr int SLOT_B_OFF = BM * SUBK * 2;
+static constexpr int RING_SLOTS = 4;
+static constexpr int GEMM_LDS = RING_SLOTS * SLOT_BYTES + BM * 4;  // ring + token ids
 
 struct GemmArgs {
   const bf16_t* Aop; int64_t lda;
@@ -99,9 +106,7 @@ __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks
 template <int FORM, bool OUT_F32>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* As = smem;                       // [2][STAGE_BYTES]
-  char* Bs = smem + 2 * STAGE_BYTES;     // [2][STAGE_BYTES]
-  int32_t* tok_s = (int32_t*)(smem + 4 * STAGE_BYTES);
+  int32_t* tok_s = (int32_t*)(smem + RING_SLOTS * SLOT_BYTES);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -139,49 +144,57 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   __syncthreads();
 
   // ---- DMA geometry.  One wave instruction moves 64 x 16 B = 1 KB into
-  // consecutive LDS bytes.  Row-k tiles: 8 rows of 128 B per instruction, lane
-  // l writes unit (l & 7) of row (l >> 3) and therefore fetches the global
-  // unit (l & 7) ^ swizzle(row).  Each wave owns 4 instructions per operand.
-  const bf16_t* a_src[4];
-  const bf16_t* b_src[4];
-  int64_t b_step;          // elements to advance b_src per k-tile
-  for (int j = 0; j < 4; ++j) {
-    const int row = wave * 32 + j * 8 + (lane >> 3);
-    const int unit = (lane & 7) ^ ((row >> 1) & 7);
+  // consecutive LDS bytes.  Row-k sub-tiles ([256][32] bf16, 64 B per row): 16
+  // rows per instruction, lane l writes unit (l & 3) of row (l >> 2) and so
+  // fetches the global unit (l & 3) ^ swizzle(row).  k-n sub-tiles ([32][256],
+  // 512 B per row): 2 k-rows per instruction.  Each wave issues 2 instructions
+  // per operand per sub-tile.
+  const bf16_t* a_src[2];
+  const bf16_t* b_src[2];
+  int64_t b_step;          // elements to advance b_src per sub-tile
+  for (int j = 0; j < 2; ++j) {
+    const int row = wave * 32 + j * 16 + (lane >> 2);
+    const int unit = (lane & 3) ^ ((row >> 2) & 3);
     const int32_t tok = tok_s[row];
     a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + unit * 8;
   }
   if (FORM == FORM_NT) {
-    for (int j = 0; j < 4; ++j) {
-      const int row = wave * 32 + j * 8 + (lane >> 3);
-      const int unit = (lane & 7) ^ ((row >> 1) & 7);
+    for (int j = 0; j < 2; ++j) {
+      const int row = wave * 32 + j * 16 + (lane >> 2);
+      const int unit = (lane & 3) ^ ((row >> 2) & 3);
       int64_t n = n0 + row;
       if (n >= a.Nout) n = a.Nout - 1;           // clamped columns are never stored
       b_src[j] = a.Bop + n * a.ldb + unit * 8;
     }
-    b_step = BK;
+    b_step = SUBK;
   } else {
-    // k-n tiles: 2 k-rows of 512 B per instruction, lane l writes unit (l & 31) of row (l >> 5)
-    for (int j = 0; j < 4; ++j) {
-      const int k = wave * 8 + j * 2 + (lane >> 5);
+    for (int j = 0; j < 2; ++j) {
+      const int k = wave * 4 + j * 2 + (lane >> 5);
       const int unit = (lane & 31) ^ ((k & 3) << 2);
       int64_t n = n0 + unit * 8;
       if (n >= a.Nout) n = a.Nout - 8;
       b_src[j] = a.Bop + (int64_t)k * a.ldb + n;
     }
-    b_step = (int64_t)BK * a.ldb;
+    b_step = (int64_t)SUBK * a.ldb;
   }
-  const int dma_off = wave * 4096;   // this wave's first KB inside an operand stage
+  const int dma_off = wave * 2048;   // this wave's first KB inside an operand part of a slot
 
   // ---- fragment geometry
   const int frow = lane & 31;          // row inside a 32-row MFMA tile
   const int fk = lane >> 5;            // which 8-wide half of the 16-wide k step
   const int a_row = wm * 128 + frow;
+  const int b_row = wn * 64 + frow;
+  // 64-wide tiles (tail and LoRA steps)
   const int a_off_row = a_row * 128;
   const int a_swz = (a_row >> 1) & 7;  // rows 32 apart share the swizzle
-  const int b_row = wn * 64 + frow;
   const int b_off_row = b_row * 128;
   const int b_swz = (b_row >> 1) & 7;
+  // 32-wide ring sub-tiles: byte offsets of this lane's fragment for ks = 0, 1
+  int a_f32[2], b_f32[2];
+  for (int ks = 0; ks < 2; ++ks) {
+    a_f32[ks] = a_row * 64 + (((ks * 2 + fk) ^ ((a_row >> 2) & 3)) << 4);
+    b_f32[ks] = b_row * 64 + (((ks * 2 + fk) ^ ((b_row >> 2) & 3)) << 4);
+  }
   int btr[2];
   {
     const int g16 = lane >> 4, i16 = lane & 15;
@@ -200,38 +213,75 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int64_t nk_full = a.Kc / BK;
+  const int64_t nsub = a.Kc / SUBK;
 
-  // ---- main loop over full k-tiles: DMA of tile kt+1 overlaps the MFMAs of tile kt
-  if (nk_full > 0) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      __builtin_amdgcn_global_load_lds((gptr_t)a_src[j], (lptr_t)(As + dma_off + j * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t)b_src[j], (lptr_t)(Bs + dma_off + j * 1024), 16, 0, 0);
-      a_src[j] += BK; b_src[j] += b_step;
-    }
-  }
-  for (int64_t kt = 0; kt < nk_full; ++kt) {
-    const int stage = (int)(kt & 1);
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's part of tile kt has landed
-    __syncthreads();                      // everyone's part has; everyone is done with tile kt-1
-    if (kt + 1 < nk_full) {
-      char* an = As + (stage ^ 1) * STAGE_BYTES + dma_off;
-      char* bn = Bs + (stage ^ 1) * STAGE_BYTES + dma_off;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        __builtin_amdgcn_global_load_lds((gptr_t)a_src[j], (lptr_t)(an + j * 1024), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t)b_src[j], (lptr_t)(bn + j * 1024), 16, 0, 0);
-        a_src[j] += BK; b_src[j] += b_step;
+#define RING_DMA(slot_)                                                                                   \
+  do {                                                                                                    \
+    char* _sb = smem + (slot_) * SLOT_BYTES + dma_off;                                                    \
+    __builtin_amdgcn_global_load_lds((gptr_t)a_src[0], (lptr_t)(_sb), 16, 0, 0);                          \
+    __builtin_amdgcn_global_load_lds((gptr_t)a_src[1], (lptr_t)(_sb + 1024), 16, 0, 0);                   \
+    __builtin_amdgcn_global_load_lds((gptr_t)b_src[0], (lptr_t)(_sb + SLOT_B_OFF), 16, 0, 0);             \
+    __builtin_amdgcn_global_load_lds((gptr_t)b_src[1], (lptr_t)(_sb + SLOT_B_OFF + 1024), 16, 0, 0);      \
+    a_src[0] += SUBK; a_src[1] += SUBK; b_src[0] += b_step; b_src[1] += b_step;                           \
+  } while (0)
+
+#define RING_READ(slot_, ks_, af_, bf_)                                                                   \
+  do {                                                                                                    \
+    const char* _as = smem + (slot_) * SLOT_BYTES;                                                        \
+    const char* _bs = _as + SLOT_B_OFF;                                                                   \
+    _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                      \
+      af_[mt] = *(const bf16x8*)(_as + a_f32[ks_] + mt * (32 * 64));                                      \
+    _Pragma("unroll") for (int nt = 0; nt < 2; ++nt) {                                                    \
+      if (FORM == FORM_NT) {                                                                              \
+        bf_[nt] = *(const bf16x8*)(_bs + b_f32[ks_] + nt * (32 * 64));                                    \
+      } else {                                                                                            \
+        const char* _p = _bs + btr[nt] + (ks_) * (16 * 512);                                              \
+        bf_[nt] = lds_read_frag_tr(_p, _p + 4 * 512);                                                     \
+      }                                                                                                   \
+    }                                                                                                     \
+  } while (0)
+
+#define RING_MMA(af_, bf_)                                                                                \
+  do {                                                                                                    \
+    _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                      \
+      _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                    \
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[mt], bf_[nt], acc[mt][nt], 0, 0, 0);    \
+  } while (0)
+
+// raw barrier: LDS traffic of this wave is complete, DMA traffic is tracked by hand with vmcnt
+#define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+
+  // ---- main loop over full sub-tiles
+  if (nsub > 0) {
+    bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
+    RING_DMA(0);
+    if (nsub > 1) RING_DMA(1);
+    if (nsub > 2) RING_DMA(2);
+    if (nsub > 2) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8): sub-tile 0 landed
+    else if (nsub > 1) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+    RING_BARRIER();
+    RING_READ(0, 0, fa0, fb0);
+    for (int64_t h = 0; h < nsub; ++h) {
+      const int slot = (int)(h & 3);
+      RING_READ(slot, 1, fa1, fb1);
+      // slot (h + 3) & 3 held sub-tile h - 1: every wave finished reading it before the barrier of step h - 1
+      if (h + 3 < nsub) RING_DMA((int)((h + 3) & 3));
+      RING_MMA(fa0, fb0);
+      if (h + 1 < nsub) {
+        // sub-tile h + 1 must have landed; h + 2 and h + 3 may still be in flight
+        if (h + 3 < nsub) __builtin_amdgcn_s_waitcnt(0x0F78);
+        else if (h + 2 < nsub) __builtin_amdgcn_s_waitcnt(0x0F74);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        RING_BARRIER();
+        RING_READ((int)((h + 1) & 3), 0, fa0, fb0);
       }
+      RING_MMA(fa1, fb1);
     }
-    const char* as = As + stage * STAGE_BYTES;
-    const char* bs = Bs + stage * STAGE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      mma_kstep<FORM>(as, bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
   }
-  __syncthreads();   // all reads of the last tile are done; stage 0 is reused below
+  __syncthreads();   // all reads of the last sub-tile are done; the ring is reused below
+  char* As = smem;                 // one 64-wide A tile
+  char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile
 
   // loader geometry of the register-staged tiles (k tail and LoRA steps)
   const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
@@ -240,9 +290,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int nkr = tid >> 5;      // 0..15
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
-  // ---- k tail (Kc not a multiple of 64): one masked tile through registers
-  if (nk_full * BK < a.Kc) {
-    const int64_t k0 = nk_full * BK;
+  // ---- k tail (Kc not a multiple of 32): one masked tile through registers
+  if (nsub * SUBK < a.Kc) {
+    const int64_t k0 = nsub * SUBK;
     const bool ka = (k0 + lc * 8) < a.Kc;
     for (int i = 0; i < 4; ++i) {
       const int row = lr + 64 * i;
