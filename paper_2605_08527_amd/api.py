@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmarlaas_lora.so")
+LIB_PATH = os.environ.get("MARLAAS_LORA_LIB", os.path.join(_HERE, "libmarlaas_lora.so"))
 
 MARLAAS_BF16, MARLAAS_F32 = 0, 1
 MARLAAS_LAYOUT_MATH, MARLAAS_LAYOUT_TORCH = 0, 1

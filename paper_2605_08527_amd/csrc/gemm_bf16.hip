@@ -10,8 +10,9 @@
 // tile that belong to another adapter are fed zeros for the extra steps, so a
 // tile may straddle any number of segments.
 //
-// Tile: 256 x 256 per workgroup of 8 waves (2 x 4), each wave 128 x 64 as
-// 4 x 2 MFMA 32x32x16 accumulators.  The contraction runs in sub-tiles of 32
+// Tile: 256 x 256 per workgroup of 4 waves (2 x 2), each wave 128 x 128 as
+// 4 x 4 MFMA 32x32x16 accumulators (a large wave tile keeps LDS read traffic,
+// which competes with the DMA writes for LDS bandwidth, under the MFMA rate).  The contraction runs in sub-tiles of 32
 // that go from global memory straight into LDS (16 bytes per lane, no register
 // staging) through a ring of four 32 KB slots: a sub-tile is requested three
 // steps before it is used, so HBM latency is covered, and there is one barrier
@@ -23,7 +24,15 @@
 namespace marlaas {
 
 static constexpr int BM = 256, BN = 256, BK = 64;
-static constexpr int GEMM_THREADS = 512;
+static constexpr int WAVES_M = 2, WAVES_N = 2;             // wave grid inside the tile
+static constexpr int NWAVES = WAVES_M * WAVES_N;
+static constexpr int GEMM_THREADS = 64 * NWAVES;
+static constexpr int MT = BM / WAVES_M / 32, NT = BN / WAVES_N / 32;   // 32x32 MFMA tiles per wave
+static constexpr int DPW = 16 / NWAVES;                    // DMA instructions per wave, operand and sub-tile
+static constexpr int LROWS = GEMM_THREADS / 8;             // rows per pass of the register-staged loaders
+static constexpr int LPASS = BM / LROWS;
+static constexpr int LKROWS = GEMM_THREADS / 32;           // k-rows per pass (k-n tiles)
+static constexpr int LKPASS = BK / LKROWS;
 static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB: one 64-wide operand tile (tail / LoRA steps)
 static constexpr int SUBK = 32;                            // contraction values per ring slot
 static constexpr int SLOT_BYTES = 2 * BM * SUBK * 2;       // 32 KB: A part then B part
@@ -45,6 +54,12 @@ struct GemmArgs {
   int tiles_m, tiles_n;
 };
 
+#ifndef EXP_NODMA
+#define EXP_NODMA 0
+#endif
+#ifndef EXP_NOADV
+#define EXP_NOADV 0
+#endif
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -80,13 +95,13 @@ __device__ __forceinline__ uint4 pack8(const bf16_t* o) {
 template <int FORM>
 __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks, int a_off_row,
                                           int a_swz, int fk, int b_off_row, int b_swz,
-                                          const int (&btr)[2], f32x16 (&acc)[4][2]) {
-  bf16x8 af[4], bfr[2];
+                                          const int (&btr)[NT], f32x16 (&acc)[MT][NT]) {
+  bf16x8 af[MT], bfr[NT];
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
     af[mt] = *(const bf16x8*)(as + a_off_row + mt * (32 * 128) + (((ks * 2 + fk) ^ a_swz) << 4));
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
+  for (int nt = 0; nt < NT; ++nt) {
     if (FORM == FORM_NT) {
       bfr[nt] = *(const bf16x8*)(bs + b_off_row + nt * (32 * 128) + (((ks * 2 + fk) ^ b_swz) << 4));
     } else {
@@ -97,9 +112,9 @@ __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks
     }
   }
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
+    for (int nt = 0; nt < NT; ++nt)
       acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
 }
 
@@ -111,7 +126,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
   // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
   // tiles; inside a run, groups of 8 row tiles share their column tiles.
@@ -135,11 +150,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int64_t m0 = (int64_t)tm * BM;
   const int64_t n0 = (int64_t)tn * BN;
 
-  if (tid < BM) {
-    int64_t m = m0 + tid;
+  for (int i = tid; i < BM; i += GEMM_THREADS) {
+    int64_t m = m0 + i;
     int32_t tok = -1;
     if (m < a.T) tok = a.perm ? a.perm[m] : (int32_t)m;
-    tok_s[tid] = tok;
+    tok_s[i] = tok;
   }
   __syncthreads();
 
@@ -149,18 +164,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   // fetches the global unit (l & 3) ^ swizzle(row).  k-n sub-tiles ([32][256],
   // 512 B per row): 2 k-rows per instruction.  Each wave issues 2 instructions
   // per operand per sub-tile.
-  const bf16_t* a_src[2];
-  const bf16_t* b_src[2];
+  const bf16_t* a_src[DPW];
+  const bf16_t* b_src[DPW];
   int64_t b_step;          // elements to advance b_src per sub-tile
-  for (int j = 0; j < 2; ++j) {
-    const int row = wave * 32 + j * 16 + (lane >> 2);
+  for (int j = 0; j < DPW; ++j) {
+    const int row = (wave * DPW + j) * 16 + (lane >> 2);
     const int unit = (lane & 3) ^ ((row >> 2) & 3);
     const int32_t tok = tok_s[row];
     a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + unit * 8;
   }
   if (FORM == FORM_NT) {
-    for (int j = 0; j < 2; ++j) {
-      const int row = wave * 32 + j * 16 + (lane >> 2);
+    for (int j = 0; j < DPW; ++j) {
+      const int row = (wave * DPW + j) * 16 + (lane >> 2);
       const int unit = (lane & 3) ^ ((row >> 2) & 3);
       int64_t n = n0 + row;
       if (n >= a.Nout) n = a.Nout - 1;           // clamped columns are never stored
@@ -168,8 +183,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     }
     b_step = SUBK;
   } else {
-    for (int j = 0; j < 2; ++j) {
-      const int k = wave * 4 + j * 2 + (lane >> 5);
+    for (int j = 0; j < DPW; ++j) {
+      const int k = (wave * DPW + j) * 2 + (lane >> 5);
       const int unit = (lane & 31) ^ ((k & 3) << 2);
       int64_t n = n0 + unit * 8;
       if (n >= a.Nout) n = a.Nout - 8;
@@ -177,13 +192,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     }
     b_step = (int64_t)SUBK * a.ldb;
   }
-  const int dma_off = wave * 2048;   // this wave's first KB inside an operand part of a slot
+  const int dma_off = wave * DPW * 1024;   // this wave's first KB inside an operand part of a slot
 
   // ---- fragment geometry
   const int frow = lane & 31;          // row inside a 32-row MFMA tile
   const int fk = lane >> 5;            // which 8-wide half of the 16-wide k step
-  const int a_row = wm * 128 + frow;
-  const int b_row = wn * 64 + frow;
+  const int a_row = wm * (MT * 32) + frow;
+  const int b_row = wn * (NT * 32) + frow;
   // 64-wide tiles (tail and LoRA steps)
   const int a_off_row = a_row * 128;
   const int a_swz = (a_row >> 1) & 7;  // rows 32 apart share the swizzle
@@ -195,88 +210,114 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     a_f32[ks] = a_row * 64 + (((ks * 2 + fk) ^ ((a_row >> 2) & 3)) << 4);
     b_f32[ks] = b_row * 64 + (((ks * 2 + fk) ^ ((b_row >> 2) & 3)) << 4);
   }
-  int btr[2];
+  int btr[NT];
   {
     const int g16 = lane >> 4, i16 = lane & 15;
     const int kb = (g16 >> 1) * 8 + (i16 >> 2);
-    for (int nt = 0; nt < 2; ++nt) {
-      const int ncol = wn * 64 + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
+    for (int nt = 0; nt < NT; ++nt) {
+      const int ncol = wn * (NT * 32) + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
       btr[nt] = swz_kn(kb, ncol >> 3) + (ncol & 7) * 2;
     }
   }
 
-  f32x16 acc[4][2];
+  f32x16 acc[MT][NT];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int64_t nsub = a.Kc / SUBK;
 
-#define RING_DMA(slot_)                                                                                   \
-  do {                                                                                                    \
-    char* _sb = smem + (slot_) * SLOT_BYTES + dma_off;                                                    \
-    __builtin_amdgcn_global_load_lds((gptr_t)a_src[0], (lptr_t)(_sb), 16, 0, 0);                          \
-    __builtin_amdgcn_global_load_lds((gptr_t)a_src[1], (lptr_t)(_sb + 1024), 16, 0, 0);                   \
-    __builtin_amdgcn_global_load_lds((gptr_t)b_src[0], (lptr_t)(_sb + SLOT_B_OFF), 16, 0, 0);             \
-    __builtin_amdgcn_global_load_lds((gptr_t)b_src[1], (lptr_t)(_sb + SLOT_B_OFF + 1024), 16, 0, 0);      \
-    a_src[0] += SUBK; a_src[1] += SUBK; b_src[0] += b_step; b_src[1] += b_step;                           \
-  } while (0)
+  static_assert(MT == 4 && NT == 4 && DPW == 4, "the interleaved schedule below is written for 4 x 4 MFMA tiles per wave");
 
-#define RING_READ(slot_, ks_, af_, bf_)                                                                   \
-  do {                                                                                                    \
-    const char* _as = smem + (slot_) * SLOT_BYTES;                                                        \
-    const char* _bs = _as + SLOT_B_OFF;                                                                   \
-    _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                      \
-      af_[mt] = *(const bf16x8*)(_as + a_f32[ks_] + mt * (32 * 64));                                      \
-    _Pragma("unroll") for (int nt = 0; nt < 2; ++nt) {                                                    \
-      if (FORM == FORM_NT) {                                                                              \
-        bf_[nt] = *(const bf16x8*)(_bs + b_f32[ks_] + nt * (32 * 64));                                    \
-      } else {                                                                                            \
-        const char* _p = _bs + btr[nt] + (ks_) * (16 * 512);                                              \
-        bf_[nt] = lds_read_frag_tr(_p, _p + 4 * 512);                                                     \
-      }                                                                                                   \
-    }                                                                                                     \
-  } while (0)
-
-#define RING_MMA(af_, bf_)                                                                                \
-  do {                                                                                                    \
-    _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                      \
-      _Pragma("unroll") for (int nt = 0; nt < 2; ++nt)                                                    \
-        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[mt], bf_[nt], acc[mt][nt], 0, 0, 0);    \
-  } while (0)
-
+// s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
+#define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 // raw barrier: LDS traffic of this wave is complete, DMA traffic is tracked by hand with vmcnt
 #define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
+// one DMA instruction: part j (0..3) of operand `isb_` (0 = A, 1 = B) of the sub-tile going to `slot_`
+#define RING_DMA1(slot_, isb_, j_)                                                                        \
+  do {                                                                                                    \
+    char* _sb = smem + (slot_) * SLOT_BYTES + dma_off + (j_) * 1024;                                      \
+    if (isb_) {                                                                                           \
+      if (!EXP_NODMA) __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)(_sb + SLOT_B_OFF), 16, 0, 0); \
+      if (!EXP_NOADV) b_src[j_] += b_step;                                                                \
+    } else {                                                                                              \
+      if (!EXP_NODMA) __builtin_amdgcn_global_load_lds((gptr_t)a_src[j_], (lptr_t)(_sb), 16, 0, 0);       \
+      if (!EXP_NOADV) a_src[j_] += SUBK;                                                                  \
+    }                                                                                                     \
+  } while (0)
+
+#define RING_DMA(slot_)                                                                                   \
+  do {                                                                                                    \
+    _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) RING_DMA1(slot_, 0, _j);                           \
+    _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) RING_DMA1(slot_, 1, _j);                           \
+  } while (0)
+
+// fragment i (0..3 = A rows, 4..7 = B columns) of k-step ks_ of the sub-tile in `slot_`
+#define RING_READ1(slot_, ks_, i_, af_, bf_)                                                              \
+  do {                                                                                                    \
+    const char* _as = smem + (slot_) * SLOT_BYTES;                                                        \
+    const char* _bs = _as + SLOT_B_OFF;                                                                   \
+    if ((i_) < 4) {                                                                                       \
+      af_[(i_) & 3] = *(const bf16x8*)(_as + a_f32[ks_] + ((i_) & 3) * (32 * 64));                        \
+    } else if (FORM == FORM_NT) {                                                                         \
+      bf_[(i_) & 3] = *(const bf16x8*)(_bs + b_f32[ks_] + ((i_) & 3) * (32 * 64));                        \
+    } else {                                                                                              \
+      const char* _p = _bs + btr[(i_) & 3] + (ks_) * (16 * 512);                                          \
+      bf_[(i_) & 3] = lds_read_frag_tr(_p, _p + 4 * 512);                                                 \
+    }                                                                                                     \
+  } while (0)
+
+// 16 MFMAs on (ua_, ub_) with, in their shadow, the 8 fragment reads of (ld_slot_, ld_ks_) into
+// (la_, lb_) and 4 DMA instructions; sched_barrier pins this order (one wave per SIMD: nothing
+// else hides the issue latency of LDS and DMA instructions).
+#define RING_PHASE(ua_, ub_, do_ld_, ld_slot_, ld_ks_, la_, lb_, do_dma_, dma_slot_, dma_isb_)            \
+  do {                                                                                                    \
+    _Pragma("unroll") for (int _i = 0; _i < 16; ++_i) {                                                   \
+      acc[_i >> 2][_i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_[_i >> 2], ub_[_i & 3],           \
+                                                                     acc[_i >> 2][_i & 3], 0, 0, 0);      \
+      if ((do_ld_) && _i < 8) RING_READ1(ld_slot_, ld_ks_, _i, la_, lb_);                                 \
+      if ((do_dma_) && _i >= 8 && _i < 12) RING_DMA1(dma_slot_, dma_isb_, _i - 8);                        \
+      __builtin_amdgcn_sched_barrier(0);                                                                  \
+    }                                                                                                     \
+  } while (0)
+
+// One sub-tile step h: phase A consumes k-step 0 (fa0, fb0) while loading k-step 1; then the
+// barrier that publishes sub-tile h + 1; phase B consumes k-step 1 while loading k-step 0 of h + 1.
+// dma_: request sub-tile h + 3 (its slot held h - 1, which every wave left before the barrier of
+// step h - 1).  wait_: DMA instructions of this wave that may still be in flight once h + 1 landed.
+#define RING_STEP(h_, dma_, wait_)                                                                        \
+  do {                                                                                                    \
+    const int _slot = (int)((h_) & 3), _nslot = (int)(((h_) + 1) & 3), _dslot = (int)(((h_) + 3) & 3);    \
+    RING_PHASE(fa0, fb0, 1, _slot, 1, fa1, fb1, dma_, _dslot, 0);                                         \
+    __builtin_amdgcn_s_waitcnt(VMCNT(wait_));                                                             \
+    RING_BARRIER();                                                                                       \
+    RING_PHASE(fa1, fb1, 1, _nslot, 0, fa0, fb0, dma_, _dslot, 1);                                        \
+  } while (0)
+
   // ---- main loop over full sub-tiles
   if (nsub > 0) {
-    bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
+    bf16x8 fa0[MT], fb0[NT], fa1[MT], fb1[NT];
     RING_DMA(0);
     if (nsub > 1) RING_DMA(1);
     if (nsub > 2) RING_DMA(2);
-    if (nsub > 2) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8): sub-tile 0 landed
-    else if (nsub > 1) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+    if (nsub > 2) __builtin_amdgcn_s_waitcnt(VMCNT(4 * DPW));        // sub-tile 0 landed, two in flight
+    else if (nsub > 1) __builtin_amdgcn_s_waitcnt(VMCNT(2 * DPW));
+    else __builtin_amdgcn_s_waitcnt(VMCNT(0));
     RING_BARRIER();
-    RING_READ(0, 0, fa0, fb0);
-    for (int64_t h = 0; h < nsub; ++h) {
-      const int slot = (int)(h & 3);
-      RING_READ(slot, 1, fa1, fb1);
-      // slot (h + 3) & 3 held sub-tile h - 1: every wave finished reading it before the barrier of step h - 1
-      if (h + 3 < nsub) RING_DMA((int)((h + 3) & 3));
-      RING_MMA(fa0, fb0);
-      if (h + 1 < nsub) {
-        // sub-tile h + 1 must have landed; h + 2 and h + 3 may still be in flight
-        if (h + 3 < nsub) __builtin_amdgcn_s_waitcnt(0x0F78);
-        else if (h + 2 < nsub) __builtin_amdgcn_s_waitcnt(0x0F74);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
-        RING_BARRIER();
-        RING_READ((int)((h + 1) & 3), 0, fa0, fb0);
-      }
-      RING_MMA(fa1, fb1);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) RING_READ1(0, 0, i, fa0, fb0);
+    int64_t h = 0;
+    for (; h + 3 < nsub; ++h) RING_STEP(h, 1, 3 * DPW);   // in flight after h + 1: all of h + 2, the A half of h + 3
+    if (h + 2 < nsub) { RING_STEP(h, 0, 2 * DPW); ++h; }
+    if (h + 1 < nsub) { RING_STEP(h, 0, 0); ++h; }
+    {
+      const int _slot = (int)(h & 3);
+      RING_PHASE(fa0, fb0, 1, _slot, 1, fa1, fb1, 0, 0, 0);
+      RING_PHASE(fa1, fb1, 0, 0, 0, fa0, fb0, 0, 0, 0);
     }
   }
   __syncthreads();   // all reads of the last sub-tile are done; the ring is reused below
@@ -285,32 +326,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   // loader geometry of the register-staged tiles (k tail and LoRA steps)
   const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
-  const int lr = tid >> 3;       // 0..63
+  const int lr = tid >> 3;       // 0..LROWS-1
   const int ncu = tid & 31;      // 16-byte unit along n (k-n tiles)
-  const int nkr = tid >> 5;      // 0..15
+  const int nkr = tid >> 5;      // 0..LKROWS-1
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
   // ---- k tail (Kc not a multiple of 32): one masked tile through registers
   if (nsub * SUBK < a.Kc) {
     const int64_t k0 = nsub * SUBK;
     const bool ka = (k0 + lc * 8) < a.Kc;
-    for (int i = 0; i < 4; ++i) {
-      const int row = lr + 64 * i;
+    for (int i = 0; i < LPASS; ++i) {
+      const int row = lr + LROWS * i;
       const int32_t tok = tok_s[row];
       uint4 v = zero4;
       if (ka && tok >= 0) v = *(const uint4*)(a.Aop + (int64_t)tok * a.lda + k0 + lc * 8);
       *(uint4*)(As + swz_rowk(row, lc)) = v;
     }
     if (FORM == FORM_NT) {
-      for (int i = 0; i < 4; ++i) {
-        const int row = lr + 64 * i;
+      for (int i = 0; i < LPASS; ++i) {
+        const int row = lr + LROWS * i;
         uint4 v = zero4;
         if (ka && (n0 + row) < a.Nout) v = *(const uint4*)(a.Bop + (n0 + row) * a.ldb + k0 + lc * 8);
         *(uint4*)(Bs + swz_rowk(row, lc)) = v;
       }
     } else {
-      for (int i = 0; i < 4; ++i) {
-        const int k = nkr + 16 * i;
+      for (int i = 0; i < LKPASS; ++i) {
+        const int k = nkr + LKROWS * i;
         uint4 v = zero4;
         if ((k0 + k) < a.Kc && (n0 + ncu * 8) < a.Nout)
           v = *(const uint4*)(a.Bop + (k0 + k) * a.ldb + n0 + ncu * 8);
@@ -344,8 +385,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
             const int kk0 = kc + lc * 8;
             const bool second = kk0 >= r_pad;
             const int q0 = kk0 - (second ? r_pad : 0);
-            for (int i = 0; i < 4; ++i) {
-              const int64_t m = m0 + lr + 64 * i;
+            for (int i = 0; i < LPASS; ++i) {
+              const int64_t m = m0 + lr + LROWS * i;
               uint4 pk = zero4;
               if (kk0 < kext && m >= lo && m < hi) {
                 const float4* up = (const float4*)(a.U + m * a.r_stride + q0);
@@ -358,12 +399,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
                 }
                 pk = pack8(o);
               }
-              *(uint4*)(As + swz_rowk(lr + 64 * i, lc)) = pk;
+              *(uint4*)(As + swz_rowk(lr + LROWS * i, lc)) = pk;
             }
             // B side: L_t stacked twice along the contraction
             if (FORM == FORM_NT) {
-              for (int i = 0; i < 4; ++i) {
-                const int64_t n = n0 + lr + 64 * i;
+              for (int i = 0; i < LPASS; ++i) {
+                const int64_t n = n0 + lr + LROWS * i;
                 uint4 pk = zero4;
                 if (kk0 < kext && n < a.Nout && q0 < r) {
                   const bf16_t* lp = L + n * r + q0;
@@ -375,16 +416,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
                     pk = pack8(o);
                   }
                 }
-                *(uint4*)(Bs + swz_rowk(lr + 64 * i, lc)) = pk;
+                *(uint4*)(Bs + swz_rowk(lr + LROWS * i, lc)) = pk;
               }
             } else {
-              for (int i = 0; i < 4; ++i) {
-                const int kk = kc + nkr + 16 * i;
+              for (int i = 0; i < LKPASS; ++i) {
+                const int kk = kc + nkr + LKROWS * i;
                 const int q = kk - (kk >= r_pad ? r_pad : 0);
                 uint4 pk = zero4;
                 if (kk < kext && q < r && (n0 + ncu * 8) < a.Nout)
                   pk = *(const uint4*)(L + (int64_t)q * a.Nout + n0 + ncu * 8);
-                *(uint4*)(Bs + swz_kn(nkr + 16 * i, ncu)) = pk;
+                *(uint4*)(Bs + swz_kn(nkr + LKROWS * i, ncu)) = pk;
               }
             }
             __syncthreads();
@@ -402,15 +443,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   // ---- epilogue: scatter rows back to token order
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
+  for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int row = wm * 128 + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      const int row = wm * (MT * 32) + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
       const int32_t tok = tok_s[row];
       if (tok < 0) continue;
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        const int64_t col = n0 + wn * 64 + nt * 32 + (lane & 31);
+      for (int nt = 0; nt < NT; ++nt) {
+        const int64_t col = n0 + wn * (NT * 32) + nt * 32 + (lane & 31);
         if (col < a.Nout) {
           if (OUT_F32) ((float*)a.out)[(int64_t)tok * a.ldo + col] = acc[mt][nt][v];
           else ((bf16_t*)a.out)[(int64_t)tok * a.ldo + col] = float_to_bf16_bits(acc[mt][nt][v]);
