@@ -286,7 +286,7 @@ extern "C" int64_t marlaas_u_stride(const marlaas_lora_desc* d) {
 }
 
 struct WsPlan {
-  size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;
+  size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;   // part: reused by every kernel with partial sums
 };
 
 static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
@@ -295,15 +295,21 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   const size_t uv = align_up((size_t)(d->T > 0 ? d->T : 1) * rs * sizeof(float), WS_ALIGN);
   size_t off = 0;
   p.u_off = off; off += uv;
+  size_t part = 0;
+  if (d->in_dtype == MARLAAS_BF16) part = gemm_splitk_bytes(d->T, d->d_in, d->d_out);
   if (want_bwd) {
     p.v_off = off; off += uv;
     if (d->in_dtype == MARLAAS_BF16) {
       const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs);
       const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs);
-      p.part_bytes = align_up(pa > pb ? pa : pb, WS_ALIGN);
-      p.part_off = off; off += p.part_bytes;
+      const size_t pg = gemm_splitk_bytes(d->T, d->d_out, d->d_in);
+      if (pa > part) part = pa;
+      if (pb > part) part = pb;
+      if (pg > part) part = pg;
     }
   }
+  p.part_bytes = align_up(part, WS_ALIGN);
+  p.part_off = off; off += p.part_bytes;
   p.total = off;
   return p;
 }
@@ -369,12 +375,14 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
   const int rs = (int)marlaas_u_stride(d);
   float* u = (float*)u_save;
   const bool lora = d->n_adapters > 0 && map->T_lora > 0;
+  WsPlan p = plan_workspace(d, 0);
+  const bool have_ws = ctx->ws && ctx->ws_bytes >= p.total;
   if (lora && !u) {
-    WsPlan p = plan_workspace(d, 0);
-    if (!ctx->ws || ctx->ws_bytes < p.total)
+    if (!have_ws)
       return fail(ctx, MARLAAS_ENOMEM, "forward needs %zu workspace bytes, have %zu", p.total, ctx->ws_bytes);
     u = (float*)((char*)ctx->ws + p.u_off);
   }
+  float* part = (have_ws && p.part_bytes) ? (float*)((char*)ctx->ws + p.part_off) : nullptr;
   const AdapterEntry* table = nullptr;
   if ((rc = adapter_table(ctx, d, &table)) != MARLAAS_OK) return rc;
   const int32_t* perm = map->identity ? nullptr : map->perm_dev;
@@ -388,7 +396,7 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
                                       map->max_seg, table, 0, form, u, rs, map->T_lora, st));
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
-                                  rs, y, ldy, out_f32, st));
+                                  rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -453,7 +461,8 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
   const int da_form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
   const int db_form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NT : FORM_NN;
   const int out_f32 = d->out_dtype == MARLAAS_F32;
-  float* part = p.part_bytes ? (float*)((char*)ctx->ws + p.part_off) : nullptr;
+  const bool have_ws = ctx->ws && ctx->ws_bytes >= p.total;
+  float* part = (have_ws && p.part_bytes) ? (float*)((char*)ctx->ws + p.part_off) : nullptr;
   if (d->in_dtype == MARLAAS_BF16) {
     const bf16_t* x = (const bf16_t*)d->x;
     const bf16_t* dy = (const bf16_t*)dY;
@@ -466,12 +475,12 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     if (dX && d->T > 0)
       PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
-                                    out_f32, st));
+                                    out_f32, part, part ? p.part_bytes : 0, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, grads, 1, db_form, u, rs, accumulate, part, p.part_bytes, st));
+                                      table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, grads, 0, da_form, v, rs, accumulate, part, p.part_bytes, st));
+                                      table, grads, 0, da_form, v, rs, accumulate, part, part ? p.part_bytes : 0, st));
     }
   } else {
     const float* x = (const float*)d->x;

@@ -78,7 +78,9 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
-                            int out_is_f32, hipStream_t stream);
+                            int out_is_f32, float* partials, size_t partial_bytes, hipStream_t stream);
+void gemm_splitk_plan(int64_t T, int64_t Kc, int64_t Nout, int* ksplit, int64_t* kchunk);
+size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout);
 
 // out_t(c, q) (+)= sum_{m in seg t} X[perm[m], c] * V[m, q]
 // out_form FORM_NN: out_t[c * r_t + q]; FORM_NT: out_t[q * C + c].

@@ -52,6 +52,10 @@ struct GemmArgs {
   const float* U; int r_stride;
   void* out; int64_t ldo;
   int tiles_m, tiles_n;
+  // split-K (few row tiles, e.g. decode): workgroup (tile, ks) handles contraction values
+  // [ks * kchunk, (ks + 1) * kchunk) and leaves its fp32 accumulators in `partials`
+  // ([tile][ks][accumulator register][thread]); splitk_finish_kernel adds them up.
+  int ksplit; int64_t kchunk; float* partials;
 };
 
 #ifndef EXP_NODMA
@@ -130,14 +134,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
   // tiles; inside a run, groups of 8 row tiles share their column tiles.
-  int tm, tn;
+  int tm, tn, ks_idx, tile_lin;
   {
-    const int G = a.tiles_m * a.tiles_n;
+    const int G = a.tiles_m * a.tiles_n * a.ksplit;
     const int b = blockIdx.x;
     const int xcd = b & 7, idx = b >> 3;
     const int q = G >> 3, rem = G & 7;
     const int start = xcd * q + (xcd < rem ? xcd : rem);
-    const int bb = start + idx;
+    const int bbs = start + idx;
+    const int bb = bbs / a.ksplit;          // the splits of one tile stay on one XCD (one L2)
+    ks_idx = bbs - bb * a.ksplit;
+    tile_lin = bb;
     const int GM = 8;
     const int per_group = GM * a.tiles_n;
     const int gid = bb / per_group;
@@ -158,6 +165,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   }
   __syncthreads();
 
+  const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
+  const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
+
   // ---- DMA geometry.  One wave instruction moves 64 x 16 B = 1 KB into
   // consecutive LDS bytes.  Row-k sub-tiles ([256][32] bf16, 64 B per row): 16
   // rows per instruction, lane l writes unit (l & 3) of row (l >> 2) and so
@@ -171,7 +181,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     const int row = (wave * DPW + j) * 16 + (lane >> 2);
     const int unit = (lane & 3) ^ ((row >> 2) & 3);
     const int32_t tok = tok_s[row];
-    a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + unit * 8;
+    a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + kbeg + unit * 8;
   }
   if (FORM == FORM_NT) {
     for (int j = 0; j < DPW; ++j) {
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int unit = (lane & 3) ^ ((row >> 2) & 3);
       int64_t n = n0 + row;
       if (n >= a.Nout) n = a.Nout - 1;           // clamped columns are never stored
-      b_src[j] = a.Bop + n * a.ldb + unit * 8;
+      b_src[j] = a.Bop + n * a.ldb + kbeg + unit * 8;
     }
     b_step = SUBK;
   } else {
@@ -188,7 +198,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int unit = (lane & 31) ^ ((k & 3) << 2);
       int64_t n = n0 + unit * 8;
       if (n >= a.Nout) n = a.Nout - 8;
-      b_src[j] = a.Bop + (int64_t)k * a.ldb + n;
+      b_src[j] = a.Bop + (kbeg + k) * a.ldb + n;
     }
     b_step = (int64_t)SUBK * a.ldb;
   }
@@ -228,14 +238,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int64_t nsub = a.Kc / SUBK;
+  const int64_t nsub = (kend - kbeg) / SUBK;
 
   static_assert(MT == 4 && NT == 4 && DPW == 4, "the interleaved schedule below is written for 4 x 4 MFMA tiles per wave");
 
 // s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
 #define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 // raw barrier: LDS traffic of this wave is complete, DMA traffic is tracked by hand with vmcnt
+#ifndef EXP_NOBAR
+#define EXP_NOBAR 0
+#endif
+#if EXP_NOBAR
+#define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
+#else
 #define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
+#endif
 
 // one DMA instruction: part j (0..3) of operand `isb_` (0 = A, 1 = B) of the sub-tile going to `slot_`
 #define RING_DMA1(slot_, isb_, j_)                                                                        \
@@ -332,9 +349,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
   // ---- k tail (Kc not a multiple of 32): one masked tile through registers
-  if (nsub * SUBK < a.Kc) {
-    const int64_t k0 = nsub * SUBK;
-    const bool ka = (k0 + lc * 8) < a.Kc;
+  if (kbeg + nsub * SUBK < kend) {
+    const int64_t k0 = kbeg + nsub * SUBK;
+    const bool ka = (k0 + lc * 8) < kend;
     for (int i = 0; i < LPASS; ++i) {
       const int row = lr + LROWS * i;
       const int32_t tok = tok_s[row];
@@ -353,16 +370,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       for (int i = 0; i < LKPASS; ++i) {
         const int k = nkr + LKROWS * i;
         uint4 v = zero4;
-        if ((k0 + k) < a.Kc && (n0 + ncu * 8) < a.Nout)
+        if ((k0 + k) < kend && (n0 + ncu * 8) < a.Nout)
           v = *(const uint4*)(a.Bop + (k0 + k) * a.ldb + n0 + ncu * 8);
         *(uint4*)(Bs + swz_kn(k, ncu)) = v;
       }
     }
     __syncthreads();
-    const int ksteps = (int)((a.Kc - k0 + 15) / 16);
+    const int ksteps = (int)((kend - k0 + 15) / 16);
     for (int ks = 0; ks < ksteps; ++ks)
       mma_kstep<FORM>(As, Bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
     __syncthreads();
+  }
+
+  if (a.ksplit > 1) {
+    // partial sums as plain fp32 rows: [ks][tiles_m * 256][tiles_n * 256]
+    const int64_t ldp = (int64_t)a.tiles_n * BN;
+    float* part = a.partials + ((int64_t)ks_idx * a.tiles_m * BM + m0) * ldp + n0;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = wm * (MT * 32) + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          part[(int64_t)row * ldp + wn * (NT * 32) + nt * 32 + (lane & 31)] = acc[mt][nt][v];
+      }
+    return;
   }
 
   // ---- LoRA expand as extra contraction steps, one adapter segment at a time
@@ -441,6 +474,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     }
   }
 
+#ifdef EXP_NOEPI
+  {  // timing experiment only: one store per lane keeps the accumulators alive
+    float sum = 0.f;
+    for (int mt = 0; mt < MT; ++mt) for (int nt = 0; nt < NT; ++nt) for (int v = 0; v < 16; ++v) sum += acc[mt][nt][v];
+    const int32_t tok = tok_s[lane];
+    if (tok >= 0) ((bf16_t*)a.out)[(int64_t)tok * a.ldo + n0 + wave] = float_to_bf16_bits(sum);
+    return;
+  }
+#endif
   // ---- epilogue: scatter rows back to token order
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -461,6 +503,82 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   }
 }
 
+// Second step of the split-K path: add the partial sums in split order, add the LoRA expand in
+// fp32 (u is fp32, so no two-term split is needed here) and scatter the rows.  One thread per
+// 4 consecutive output columns of one grouped row.
+template <int FORM, bool OUT_F32>
+__global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a) {
+  const int64_t ldp = (int64_t)a.tiles_n * BN;
+  const int64_t n4 = a.Nout / 4;                    // Nout is a multiple of 8
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= a.T * n4) return;
+  const int64_t m = idx / n4;
+  const int64_t n = (idx - m * n4) * 4;
+  const float* part = a.partials + m * ldp + n;
+  const int64_t kstride = (int64_t)a.tiles_m * BM * ldp;
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  int ks = 0;
+  for (; ks + 4 <= a.ksplit; ks += 4) {
+    const float4 p0 = *(const float4*)(part + (ks + 0) * kstride);
+    const float4 p1 = *(const float4*)(part + (ks + 1) * kstride);
+    const float4 p2 = *(const float4*)(part + (ks + 2) * kstride);
+    const float4 p3 = *(const float4*)(part + (ks + 3) * kstride);
+    sum.x = ((sum.x + p0.x) + p1.x) + p2.x + p3.x; sum.y = ((sum.y + p0.y) + p1.y) + p2.y + p3.y;
+    sum.z = ((sum.z + p0.z) + p1.z) + p2.z + p3.z; sum.w = ((sum.w + p0.w) + p1.w) + p2.w + p3.w;
+  }
+  for (; ks < a.ksplit; ++ks) {
+    const float4 p0 = *(const float4*)(part + ks * kstride);
+    sum.x += p0.x; sum.y += p0.y; sum.z += p0.z; sum.w += p0.w;
+  }
+  float y[4] = {sum.x, sum.y, sum.z, sum.w};
+  if (a.n_adapters > 0 && a.U != nullptr && m < (int64_t)a.seg_off[a.n_adapters]) {
+    const int t = segment_of(a.seg_off, a.n_adapters, (int)m);
+    const AdapterEntry e = a.table[t];
+    const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
+    const float* u = a.U + m * a.r_stride;
+    const int r = e.rank;
+    float lora[4] = {0.f, 0.f, 0.f, 0.f};
+    if (FORM == FORM_NT) {               // L[n * r + q]
+      if ((r & 7) == 0) {
+        for (int q0 = 0; q0 < r; q0 += 8) {
+          const float4 u0 = *(const float4*)(u + q0), u1 = *(const float4*)(u + q0 + 4);
+          const float uu[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint4 w = *(const uint4*)(L + (n + j) * r + q0);
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              lora[j] = fmaf(uu[i], __uint_as_float((ww[i >> 1] >> ((i & 1) * 16)) << 16), lora[j]);
+          }
+        }
+      } else {
+        for (int q = 0; q < r; ++q)
+          for (int j = 0; j < 4; ++j) lora[j] = fmaf(u[q], bf16_bits_to_float(L[(n + j) * r + q]), lora[j]);
+      }
+    } else {                             // L[q * Nout + n]
+      for (int q = 0; q < r; ++q) {
+        const uint2 w = *(const uint2*)(L + (int64_t)q * a.Nout + n);
+        const float uq = u[q];
+        lora[0] = fmaf(uq, __uint_as_float(w.x << 16), lora[0]);
+        lora[1] = fmaf(uq, __uint_as_float(w.x & 0xffff0000u), lora[1]);
+        lora[2] = fmaf(uq, __uint_as_float(w.y << 16), lora[2]);
+        lora[3] = fmaf(uq, __uint_as_float(w.y & 0xffff0000u), lora[3]);
+      }
+    }
+    for (int j = 0; j < 4; ++j) y[j] += lora[j];
+  }
+  const int64_t tok = a.perm ? a.perm[m] : m;
+  if (OUT_F32) {
+    *(float4*)((float*)a.out + tok * a.ldo + n) = make_float4(y[0], y[1], y[2], y[3]);
+  } else {
+    uint2 o;
+    o.x = float_to_bf16_bits(y[0]) | ((uint32_t)float_to_bf16_bits(y[1]) << 16);
+    o.y = float_to_bf16_bits(y[2]) | ((uint32_t)float_to_bf16_bits(y[3]) << 16);
+    *(uint2*)((bf16_t*)a.out + tok * a.ldo + n) = o;
+  }
+}
+
 template <int FORM, bool OUT_F32>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
   static bool attr_set = false;
@@ -471,15 +589,44 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
     attr_set = true;
   }
   const int G = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL(kern, dim3(G), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
+  hipLaunchKernelGGL(kern, dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.ksplit == 1) return e;
+  const int64_t work = a.T * (a.Nout / 4);
+  hipLaunchKernelGGL((splitk_finish_kernel<FORM, OUT_F32>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, a);
   return hipGetLastError();
+}
+
+size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout) {
+  int ksplit; int64_t kchunk;
+  gemm_splitk_plan(T, Kc, Nout, &ksplit, &kchunk);
+  if (ksplit <= 1) return 0;
+  const int64_t G = ((T + BM - 1) / BM) * ((Nout + BN - 1) / BN);
+  return (size_t)G * ksplit * BM * BN * sizeof(float);
+}
+
+// Split the contraction when the tiles alone cannot fill the 256 compute units.
+void gemm_splitk_plan(int64_t T, int64_t Kc, int64_t Nout, int* ksplit, int64_t* kchunk) {
+  const int64_t G = ((T + BM - 1) / BM) * ((Nout + BN - 1) / BN);
+  int s = 1;
+  if (G > 0 && G <= 128) {
+    s = (int)(256 / G);
+    const int64_t max_s = Kc / 128 > 0 ? Kc / 128 : 1;      // at least 128 contraction values per split
+    if (s > max_s) s = (int)max_s;
+    if (s > 32) s = 32;
+    if (s < 1) s = 1;
+  }
+  int64_t kc = (Kc + s - 1) / s;
+  kc = (kc + SUBK - 1) / SUBK * SUBK;
+  *kchunk = kc;
+  *ksplit = (int)((Kc + kc - 1) / kc);
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
                             int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
-                            int out_is_f32, hipStream_t stream) {
+                            int out_is_f32, float* partials, size_t partial_bytes, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   GemmArgs a;
   a.Aop = Aop; a.lda = lda; a.Bop = Bop; a.ldb = ldb; a.T = T; a.Kc = Kc; a.Nout = Nout;
@@ -487,6 +634,11 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   a.U = U; a.r_stride = r_stride; a.out = out; a.ldo = ldo;
   a.tiles_m = (int)((T + BM - 1) / BM);
   a.tiles_n = (int)((Nout + BN - 1) / BN);
+  gemm_splitk_plan(T, Kc, Nout, &a.ksplit, &a.kchunk);
+  a.partials = partials;
+  if (a.ksplit > 1 && (partials == nullptr || partial_bytes < gemm_splitk_bytes(T, Kc, Nout))) {
+    a.ksplit = 1; a.kchunk = Kc;    // no scratch for partial sums: one workgroup per tile
+  }
   if (form == FORM_NT) return out_is_f32 ? launch_one<FORM_NT, true>(a, stream) : launch_one<FORM_NT, false>(a, stream);
   return out_is_f32 ? launch_one<FORM_NN, true>(a, stream) : launch_one<FORM_NN, false>(a, stream);
 }

@@ -113,6 +113,76 @@ __global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
       }
 }
 
+// Small batches (decode): one block per (adapter, 16 grouped rows); its 8 waves split the
+// contraction, take both operands straight from global memory (L_t stored [r_t, C], so a lane's 8
+// contraction values are one 16-byte load) and add their partial tiles through LDS in wave order,
+// so the result does not depend on timing.
+static constexpr int SS_WAVES = 8;
+template <int DUMMY>
+__global__ __launch_bounds__(64 * SS_WAVES) void shrink_small_nt_kernel(ShrinkArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char red[];   // [SS_WAVES][nqt][64] f32x4
+  const int t = blockIdx.y;
+  const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
+  const int row0 = lo + blockIdx.x * 16;
+  if (row0 >= hi) return;
+  const AdapterEntry e = a.table[t];
+  const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
+  const int r = e.rank, r_pad = (r + 15) & ~15, nqt = r_pad >> 4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 4, li = lane & 15;
+  int m = row0 + li;
+  if (m >= hi) m = hi - 1;
+  const int64_t tok = a.perm ? a.perm[m] : m;
+  const bf16_t* xrow = a.X + tok * a.ldx;
+  const int64_t kw = ((a.C + SS_WAVES * 128 - 1) / (SS_WAVES * 128)) * 128;   // per wave, multiple of 128
+  const int64_t kbeg = wave * kw;
+  const int64_t kend = (kbeg + kw) < a.C ? (kbeg + kw) : a.C;
+  f32x4 acc[8];
+  for (int q = 0; q < 8; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  for (int64_t k0 = kbeg; k0 < kend; k0 += 128) {
+    uint4 xf[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int64_t k = k0 + g * 32 + j * 8;
+      xf[j] = k < kend ? *(const uint4*)(xrow + k) : zero4;
+    }
+#pragma unroll
+    for (int qt = 0; qt < 8; ++qt)
+      if (qt < nqt) {
+        const int q = qt * 16 + li;
+        uint4 lf[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t k = k0 + g * 32 + j * 8;
+          lf[j] = (q < r && k < kend) ? *(const uint4*)(L + (int64_t)q * a.C + k) : zero4;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          union { uint4 u; bf16x8 v; } xa, lb; xa.u = xf[j]; lb.u = lf[j];
+          acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, lb.v, acc[qt], 0, 0, 0);
+        }
+      }
+  }
+  f32x4* rp = (f32x4*)red;
+#pragma unroll
+  for (int qt = 0; qt < 8; ++qt)
+    if (qt < nqt) rp[(wave * nqt + qt) * 64 + lane] = acc[qt];
+  __syncthreads();
+  // wave w finishes q-tiles w, w + 8, ...
+  for (int qt = wave; qt < nqt; qt += SS_WAVES) {
+    f32x4 sum = rp[(0 * nqt + qt) * 64 + lane];
+    for (int w = 1; w < SS_WAVES; ++w) {
+      const f32x4 p = rp[(w * nqt + qt) * 64 + lane];
+      sum[0] += p[0]; sum[1] += p[1]; sum[2] += p[2]; sum[3] += p[3];
+    }
+    for (int v = 0; v < 4; ++v) {
+      const int mr = row0 + 4 * g + v;
+      if (mr < hi) a.u[(int64_t)mr * a.r_stride + qt * 16 + li] = e.scale * sum[v];
+    }
+  }
+}
+
 // plain fill (a kernel, not a memset node, so that callers may capture the pass in a HIP graph)
 __global__ __launch_bounds__(256) void zero_f32_kernel(float4* p, int64_t n4) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -127,8 +197,15 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   ShrinkArgs a;
   a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
   a.which = which; a.u = u; a.r_stride = r_stride;
-  const int rb_max = (max_seg + SH_ROWS - 1) / SH_ROWS;
   const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
+  if (lora_form == FORM_NT && real_blocks < 512) {
+    a.ksplit = 1; a.kchunk = 0;
+    const size_t lds = (size_t)SS_WAVES * (r_stride / 16) * 64 * sizeof(f32x4);
+    hipLaunchKernelGGL(shrink_small_nt_kernel<0>, dim3((max_seg + 15) / 16, n_adapters), dim3(64 * SS_WAVES), lds,
+                       stream, a);
+    return hipGetLastError();
+  }
+  const int rb_max = (max_seg + SH_ROWS - 1) / SH_ROWS;
   const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
   int ksplit = 1;
   if (real_blocks < 512) {
