@@ -12,7 +12,8 @@
 //
 // Tile: 256 x 256 per workgroup of 4 waves (2 x 2), each wave 128 x 128 as
 // 4 x 4 MFMA 32x32x16 accumulators (a large wave tile keeps LDS read traffic,
-// which competes with the DMA writes for LDS bandwidth, under the MFMA rate).  The contraction runs in sub-tiles of 32
+// which competes with the DMA writes for LDS bandwidth, under the MFMA rate).
+// The contraction runs in sub-tiles of 32
 // that go from global memory straight into LDS (16 bytes per lane, no register
 // staging) through a ring of four 32 KB slots: a sub-tile is requested three
 // steps before it is used, so HBM latency is covered, and there is one barrier
@@ -53,8 +54,8 @@ struct GemmArgs {
   void* out; int64_t ldo;
   int tiles_m, tiles_n;
   // split-K (few row tiles, e.g. decode): workgroup (tile, ks) handles contraction values
-  // [ks * kchunk, (ks + 1) * kchunk) and leaves its fp32 accumulators in `partials`
-  // ([tile][ks][accumulator register][thread]); splitk_finish_kernel adds them up.
+  // [ks * kchunk, (ks + 1) * kchunk) and leaves its fp32 sums in `partials`
+  // ([ks][tiles_m * 256][tiles_n * 256], grouped row order); splitk_finish_kernel adds them up.
   int ksplit; int64_t kchunk; float* partials;
 };
 
@@ -95,7 +96,7 @@ __device__ __forceinline__ uint4 pack8(const bf16_t* o) {
   return pk;
 }
 
-// One 16-wide contraction step of the wave's 128 x 64 block from LDS stage (as, bs).
+// One 16-wide contraction step of the wave's block from a 64-wide LDS tile pair (as, bs).
 template <int FORM>
 __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks, int a_off_row,
                                           int a_swz, int fk, int b_off_row, int b_swz,

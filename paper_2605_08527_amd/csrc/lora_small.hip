@@ -23,8 +23,9 @@ struct ShrinkArgs {
 };
 
 // grid: x = row blocks of the largest segment * ksplit, y = adapter
-template <int LFORM>
-__global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
+// NQT: 16-wide output tiles held per wave (covers the largest padded rank of the call)
+template <int LFORM, int NQT>
+__global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 2 : 4)) void shrink_bf16_kernel(ShrinkArgs a) {
   extern __shared__ __attribute__((aligned(16))) char Ls[];   // [r_pad][SH_PITCH]
   const int t = blockIdx.y;
   const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
@@ -47,16 +48,17 @@ __global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
   const int64_t tok = a.perm ? a.perm[m] : m;
   const bf16_t* xrow = a.X + tok * a.ldx;
 
-  f32x4 acc[8];
-  for (int q = 0; q < 8; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 acc[NQT];
+  for (int q = 0; q < NQT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
   for (int64_t k0 = kbeg; k0 < kend; k0 += SH_KSTG) {
-    // x fragments of this step: lane group g owns 32 consecutive k of every 128
+    // x fragments of this step: instruction (ms, j) covers 32 consecutive k, 8 per lane group,
+    // so the four lanes of a row fetch 64 contiguous bytes
     uint4 xf[2][4];
     for (int ms = 0; ms < 2; ++ms)
       for (int j = 0; j < 4; ++j) {
-        const int64_t k = k0 + ms * 128 + g * 32 + j * 8;
+        const int64_t k = k0 + ms * 128 + j * 32 + g * 8;
         xf[ms][j] = k < kend ? *(const uint4*)(xrow + k) : zero4;
       }
     __syncthreads();   // previous step's reads of Ls are done
@@ -90,9 +92,9 @@ __global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         union { uint4 u; bf16x8 v; } xa; xa.u = xf[ms][j];
-        const int koff = (ms * 128 + g * 32 + j * 8) * 2;
+        const int koff = (ms * 128 + j * 32 + g * 8) * 2;
 #pragma unroll
-        for (int qt = 0; qt < 8; ++qt)
+        for (int qt = 0; qt < NQT; ++qt)
           if (qt < nqt) {
             bf16x8 b = *(const bf16x8*)(Ls + (qt * 16 + li) * SH_PITCH + koff);
             acc[qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa.v, b, acc[qt], 0, 0, 0);
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(SH_THREADS) void shrink_bf16_kernel(ShrinkArgs a) {
   }
   // D layout: row = 4 * (lane / 16) + v, column = lane % 16
 #pragma unroll
-  for (int qt = 0; qt < 8; ++qt)
+  for (int qt = 0; qt < NQT; ++qt)
     if (qt < nqt)
       for (int v = 0; v < 4; ++v) {
         const int mr = row0 + wave * 16 + 4 * g + v;
@@ -220,7 +222,15 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
     hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, (float4*)u, n4);
   }
   const size_t lds = (size_t)r_stride * SH_PITCH;   // r_stride >= every r_pad
-  auto kern = lora_form == FORM_NT ? shrink_bf16_kernel<FORM_NT> : shrink_bf16_kernel<FORM_NN>;
+  typedef void (*kern_t)(ShrinkArgs);
+  const int nq = r_stride / 16;
+  kern_t kern;
+  if (lora_form == FORM_NT)
+    kern = nq <= 1 ? shrink_bf16_kernel<FORM_NT, 1> : nq <= 2 ? shrink_bf16_kernel<FORM_NT, 2>
+         : nq <= 4 ? shrink_bf16_kernel<FORM_NT, 4> : shrink_bf16_kernel<FORM_NT, 8>;
+  else
+    kern = nq <= 1 ? shrink_bf16_kernel<FORM_NN, 1> : nq <= 2 ? shrink_bf16_kernel<FORM_NN, 2>
+         : nq <= 4 ? shrink_bf16_kernel<FORM_NN, 4> : shrink_bf16_kernel<FORM_NN, 8>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -252,8 +262,8 @@ __device__ __forceinline__ int swz_tokc(int tk, int unit) {
 }
 
 // grid: x = slabs * chunks_max, y = adapter
-template <int OFORM>
-__global__ __launch_bounds__(RD_THREADS) void reduce_bf16_kernel(ReduceArgs a) {
+template <int OFORM, int NQT>
+__global__ __launch_bounds__(RD_THREADS, 2) void reduce_bf16_kernel(ReduceArgs a) {
   extern __shared__ __attribute__((aligned(16))) char rsm[];
   char* Xs = rsm;                               // [RD_TOK][RD_COLS] bf16, swizzled
   char* Vt = rsm + RD_TOK * RD_COLS * 2;        // [2][r_pad][RD_VPITCH]: hi, lo, transposed
@@ -270,9 +280,9 @@ __global__ __launch_bounds__(RD_THREADS) void reduce_bf16_kernel(ReduceArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 4, li = lane & 15;
-  f32x4 acc[4][8];
+  f32x4 acc[4][NQT];
   for (int i = 0; i < 4; ++i)
-    for (int q = 0; q < 8; ++q) acc[i][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < NQT; ++q) acc[i][q] = f32x4{0.f, 0.f, 0.f, 0.f};
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
   const int xu = tid & 31, xr = tid >> 5;     // X loader: unit along c, token row (+8 per step)
   const bool col_ok = (c0 + xu * 8) < a.C;
@@ -319,7 +329,7 @@ __global__ __launch_bounds__(RD_THREADS) void reduce_bf16_kernel(ReduceArgs a) {
         xa[ct] = u.v;
       }
 #pragma unroll
-      for (int qt = 0; qt < 8; ++qt)
+      for (int qt = 0; qt < NQT; ++qt)
         if (qt < nqt) {
           const int voff = (kstep * 32 + g * 8) * 2;
           bf16x8 vh = *(const bf16x8*)(Vt + (qt * 16 + li) * RD_VPITCH + voff);
@@ -339,7 +349,7 @@ __global__ __launch_bounds__(RD_THREADS) void reduce_bf16_kernel(ReduceArgs a) {
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-    for (int qt = 0; qt < 8; ++qt)
+    for (int qt = 0; qt < NQT; ++qt)
       if (qt < nqt)
         for (int v = 0; v < 4; ++v) {
           const int64_t c = c0 + wave * 64 + ct * 16 + 4 * g + v;
@@ -417,7 +427,15 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   }
   a.partials = partials;
   const size_t lds = (size_t)RD_TOK * RD_COLS * 2 + (size_t)2 * r_stride * RD_VPITCH;
-  auto kern = out_form == FORM_NN ? reduce_bf16_kernel<FORM_NN> : reduce_bf16_kernel<FORM_NT>;
+  typedef void (*rkern_t)(ReduceArgs);
+  const int nq = r_stride / 16;
+  rkern_t kern;
+  if (out_form == FORM_NN)
+    kern = nq <= 1 ? reduce_bf16_kernel<FORM_NN, 1> : nq <= 2 ? reduce_bf16_kernel<FORM_NN, 2>
+         : nq <= 4 ? reduce_bf16_kernel<FORM_NN, 4> : reduce_bf16_kernel<FORM_NN, 8>;
+  else
+    kern = nq <= 1 ? reduce_bf16_kernel<FORM_NT, 1> : nq <= 2 ? reduce_bf16_kernel<FORM_NT, 2>
+         : nq <= 4 ? reduce_bf16_kernel<FORM_NT, 4> : reduce_bf16_kernel<FORM_NT, 8>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
