@@ -13,13 +13,14 @@
 // Tile: 256 x 256 per workgroup of 4 waves (2 x 2), each wave 128 x 128 as
 // 4 x 4 MFMA 32x32x16 accumulators (a large wave tile keeps LDS read traffic,
 // which competes with the DMA writes for LDS bandwidth, under the MFMA rate).
-// The contraction runs in sub-tiles of 32
-// that go from global memory straight into LDS (16 bytes per lane, no register
-// staging) through a ring of four 32 KB slots: a sub-tile is requested three
-// steps before it is used, so HBM latency is covered, and there is one barrier
-// per sub-tile, placed between the two MFMA groups of a step so that the first
-// fragment reads of the next sub-tile overlap the second group.  16-byte units
-// are XOR-swizzled so that DMA writes and fragment reads are bank-conflict free.
+// The contraction runs in k-tiles of 64 that go from global memory straight
+// into LDS (16 bytes per lane, no register staging; every row segment is one
+// whole 128-byte line, which halves the L2 requests of a 32-wide tile) through
+// two 64 KB slots.  The parts of a k-tile are requested while the previous one
+// is multiplied, at least two MFMA phases before they are needed; the single
+// barrier per k-tile sits before the last phase, so the first fragment reads of
+// the next tile overlap MFMAs.  16-byte units are XOR-swizzled so that DMA
+// writes and fragment reads are bank-conflict free.
 #include "common.h"
 
 namespace marlaas {
@@ -29,16 +30,15 @@ static constexpr int WAVES_M = 2, WAVES_N = 2;             // wave grid inside t
 static constexpr int NWAVES = WAVES_M * WAVES_N;
 static constexpr int GEMM_THREADS = 64 * NWAVES;
 static constexpr int MT = BM / WAVES_M / 32, NT = BN / WAVES_N / 32;   // 32x32 MFMA tiles per wave
-static constexpr int DPW = 16 / NWAVES;                    // DMA instructions per wave, operand and sub-tile
+static constexpr int DPW = 32 / NWAVES;                    // DMA instructions per wave, operand and k-tile
 static constexpr int LROWS = GEMM_THREADS / 8;             // rows per pass of the register-staged loaders
 static constexpr int LPASS = BM / LROWS;
 static constexpr int LKROWS = GEMM_THREADS / 32;           // k-rows per pass (k-n tiles)
 static constexpr int LKPASS = BK / LKROWS;
-static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB: one 64-wide operand tile (tail / LoRA steps)
-static constexpr int SUBK = 32;                            // contraction values per ring slot
-static constexpr int SLOT_BYTES = 2 * BM * SUBK * 2;       // 32 KB: A part then B part
-static constexpr int SLOT_B_OFF = BM * SUBK * 2;
-static constexpr int RING_SLOTS = 4;
+static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB: one operand tile
+static constexpr int SLOT_BYTES = 2 * STAGE_BYTES;         // 64 KB: A part then B part
+static constexpr int SLOT_B_OFF = STAGE_BYTES;
+static constexpr int RING_SLOTS = 2;
 static constexpr int GEMM_LDS = RING_SLOTS * SLOT_BYTES + BM * 4;  // ring + token ids
 
 struct GemmArgs {
@@ -169,31 +169,33 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
   const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
 
-  // ---- DMA geometry.  One wave instruction moves 64 x 16 B = 1 KB into
-  // consecutive LDS bytes.  Row-k sub-tiles ([256][32] bf16, 64 B per row): 16
-  // rows per instruction, lane l writes unit (l & 3) of row (l >> 2) and so
-  // fetches the global unit (l & 3) ^ swizzle(row).  k-n sub-tiles ([32][256],
-  // 512 B per row): 2 k-rows per instruction.  Each wave issues 2 instructions
-  // per operand per sub-tile.
+  // ---- DMA geometry.  One wave instruction moves 64 x 16 B = 1 KB into consecutive LDS
+  // bytes.  Row-k tiles ([256][64] bf16, 128 B per row): 8 rows per instruction, lane l writes
+  // unit (l & 7) of row (l >> 3) and so fetches the global unit (l & 7) ^ swizzle(row); every
+  // row segment is one whole 128-byte cache line.  k-n tiles ([64][256], 512 B per row): 2
+  // k-rows per instruction.  Each wave issues DPW = 8 instructions per operand per k-tile.
   const bf16_t* a_src[DPW];
   const bf16_t* b_src[DPW];
-  int64_t b_step;          // elements to advance b_src per sub-tile
+  int64_t b_step;          // elements to advance b_src per k-tile
+#pragma unroll
   for (int j = 0; j < DPW; ++j) {
-    const int row = (wave * DPW + j) * 16 + (lane >> 2);
-    const int unit = (lane & 3) ^ ((row >> 2) & 3);
+    const int row = (wave * DPW + j) * 8 + (lane >> 3);
+    const int unit = (lane & 7) ^ ((row >> 1) & 7);
     const int32_t tok = tok_s[row];
     a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + kbeg + unit * 8;
   }
   if (FORM == FORM_NT) {
+#pragma unroll
     for (int j = 0; j < DPW; ++j) {
-      const int row = (wave * DPW + j) * 16 + (lane >> 2);
-      const int unit = (lane & 3) ^ ((row >> 2) & 3);
+      const int row = (wave * DPW + j) * 8 + (lane >> 3);
+      const int unit = (lane & 7) ^ ((row >> 1) & 7);
       int64_t n = n0 + row;
       if (n >= a.Nout) n = a.Nout - 1;           // clamped columns are never stored
       b_src[j] = a.Bop + n * a.ldb + kbeg + unit * 8;
     }
-    b_step = SUBK;
+    b_step = BK;
   } else {
+#pragma unroll
     for (int j = 0; j < DPW; ++j) {
       const int k = (wave * DPW + j) * 2 + (lane >> 5);
       const int unit = (lane & 31) ^ ((k & 3) << 2);
@@ -201,26 +203,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       if (n >= a.Nout) n = a.Nout - 8;
       b_src[j] = a.Bop + (kbeg + k) * a.ldb + n;
     }
-    b_step = (int64_t)SUBK * a.ldb;
+    b_step = (int64_t)BK * a.ldb;
   }
   const int dma_off = wave * DPW * 1024;   // this wave's first KB inside an operand part of a slot
 
-  // ---- fragment geometry
+  // ---- fragment geometry (all tiles are 64 wide)
   const int frow = lane & 31;          // row inside a 32-row MFMA tile
   const int fk = lane >> 5;            // which 8-wide half of the 16-wide k step
   const int a_row = wm * (MT * 32) + frow;
   const int b_row = wn * (NT * 32) + frow;
-  // 64-wide tiles (tail and LoRA steps)
   const int a_off_row = a_row * 128;
   const int a_swz = (a_row >> 1) & 7;  // rows 32 apart share the swizzle
   const int b_off_row = b_row * 128;
   const int b_swz = (b_row >> 1) & 7;
-  // 32-wide ring sub-tiles: byte offsets of this lane's fragment for ks = 0, 1
-  int a_f32[2], b_f32[2];
-  for (int ks = 0; ks < 2; ++ks) {
-    a_f32[ks] = a_row * 64 + (((ks * 2 + fk) ^ ((a_row >> 2) & 3)) << 4);
-    b_f32[ks] = b_row * 64 + (((ks * 2 + fk) ^ ((b_row >> 2) & 3)) << 4);
-  }
   int btr[NT];
   {
     const int g16 = lane >> 4, i16 = lane & 15;
@@ -239,9 +234,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int64_t nsub = (kend - kbeg) / SUBK;
+  const int64_t ntile = (kend - kbeg) / BK;
 
-  static_assert(MT == 4 && NT == 4 && DPW == 4, "the interleaved schedule below is written for 4 x 4 MFMA tiles per wave");
+  static_assert(MT == 4 && NT == 4 && DPW == 8, "the interleaved schedule below is written for 4 x 4 MFMA tiles per wave");
 
 // s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
 #define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
@@ -255,7 +250,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 #define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 #endif
 
-// one DMA instruction: part j (0..3) of operand `isb_` (0 = A, 1 = B) of the sub-tile going to `slot_`
+// one DMA instruction: part j (0..7) of operand `isb_` (0 = A, 1 = B) of the k-tile going to `slot_`
 #define RING_DMA1(slot_, isb_, j_)                                                                        \
   do {                                                                                                    \
     char* _sb = smem + (slot_) * SLOT_BYTES + dma_off + (j_) * 1024;                                      \
@@ -264,25 +259,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       if (!EXP_NOADV) b_src[j_] += b_step;                                                                \
     } else {                                                                                              \
       if (!EXP_NODMA) __builtin_amdgcn_global_load_lds((gptr_t)a_src[j_], (lptr_t)(_sb), 16, 0, 0);       \
-      if (!EXP_NOADV) a_src[j_] += SUBK;                                                                  \
+      if (!EXP_NOADV) a_src[j_] += BK;                                                                    \
     }                                                                                                     \
   } while (0)
 
-#define RING_DMA(slot_)                                                                                   \
+#define RING_DMA(slot_, isb_)                                                                             \
   do {                                                                                                    \
-    _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) RING_DMA1(slot_, 0, _j);                           \
-    _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) RING_DMA1(slot_, 1, _j);                           \
+    _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) RING_DMA1(slot_, isb_, _j);                        \
   } while (0)
 
-// fragment i (0..3 = A rows, 4..7 = B columns) of k-step ks_ of the sub-tile in `slot_`
+// fragment i (0..3 = A rows, 4..7 = B columns) of k-step ks_ of the k-tile in `slot_`
 #define RING_READ1(slot_, ks_, i_, af_, bf_)                                                              \
   do {                                                                                                    \
     const char* _as = smem + (slot_) * SLOT_BYTES;                                                        \
     const char* _bs = _as + SLOT_B_OFF;                                                                   \
     if ((i_) < 4) {                                                                                       \
-      af_[(i_) & 3] = *(const bf16x8*)(_as + a_f32[ks_] + ((i_) & 3) * (32 * 64));                        \
+      af_[(i_) & 3] = *(const bf16x8*)(_as + a_off_row + ((i_) & 3) * (32 * 128) +                        \
+                                       ((((ks_) * 2 + fk) ^ a_swz) << 4));                                \
     } else if (FORM == FORM_NT) {                                                                         \
-      bf_[(i_) & 3] = *(const bf16x8*)(_bs + b_f32[ks_] + ((i_) & 3) * (32 * 64));                        \
+      bf_[(i_) & 3] = *(const bf16x8*)(_bs + b_off_row + ((i_) & 3) * (32 * 128) +                        \
+                                       ((((ks_) * 2 + fk) ^ b_swz) << 4));                                \
     } else {                                                                                              \
       const char* _p = _bs + btr[(i_) & 3] + (ks_) * (16 * 512);                                          \
       bf_[(i_) & 3] = lds_read_frag_tr(_p, _p + 4 * 512);                                                 \
@@ -290,7 +286,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   } while (0)
 
 // 16 MFMAs on (ua_, ub_) with, in their shadow, the 8 fragment reads of (ld_slot_, ld_ks_) into
-// (la_, lb_) and 4 DMA instructions; sched_barrier pins this order (one wave per SIMD: nothing
+// (la_, lb_) and 8 DMA instructions; sched_barrier pins this order (one wave per SIMD: nothing
 // else hides the issue latency of LDS and DMA instructions).
 #define RING_PHASE(ua_, ub_, do_ld_, ld_slot_, ld_ks_, la_, lb_, do_dma_, dma_slot_, dma_isb_)            \
   do {                                                                                                    \
@@ -298,47 +294,49 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       acc[_i >> 2][_i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_[_i >> 2], ub_[_i & 3],           \
                                                                      acc[_i >> 2][_i & 3], 0, 0, 0);      \
       if ((do_ld_) && _i < 8) RING_READ1(ld_slot_, ld_ks_, _i, la_, lb_);                                 \
-      if ((do_dma_) && _i >= 8 && _i < 12) RING_DMA1(dma_slot_, dma_isb_, _i - 8);                        \
+      if ((do_dma_) && _i >= 8) RING_DMA1(dma_slot_, dma_isb_, _i - 8);                                   \
       __builtin_amdgcn_sched_barrier(0);                                                                  \
     }                                                                                                     \
   } while (0)
 
-// One sub-tile step h: phase A consumes k-step 0 (fa0, fb0) while loading k-step 1; then the
-// barrier that publishes sub-tile h + 1; phase B consumes k-step 1 while loading k-step 0 of h + 1.
-// dma_: request sub-tile h + 3 (its slot held h - 1, which every wave left before the barrier of
-// step h - 1).  wait_: DMA instructions of this wave that may still be in flight once h + 1 landed.
-#define RING_STEP(h_, dma_, wait_)                                                                        \
+// One k-tile kt (slot kt & 1), four phases of 16 MFMAs.  Phase 0 also requests the B part of
+// tile kt + 1 (its A part was requested one tile earlier).  Before phase 3 every wave waits for
+// its own DMA (all of tile kt + 1) and meets the others: tile kt + 1 is then complete, and no
+// wave still reads tile kt from LDS (its last fragments are in registers), so phase 3 reads the
+// first fragments of tile kt + 1 and requests the A part of tile kt + 2 into the slot of tile kt.
+#define RING_TILE(kt_, dma_b_, dma_a_, has_next_)                                                         \
   do {                                                                                                    \
-    const int _slot = (int)((h_) & 3), _nslot = (int)(((h_) + 1) & 3), _dslot = (int)(((h_) + 3) & 3);    \
-    RING_PHASE(fa0, fb0, 1, _slot, 1, fa1, fb1, dma_, _dslot, 0);                                         \
-    __builtin_amdgcn_s_waitcnt(VMCNT(wait_));                                                             \
-    RING_BARRIER();                                                                                       \
-    RING_PHASE(fa1, fb1, 1, _nslot, 0, fa0, fb0, dma_, _dslot, 1);                                        \
+    const int _slot = (int)((kt_) & 1), _nslot = _slot ^ 1;                                               \
+    RING_PHASE(fa0, fb0, 1, _slot, 1, fa1, fb1, dma_b_, _nslot, 1);                                       \
+    RING_PHASE(fa1, fb1, 1, _slot, 2, fa0, fb0, 0, 0, 0);                                                 \
+    RING_PHASE(fa0, fb0, 1, _slot, 3, fa1, fb1, 0, 0, 0);                                                 \
+    if (has_next_) {                                                                                      \
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));                                                               \
+      RING_BARRIER();                                                                                     \
+    }                                                                                                     \
+    RING_PHASE(fa1, fb1, has_next_, _nslot, 0, fa0, fb0, dma_a_, _slot, 0);                               \
   } while (0)
 
-  // ---- main loop over full sub-tiles
-  if (nsub > 0) {
+  // ---- main loop over full k-tiles
+  if (ntile > 0) {
     bf16x8 fa0[MT], fb0[NT], fa1[MT], fb1[NT];
-    RING_DMA(0);
-    if (nsub > 1) RING_DMA(1);
-    if (nsub > 2) RING_DMA(2);
-    if (nsub > 2) __builtin_amdgcn_s_waitcnt(VMCNT(4 * DPW));        // sub-tile 0 landed, two in flight
-    else if (nsub > 1) __builtin_amdgcn_s_waitcnt(VMCNT(2 * DPW));
-    else __builtin_amdgcn_s_waitcnt(VMCNT(0));
+    RING_DMA(0, 0);
+    RING_DMA(0, 1);
+    if (ntile > 1) {
+      RING_DMA(1, 0);
+      __builtin_amdgcn_s_waitcnt(VMCNT(DPW));     // tile 0 landed, the A part of tile 1 in flight
+    } else {
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+    }
     RING_BARRIER();
 #pragma unroll
     for (int i = 0; i < 8; ++i) RING_READ1(0, 0, i, fa0, fb0);
-    int64_t h = 0;
-    for (; h + 3 < nsub; ++h) RING_STEP(h, 1, 3 * DPW);   // in flight after h + 1: all of h + 2, the A half of h + 3
-    if (h + 2 < nsub) { RING_STEP(h, 0, 2 * DPW); ++h; }
-    if (h + 1 < nsub) { RING_STEP(h, 0, 0); ++h; }
-    {
-      const int _slot = (int)(h & 3);
-      RING_PHASE(fa0, fb0, 1, _slot, 1, fa1, fb1, 0, 0, 0);
-      RING_PHASE(fa1, fb1, 0, 0, 0, fa0, fb0, 0, 0, 0);
-    }
+    int64_t kt = 0;
+    for (; kt + 2 < ntile; ++kt) RING_TILE(kt, 1, 1, 1);
+    if (kt + 1 < ntile) { RING_TILE(kt, 1, 0, 1); ++kt; }
+    RING_TILE(kt, 0, 0, 0);
   }
-  __syncthreads();   // all reads of the last sub-tile are done; the ring is reused below
+  __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
   char* As = smem;                 // one 64-wide A tile
   char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile
 
@@ -349,9 +347,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int nkr = tid >> 5;      // 0..LKROWS-1
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
-  // ---- k tail (Kc not a multiple of 32): one masked tile through registers
-  if (kbeg + nsub * SUBK < kend) {
-    const int64_t k0 = kbeg + nsub * SUBK;
+  // ---- k tail (Kc not a multiple of 64): one masked tile through registers
+  if (kbeg + ntile * BK < kend) {
+    const int64_t k0 = kbeg + ntile * BK;
     const bool ka = (k0 + lc * 8) < kend;
     for (int i = 0; i < LPASS; ++i) {
       const int row = lr + LROWS * i;
@@ -484,7 +482,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     return;
   }
 #endif
-  // ---- epilogue: scatter rows back to token order
+#ifdef EXP_OLDEPI
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -500,6 +498,44 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
           else ((bf16_t*)a.out)[(int64_t)tok * a.ldo + col] = float_to_bf16_bits(acc[mt][nt][v]);
         }
       }
+    }
+  }
+  return;
+#endif
+  // ---- epilogue: each wave turns its accumulators (one column per lane) into rows through a
+  // private LDS strip, 32 rows at a time, so that every lane stores 16 contiguous bytes and a
+  // row segment of the wave (128 columns) leaves as whole cache lines; rows are scattered back
+  // to token order.  LDS traffic of one wave is ordered, so no workgroup barrier is needed.
+  {
+    constexpr int EPITCH = OUT_F32 ? (128 * 4 + 16) : (128 * 2 + 16);
+    constexpr int ECHUNKS = OUT_F32 ? 32 : 16;          // 16-byte chunks per row segment
+    constexpr int EITERS = 32 * ECHUNKS / 64;
+    char* ep = smem + wave * (32 * (128 * 4 + 16));
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row_l = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          const int col_l = nt * 32 + (lane & 31);
+          if (OUT_F32) *(float*)(ep + row_l * EPITCH + col_l * 4) = acc[mt][nt][v];
+          else *(bf16_t*)(ep + row_l * EPITCH + col_l * 2) = float_to_bf16_bits(acc[mt][nt][v]);
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int it = 0; it < EITERS; ++it) {
+        const int c = it * 64 + lane;
+        const int row_l = c / ECHUNKS, ch = c % ECHUNKS;
+        const uint4 val = *(const uint4*)(ep + row_l * EPITCH + ch * 16);
+        const int32_t tok = tok_s[wm * (MT * 32) + mt * 32 + row_l];
+        const int64_t col = n0 + wn * (NT * 32) + ch * (OUT_F32 ? 4 : 8);
+        if (tok >= 0 && col < a.Nout) {
+          if (OUT_F32) *(uint4*)((float*)a.out + (int64_t)tok * a.ldo + col) = val;
+          else *(uint4*)((bf16_t*)a.out + (int64_t)tok * a.ldo + col) = val;
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
   }
 }
@@ -618,7 +654,7 @@ void gemm_splitk_plan(int64_t T, int64_t Kc, int64_t Nout, int* ksplit, int64_t*
     if (s < 1) s = 1;
   }
   int64_t kc = (Kc + s - 1) / s;
-  kc = (kc + SUBK - 1) / SUBK * SUBK;
+  kc = (kc + BK - 1) / BK * BK;
   *kchunk = kc;
   *ksplit = (int)((Kc + kc - 1) / kc);
 }
