@@ -65,6 +65,12 @@ struct GemmArgs {
 #ifndef EXP_NOADV
 #define EXP_NOADV 0
 #endif
+#ifdef EXP_TIMING
+__device__ unsigned long long g_tim[8];
+#define TSTAMP(i) do { if (tid == 0) { const long long _t = clock64(); atomicAdd(&g_tim[i], (unsigned long long)(_t - t_prev)); t_prev = _t; } } while (0)
+#else
+#define TSTAMP(i) do {} while (0)
+#endif
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -132,6 +138,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+#ifdef EXP_TIMING
+  long long t_prev = clock64();
+#endif
 
   // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
   // tiles; inside a run, groups of 8 row tiles share their column tiles.
@@ -317,11 +326,113 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     RING_PHASE(fa1, fb1, has_next_, _nslot, 0, fa0, fb0, dma_a_, _slot, 0);                               \
   } while (0)
 
+  // loader geometry of the register-staged tiles (k tail and LoRA steps)
+  const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
+  const int lr = tid >> 3;       // 0..LROWS-1
+  const int ncu = tid & 31;      // 16-byte unit along n (k-n tiles)
+  const int nkr = tid >> 5;      // 0..LKROWS-1
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+
+  // ---- request the first k-tile, then (while it is in flight) do the LoRA expand
+  if (ntile > 0) { RING_DMA(0, 0); RING_DMA(0, 1); }
+
+  // LoRA expand as extra contraction steps, one adapter segment at a time, staged through slot 1.
+  // All global loads of a chunk are issued before any of them is used.
+  if (a.ksplit == 1 && a.n_adapters > 0 && a.U != nullptr) {
+    char* La = smem + SLOT_BYTES;
+    char* Lb = La + STAGE_BYTES;
+    const int64_t T_lora = a.seg_off[a.n_adapters];
+    const int64_t m_end = (m0 + BM) < T_lora ? (m0 + BM) : T_lora;
+    if (m0 < m_end) {
+      int t = segment_of(a.seg_off, a.n_adapters, (int)m0);
+      while (t < a.n_adapters && (int64_t)a.seg_off[t] < m_end) {
+        const int64_t lo = a.seg_off[t] > m0 ? (int64_t)a.seg_off[t] : m0;
+        const int64_t hi = (int64_t)a.seg_off[t + 1] < m_end ? (int64_t)a.seg_off[t + 1] : m_end;
+        if (hi > lo) {
+          const AdapterEntry e = a.table[t];
+          const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
+          const int r = e.rank;
+          const int r_pad = (r + 15) & ~15;
+          const int kext = 2 * r_pad;
+          for (int kc = 0; kc < kext; kc += BK) {
+            const int kk0 = kc + lc * 8;
+            const bool second = kk0 >= r_pad;
+            const int q0 = kk0 - (second ? r_pad : 0);
+            float4 uf[LPASS][2];
+            uint4 lw[LPASS];
+            // A side: u of the rows of this segment, zeros elsewhere
+#pragma unroll
+            for (int i = 0; i < LPASS; ++i) {
+              const int64_t m = m0 + lr + LROWS * i;
+              uf[i][0] = uf[i][1] = make_float4(0.f, 0.f, 0.f, 0.f);
+              if (kk0 < kext && m >= lo && m < hi) {
+                const float4* up = (const float4*)(a.U + m * a.r_stride + q0);
+                uf[i][0] = up[0]; uf[i][1] = up[1];
+              }
+            }
+            // B side: L_t stacked twice along the contraction
+            if (FORM == FORM_NT) {
+#pragma unroll
+              for (int i = 0; i < LPASS; ++i) {
+                const int64_t n = n0 + lr + LROWS * i;
+                lw[i] = zero4;
+                if (kk0 < kext && n < a.Nout && q0 < r) {
+                  const bf16_t* lp = L + n * r + q0;
+                  if ((r & 7) == 0) {
+                    lw[i] = *(const uint4*)lp;
+                  } else {
+                    bf16_t o[8];
+                    for (int j = 0; j < 8; ++j) o[j] = (q0 + j < r) ? lp[j] : (bf16_t)0;
+                    lw[i] = pack8(o);
+                  }
+                }
+              }
+            } else {
+#pragma unroll
+              for (int i = 0; i < LKPASS; ++i) {
+                const int kk = kc + nkr + LKROWS * i;
+                const int q = kk - (kk >= r_pad ? r_pad : 0);
+                lw[i] = zero4;
+                if (kk < kext && q < r && (n0 + ncu * 8) < a.Nout)
+                  lw[i] = *(const uint4*)(L + (int64_t)q * a.Nout + n0 + ncu * 8);
+              }
+            }
+            // two-term bf16 split of u: [u_hi | u_lo]
+#pragma unroll
+            for (int i = 0; i < LPASS; ++i) {
+              const float f[8] = {uf[i][0].x, uf[i][0].y, uf[i][0].z, uf[i][0].w,
+                                  uf[i][1].x, uf[i][1].y, uf[i][1].z, uf[i][1].w};
+              bf16_t o[8];
+              for (int j = 0; j < 8; ++j) {
+                const bf16_t h = float_to_bf16_bits(f[j]);
+                o[j] = second ? float_to_bf16_bits(f[j] - bf16_bits_to_float(h)) : h;
+              }
+              *(uint4*)(La + swz_rowk(lr + LROWS * i, lc)) = pack8(o);
+            }
+            if (FORM == FORM_NT) {
+#pragma unroll
+              for (int i = 0; i < LPASS; ++i) *(uint4*)(Lb + swz_rowk(lr + LROWS * i, lc)) = lw[i];
+            } else {
+#pragma unroll
+              for (int i = 0; i < LKPASS; ++i) *(uint4*)(Lb + swz_kn(nkr + LKROWS * i, ncu)) = lw[i];
+            }
+            __syncthreads();
+            const int left = kext - kc;
+            const int ksteps = left >= BK ? 4 : left / 16;
+            for (int ks = 0; ks < ksteps; ++ks)
+              mma_kstep<FORM>(La, Lb, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
+            __syncthreads();
+          }
+        }
+        ++t;
+      }
+    }
+  }
+
   // ---- main loop over full k-tiles
   if (ntile > 0) {
     bf16x8 fa0[MT], fb0[NT], fa1[MT], fb1[NT];
-    RING_DMA(0, 0);
-    RING_DMA(0, 1);
     if (ntile > 1) {
       RING_DMA(1, 0);
       __builtin_amdgcn_s_waitcnt(VMCNT(DPW));     // tile 0 landed, the A part of tile 1 in flight
@@ -329,6 +440,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       __builtin_amdgcn_s_waitcnt(VMCNT(0));
     }
     RING_BARRIER();
+    TSTAMP(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) RING_READ1(0, 0, i, fa0, fb0);
     int64_t kt = 0;
@@ -336,16 +448,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     if (kt + 1 < ntile) { RING_TILE(kt, 1, 0, 1); ++kt; }
     RING_TILE(kt, 0, 0, 0);
   }
+  TSTAMP(1);
   __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
   char* As = smem;                 // one 64-wide A tile
   char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile
-
-  // loader geometry of the register-staged tiles (k tail and LoRA steps)
-  const int lc = tid & 7;        // 16-byte unit along k (row-k tiles)
-  const int lr = tid >> 3;       // 0..LROWS-1
-  const int ncu = tid & 31;      // 16-byte unit along n (k-n tiles)
-  const int nkr = tid >> 5;      // 0..LKROWS-1
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
   // ---- k tail (Kc not a multiple of 64): one masked tile through registers
   if (kbeg + ntile * BK < kend) {
@@ -397,82 +503,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     return;
   }
 
-  // ---- LoRA expand as extra contraction steps, one adapter segment at a time
-  if (a.n_adapters > 0 && a.U != nullptr) {
-    const int64_t T_lora = a.seg_off[a.n_adapters];
-    const int64_t m_end = (m0 + BM) < T_lora ? (m0 + BM) : T_lora;
-    if (m0 < m_end) {
-      int t = segment_of(a.seg_off, a.n_adapters, (int)m0);
-      while (t < a.n_adapters && (int64_t)a.seg_off[t] < m_end) {
-        const int64_t lo = a.seg_off[t] > m0 ? (int64_t)a.seg_off[t] : m0;
-        const int64_t hi = (int64_t)a.seg_off[t + 1] < m_end ? (int64_t)a.seg_off[t + 1] : m_end;
-        if (hi > lo) {
-          const AdapterEntry e = a.table[t];
-          const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
-          const int r = e.rank;
-          const int r_pad = (r + 15) & ~15;
-          const int kext = 2 * r_pad;
-          for (int kc = 0; kc < kext; kc += BK) {
-            // A side: [u_hi | u_lo] of the rows of this segment, zeros elsewhere
-            const int kk0 = kc + lc * 8;
-            const bool second = kk0 >= r_pad;
-            const int q0 = kk0 - (second ? r_pad : 0);
-            for (int i = 0; i < LPASS; ++i) {
-              const int64_t m = m0 + lr + LROWS * i;
-              uint4 pk = zero4;
-              if (kk0 < kext && m >= lo && m < hi) {
-                const float4* up = (const float4*)(a.U + m * a.r_stride + q0);
-                float4 f0 = up[0], f1 = up[1];
-                float f[8] = {f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
-                bf16_t o[8];
-                for (int j = 0; j < 8; ++j) {
-                  bf16_t h = float_to_bf16_bits(f[j]);
-                  o[j] = second ? float_to_bf16_bits(f[j] - bf16_bits_to_float(h)) : h;
-                }
-                pk = pack8(o);
-              }
-              *(uint4*)(As + swz_rowk(lr + LROWS * i, lc)) = pk;
-            }
-            // B side: L_t stacked twice along the contraction
-            if (FORM == FORM_NT) {
-              for (int i = 0; i < LPASS; ++i) {
-                const int64_t n = n0 + lr + LROWS * i;
-                uint4 pk = zero4;
-                if (kk0 < kext && n < a.Nout && q0 < r) {
-                  const bf16_t* lp = L + n * r + q0;
-                  if ((r & 7) == 0) {
-                    pk = *(const uint4*)lp;
-                  } else {
-                    bf16_t o[8];
-                    for (int j = 0; j < 8; ++j) o[j] = (q0 + j < r) ? lp[j] : (bf16_t)0;
-                    pk = pack8(o);
-                  }
-                }
-                *(uint4*)(Bs + swz_rowk(lr + LROWS * i, lc)) = pk;
-              }
-            } else {
-              for (int i = 0; i < LKPASS; ++i) {
-                const int kk = kc + nkr + LKROWS * i;
-                const int q = kk - (kk >= r_pad ? r_pad : 0);
-                uint4 pk = zero4;
-                if (kk < kext && q < r && (n0 + ncu * 8) < a.Nout)
-                  pk = *(const uint4*)(L + (int64_t)q * a.Nout + n0 + ncu * 8);
-                *(uint4*)(Bs + swz_kn(nkr + LKROWS * i, ncu)) = pk;
-              }
-            }
-            __syncthreads();
-            const int left = kext - kc;
-            const int ksteps = left >= BK ? 4 : left / 16;
-            for (int ks = 0; ks < ksteps; ++ks)
-              mma_kstep<FORM>(As, Bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
-            __syncthreads();
-          }
-        }
-        ++t;
-      }
-    }
-  }
-
 #ifdef EXP_NOEPI
   {  // timing experiment only: one store per lane keeps the accumulators alive
     float sum = 0.f;
@@ -482,6 +512,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     return;
   }
 #endif
+  TSTAMP(2);
 #ifdef EXP_OLDEPI
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -538,7 +569,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
   }
+  TSTAMP(3);
 }
+
+#ifdef EXP_TIMING
+extern "C" int marlaas_debug_timing(unsigned long long* out8, int reset) {
+  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_tim), sizeof(g_tim)) != hipSuccess) return -1;
+  if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_tim), z, sizeof z) != hipSuccess) return -1; }
+  return 0;
+}
+#endif
 
 // Second step of the split-K path: add the partial sums in split order, add the LoRA expand in
 // fp32 (u is fp32, so no two-term split is needed here) and scatter the rows.  One thread per
