@@ -36,11 +36,10 @@ enum { FORM_NT = 0, FORM_NN = 1 };
 __device__ __forceinline__ float bf16_bits_to_float(bf16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);
 }
-// round to nearest even; inputs here are finite
+// round to nearest even (the hardware conversion of gfx950)
 __device__ __forceinline__ bf16_t float_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+  const __bf16 h = (__bf16)f;
+  return __builtin_bit_cast(bf16_t, h);
 }
 
 // Segment t of the grouped token order is [seg_off[t], seg_off[t+1]).

@@ -68,8 +68,14 @@ struct GemmArgs {
 #ifdef EXP_TIMING
 __device__ unsigned long long g_tim[8];
 #define TSTAMP(i) do { if (tid == 0) { const long long _t = clock64(); atomicAdd(&g_tim[i], (unsigned long long)(_t - t_prev)); t_prev = _t; } } while (0)
+#define TWAIT_BEGIN() long long _tw0 = 0, _tw1 = 0; do { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); _tw0 = clock64(); } while (0)
+#define TWAIT_MID() do { _tw1 = clock64(); } while (0)
+#define TWAIT_END() do { const long long _tw2 = clock64(); tw_vm += _tw1 - _tw0; tw_bar += _tw2 - _tw1; } while (0)
 #else
 #define TSTAMP(i) do {} while (0)
+#define TWAIT_BEGIN() do {} while (0)
+#define TWAIT_MID() do {} while (0)
+#define TWAIT_END() do {} while (0)
 #endif
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -136,10 +142,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets stay scalar
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 #ifdef EXP_TIMING
   long long t_prev = clock64();
+  long long tw_vm = 0, tw_bar = 0;
 #endif
 
   // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
@@ -320,8 +327,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     RING_PHASE(fa1, fb1, 1, _slot, 2, fa0, fb0, 0, 0, 0);                                                 \
     RING_PHASE(fa0, fb0, 1, _slot, 3, fa1, fb1, 0, 0, 0);                                                 \
     if (has_next_) {                                                                                      \
+      TWAIT_BEGIN();                                                                                      \
       __builtin_amdgcn_s_waitcnt(VMCNT(0));                                                               \
+      TWAIT_MID();                                                                                        \
       RING_BARRIER();                                                                                     \
+      TWAIT_END();                                                                                        \
     }                                                                                                     \
     RING_PHASE(fa1, fb1, has_next_, _nslot, 0, fa0, fb0, dma_a_, _slot, 0);                               \
   } while (0)
@@ -449,6 +459,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     RING_TILE(kt, 0, 0, 0);
   }
   TSTAMP(1);
+#ifdef EXP_TIMING
+  if (tid == 0) { atomicAdd(&g_tim[4], (unsigned long long)tw_vm); atomicAdd(&g_tim[5], (unsigned long long)tw_bar); }
+#endif
   __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
   char* As = smem;                 // one 64-wide A tile
   char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile

@@ -22,6 +22,8 @@ The five workloads follow the benchmark configurations of this build:
      scale 16/r, 16384 prefill + 512 decode tokens, token-granular shuffle
 Init for all: x~N(0,1), W~N(0,1/d_in), A_t~N(0,1/d_in), B_t~N(0,1/r_t).
 """
+import os
+
 import numpy as np
 
 MATH, TORCH = 0, 1
@@ -47,17 +49,31 @@ def to_f64(a):
     return a.astype(np.float64)
 
 
-def _normal(rng, shape, std, dtype):
-    """N(0, std^2) drawn in fp32 chunk by chunk, stored as `dtype`."""
+_CHUNK = 1 << 22
+
+
+def _normal(ss, shape, std, dtype):
+    """N(0, std^2) drawn in fp32 and stored as `dtype`.  `ss` is a SeedSequence; every chunk of
+    2^22 elements has its own child stream, so the values do not depend on the thread count."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.uint16 if dtype == "bf16" else np.float32)
-    step = 1 << 24
-    for s in range(0, n, step):
-        e = min(n, s + step)
-        c = rng.standard_normal(e - s, dtype=np.float32)
+    nchunks = (n + _CHUNK - 1) // _CHUNK
+    children = ss.spawn(nchunks) if nchunks else []
+
+    def fill(i):
+        s0, e0 = i * _CHUNK, min(n, (i + 1) * _CHUNK)
+        c = np.random.Generator(np.random.PCG64(children[i])).standard_normal(e0 - s0, dtype=np.float32)
         if std != 1.0:
             c *= np.float32(std)
-        out[s:e] = f32_to_bf16_bits(c) if dtype == "bf16" else c
+        out[s0:e0] = f32_to_bf16_bits(c) if dtype == "bf16" else c
+
+    if nchunks <= 2:
+        for i in range(nchunks):
+            fill(i)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, range(nchunks)))
     return out.reshape(shape)
 
 
@@ -95,14 +111,14 @@ def ragged_contiguous_ids(rng, n, T_total, seq_lo=256, seq_hi=2048, max_seqs=8):
 
 def make_layer(seed, T, d_in, d_out, ranks, scales, ids, dtype="bf16", layout=MATH, want_dY=False):
     """Draw x, W, A_t, B_t (and dY) for given shapes and token->adapter ids."""
-    rng = np.random.Generator(np.random.PCG64(seed))
     ranks = np.asarray(ranks, dtype=np.int32)
     n = len(ranks)
-    x = _normal(rng, (T, d_in), 1.0, dtype)
-    W = _normal(rng, (d_in, d_out), d_in ** -0.5, dtype)
-    A = [_normal(rng, (d_in, int(r)), d_in ** -0.5, dtype) for r in ranks]
-    B = [_normal(rng, (int(r), d_out), float(r) ** -0.5, dtype) for r in ranks]
-    dY = _normal(rng, (T, d_out), 1.0, dtype) if want_dY else None
+    stream = lambda *tag: np.random.SeedSequence([int(seed)] + [int(v) for v in tag])
+    x = _normal(stream(0), (T, d_in), 1.0, dtype)
+    W = _normal(stream(1), (d_in, d_out), d_in ** -0.5, dtype)
+    A = [_normal(stream(2, t), (d_in, int(r)), d_in ** -0.5, dtype) for t, r in enumerate(ranks)]
+    B = [_normal(stream(3, t), (int(r), d_out), float(r) ** -0.5, dtype) for t, r in enumerate(ranks)]
+    dY = _normal(stream(4), (T, d_out), 1.0, dtype) if want_dY else None
     if layout == TORCH:
         W = np.ascontiguousarray(W.T)
         A = [np.ascontiguousarray(a.T) for a in A]
