@@ -29,6 +29,10 @@ struct marlaas_ctx {
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
   std::vector<Span> spans;       // event pairs recorded while profiling is on
+  // Second stream for work that is independent of the main GEMM (the LoRA shrink of a small
+  // batch runs beside it); forked from and joined to the caller's stream with these events.
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 };
 
 struct marlaas_segmap {
@@ -41,6 +45,8 @@ struct marlaas_segmap {
   bool identity = false;            // ids were already grouped: kernels skip the gather
   int max_seg = 0;                  // largest adapter segment
   int64_t T_lora = 0;               // tokens that have an adapter
+  RowChunk* chunks_dev = nullptr;   // row chunks of the grouped order (see RowChunk)
+  int n_chunks = 0;
 };
 
 static const size_t TABLE_CACHE_SLOTS = 512;
@@ -109,6 +115,13 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   marlaas_ctx* ctx = new (std::nothrow) marlaas_ctx();
   if (!ctx) return MARLAAS_ENOMEM;
   ctx->device = device;
+  if (hipSetDevice(device) != hipSuccess ||
+      hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
+    marlaas_destroy(ctx);
+    return MARLAAS_EHIP;
+  }
   *out = ctx;
   return MARLAAS_OK;
 }
@@ -149,6 +162,9 @@ extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
   (void)hipSetDevice(ctx->device);
   drop_spans(ctx);
   for (auto& s : ctx->tables) (void)hipFree(s.dev);
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   delete ctx;
 }
 
@@ -224,6 +240,26 @@ extern "C" int marlaas_segmap_build(marlaas_ctx* ctx, const int32_t* token_adapt
     if (len > m->max_seg) m->max_seg = len;
   }
   m->T_lora = m->seg_off[n_adapters];
+  // row chunks: segment t split into pieces of ROW_CHUNK rows; the rows without an adapter last
+  std::vector<RowChunk> chunks;
+  for (int t = 0; t <= n_adapters; ++t) {
+    const int32_t end = t < n_adapters ? m->seg_off[t + 1] : (int32_t)T;
+    for (int32_t row0 = m->seg_off[t]; row0 < end; row0 += ROW_CHUNK) {
+      RowChunk c;
+      c.row0 = row0; c.nrows = end - row0 < ROW_CHUNK ? end - row0 : ROW_CHUNK; c.t = t < n_adapters ? t : -1; c.pad = 0;
+      chunks.push_back(c);
+    }
+  }
+  m->n_chunks = (int)chunks.size();
+  if (m->n_chunks > 0) {
+    e = hipMalloc((void**)&m->chunks_dev, sizeof(RowChunk) * chunks.size());
+    if (e == hipSuccess) e = hipMemcpy(m->chunks_dev, chunks.data(), sizeof(RowChunk) * chunks.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      status = fail(ctx, MARLAAS_EHIP, "segmap_build: %s", hipGetErrorString(e));
+      marlaas_segmap_destroy(m);
+      return status;
+    }
+  }
   *out = m;
   return MARLAAS_OK;
 }
@@ -233,6 +269,7 @@ extern "C" void marlaas_segmap_destroy(marlaas_segmap* map) {
   (void)hipSetDevice(map->device);
   (void)hipFree(map->perm_dev);
   (void)hipFree(map->seg_off_dev);
+  (void)hipFree(map->chunks_dev);
   delete map;
 }
 
@@ -391,12 +428,23 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
   const int form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
   const int out_f32 = d->out_dtype == MARLAAS_F32;
   if (d->in_dtype == MARLAAS_BF16) {
+    // A small batch leaves the expand to the split-K finish kernel, so the shrink is independent
+    // of the main GEMM kernel and runs beside it on the second stream (not while profiling:
+    // per-kernel times are taken one kernel at a time).
+    const bool beside = lora && !ctx->profile && ctx->side && !getenv("MARLAAS_SERIAL") && part && gemm_expand_in_finish(d->T, d->d_in, d->d_out, p.part_bytes);
+    hipStream_t sst = beside ? ctx->side : st;
+    if (beside) {
+      HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, st));
+      HIP_TRY(ctx, hipStreamWaitEvent(sst, ctx->ev_fork, 0));
+    }
     if (lora)
-      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
-                                      map->max_seg, table, 0, form, u, rs, map->T_lora, st));
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, sst, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
+                                      map->max_seg, table, 0, form, u, rs, map->T_lora, sst));
+    if (beside) HIP_TRY(ctx, hipEventRecord(ctx->ev_join, sst));
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
-                                  rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, st));
+                                  rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
+                                  beside ? ctx->ev_join : nullptr, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -475,7 +523,7 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     if (dX && d->T > 0)
       PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
-                                    out_f32, part, part ? p.part_bytes : 0, st));
+                                    out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks, nullptr, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));

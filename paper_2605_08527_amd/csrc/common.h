@@ -28,6 +28,13 @@ struct GradEntry {
   float* dB;
 };
 
+// Up to ROW_CHUNK consecutive rows of the grouped token order that belong to one adapter
+// (t = -1: rows without an adapter).  The chunks of a segment map cover every row once.
+static constexpr int ROW_CHUNK = 8;
+struct RowChunk {
+  int32_t row0, nrows, t, pad;
+};
+
 // How a [contraction, output] operand is stored.
 //   FORM_NT: element (k, n) at ptr[n * ld + k]   (contraction index contiguous)
 //   FORM_NN: element (k, n) at ptr[k * ld + n]   (output index contiguous)
@@ -73,13 +80,17 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               int r_stride, int64_t T_lora, hipStream_t stream);
 
 // out[perm[m], :] = Aop[perm[m], :] * Bop + (m in segment t) U[m, :] * L_t
+// u_ready (may be null): event after which U is valid; the kernel that reads U waits for it.
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
                             int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
-                            int out_is_f32, float* partials, size_t partial_bytes, hipStream_t stream);
-void gemm_splitk_plan(int64_t T, int64_t Kc, int64_t Nout, int* ksplit, int64_t* kchunk);
+                            int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
+                            int n_chunks, hipEvent_t u_ready, hipStream_t stream);
 size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout);
+// true when a call with these sizes and this much scratch adds the LoRA term in a separate
+// finish kernel (so that U is not needed by the main GEMM kernel)
+bool gemm_expand_in_finish(int64_t T, int64_t Kc, int64_t Nout, size_t partial_bytes);
 
 // out_t(c, q) (+)= sum_{m in seg t} X[perm[m], c] * V[m, q]
 // out_form FORM_NN: out_t[c * r_t + q]; FORM_NT: out_t[q * C + c].

@@ -55,8 +55,11 @@ struct GemmArgs {
   int tiles_m, tiles_n;
   // split-K (few row tiles, e.g. decode): workgroup (tile, ks) handles contraction values
   // [ks * kchunk, (ks + 1) * kchunk) and leaves its fp32 sums in `partials`
-  // ([ks][tiles_m * 256][tiles_n * 256], grouped row order); splitk_finish_kernel adds them up.
+  // ([ks][tiles_m * 256][ldp], grouped row order); splitk_finish_kernel adds them up.
   int ksplit; int64_t kchunk; float* partials;
+  int64_t ldp;             // row stride of the partial sums (tiles_n * tile width)
+  int64_t pm;              // rows of one split's partial sums (tiles_m * tile height)
+  const RowChunk* chunks; int n_chunks;   // row chunks of the grouped order (finish kernel)
 };
 
 #ifndef EXP_NODMA
@@ -65,8 +68,11 @@ struct GemmArgs {
 #ifndef EXP_NOADV
 #define EXP_NOADV 0
 #endif
-#ifdef EXP_TIMING
+#if defined(EXP_TIMING) || defined(EXP_TIMING_SK) || defined(EXP_TIMING_FIN)
 __device__ unsigned long long g_tim[8];
+__device__ long long g_stamps[4096 * 8];   // [block][stamp]: wall clock (10 ns units)
+#endif
+#ifdef EXP_TIMING
 #define TSTAMP(i) do { if (tid == 0) { const long long _t = clock64(); atomicAdd(&g_tim[i], (unsigned long long)(_t - t_prev)); t_prev = _t; } } while (0)
 #define TWAIT_BEGIN() long long _tw0 = 0, _tw1 = 0; do { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); _tw0 = clock64(); } while (0)
 #define TWAIT_MID() do { _tw1 = clock64(); } while (0)
@@ -502,8 +508,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   if (a.ksplit > 1) {
     // partial sums as plain fp32 rows: [ks][tiles_m * 256][tiles_n * 256]
-    const int64_t ldp = (int64_t)a.tiles_n * BN;
-    float* part = a.partials + ((int64_t)ks_idx * a.tiles_m * BM + m0) * ldp + n0;
+    const int64_t ldp = a.ldp;
+    float* part = a.partials + ((int64_t)ks_idx * a.pm + m0) * ldp + n0;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -585,7 +591,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   TSTAMP(3);
 }
 
-#ifdef EXP_TIMING
+#if defined(EXP_TIMING) || defined(EXP_TIMING_SK) || defined(EXP_TIMING_FIN)
+extern "C" int marlaas_debug_stamps(long long* out, int n) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_stamps), sizeof(long long) * n) == hipSuccess ? 0 : -1;
+}
 extern "C" int marlaas_debug_timing(unsigned long long* out8, int reset) {
   if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_tim), sizeof(g_tim)) != hipSuccess) return -1;
   if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_tim), z, sizeof z) != hipSuccess) return -1; }
@@ -593,144 +602,557 @@ extern "C" int marlaas_debug_timing(unsigned long long* out8, int reset) {
 }
 #endif
 
-// Second step of the split-K path: add the partial sums in split order, add the LoRA expand in
-// fp32 (u is fp32, so no two-term split is needed here) and scatter the rows.  One thread per
-// 4 consecutive output columns of one grouped row.
-template <int FORM, bool OUT_F32>
-__global__ __launch_bounds__(256) void splitk_finish_kernel(GemmArgs a) {
-  const int64_t ldp = (int64_t)a.tiles_n * BN;
-  const int64_t n4 = a.Nout / 4;                    // Nout is a multiple of 8
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= a.T * n4) return;
-  const int64_t m = idx / n4;
-  const int64_t n = (idx - m * n4) * 4;
-  const float* part = a.partials + m * ldp + n;
-  const int64_t kstride = (int64_t)a.tiles_m * BM * ldp;
-  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-  int ks = 0;
-  for (; ks + 4 <= a.ksplit; ks += 4) {
-    const float4 p0 = *(const float4*)(part + (ks + 0) * kstride);
-    const float4 p1 = *(const float4*)(part + (ks + 1) * kstride);
-    const float4 p2 = *(const float4*)(part + (ks + 2) * kstride);
-    const float4 p3 = *(const float4*)(part + (ks + 3) * kstride);
-    sum.x = ((sum.x + p0.x) + p1.x) + p2.x + p3.x; sum.y = ((sum.y + p0.y) + p1.y) + p2.y + p3.y;
-    sum.z = ((sum.z + p0.z) + p1.z) + p2.z + p3.z; sum.w = ((sum.w + p0.w) + p1.w) + p2.w + p3.w;
+// ---------------------------------------------------------------------------------------------
+// Small batches (decode): the weight is streamed once from HBM and is the dominant traffic.  With
+// few rows the 256 x 256 tile needs many contraction splits to fill the chip, and the fp32
+// partial sums then cost more traffic than the weight.  Here the tile is 128 x 128 (a quarter of
+// the splits for the same number of workgroups) and the DMA ring is four k-tiles deep, three of
+// them in flight (48 KB of weight per compute unit), which is what covers the HBM latency.  Each
+// wave owns 64 x 64.  The result always goes to fp32 partial rows; splitk_finish_kernel adds the
+// splits, the LoRA expand and the rounding.
+static constexpr int SK_BM = 128, SK_BN = 128;
+static constexpr int SK_A_BYTES = SK_BM * BK * 2;         // 16 KB
+static constexpr int SK_B_BYTES = SK_BN * BK * 2;         // 16 KB
+static constexpr int SK_SLOT = SK_A_BYTES + SK_B_BYTES;   // 32 KB
+static constexpr int SK_SLOTS = 4;
+static constexpr int SK_LDS = SK_SLOTS * SK_SLOT + SK_BM * 4;
+
+template <int FORM>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int32_t* tok_s = (int32_t*)(smem + SK_SLOTS * SK_SLOT);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+#ifdef EXP_TIMING_SK
+  long long t_prev = wall_clock64();
+  const long long t_begin = t_prev;
+  long long c_loop = 0;
+#define SKSTAMP(i) do { if (tid == 0) { const long long _t = wall_clock64(); atomicAdd(&g_tim[i], (unsigned long long)(_t - t_prev)); t_prev = _t; } } while (0)
+#else
+#define SKSTAMP(i) do {} while (0)
+#endif
+  int tm, tn, ks_idx;
+  {
+    // consecutive workgroups of one XCD: the row tiles of one column tile (they share the weight
+    // tile through that XCD's L2), then its contraction splits, then the next column tile
+    const int G = a.tiles_m * a.tiles_n * a.ksplit;
+    const int b = blockIdx.x;
+    const int xcd = b & 7, idx = b >> 3;
+    const int q = G >> 3, rem = G & 7;
+    const int bbs = xcd * q + (xcd < rem ? xcd : rem) + idx;
+    tm = bbs % a.tiles_m;
+    const int rest = bbs / a.tiles_m;
+    ks_idx = rest % a.ksplit;
+    tn = rest / a.ksplit;
   }
-  for (; ks < a.ksplit; ++ks) {
-    const float4 p0 = *(const float4*)(part + ks * kstride);
-    sum.x += p0.x; sum.y += p0.y; sum.z += p0.z; sum.w += p0.w;
+  const int64_t m0 = (int64_t)tm * SK_BM;
+  const int64_t n0 = (int64_t)tn * SK_BN;
+  if (tid < SK_BM) {
+    const int64_t m = m0 + tid;
+    tok_s[tid] = m < a.T ? (a.perm ? a.perm[m] : (int32_t)m) : -1;
   }
-  float y[4] = {sum.x, sum.y, sum.z, sum.w};
-  if (a.n_adapters > 0 && a.U != nullptr && m < (int64_t)a.seg_off[a.n_adapters]) {
-    const int t = segment_of(a.seg_off, a.n_adapters, (int)m);
-    const AdapterEntry e = a.table[t];
-    const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
-    const float* u = a.U + m * a.r_stride;
-    const int r = e.rank;
-    float lora[4] = {0.f, 0.f, 0.f, 0.f};
-    if (FORM == FORM_NT) {               // L[n * r + q]
-      if ((r & 7) == 0) {
-        for (int q0 = 0; q0 < r; q0 += 8) {
-          const float4 u0 = *(const float4*)(u + q0), u1 = *(const float4*)(u + q0 + 4);
-          const float uu[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+  __syncthreads();
+  const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
+  const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
+  const int64_t ntile = (kend - kbeg) / BK;
+
+  // DMA sources: 4 instructions (1 KB each) per wave per operand per k-tile
+  const bf16_t* a_src[4];
+  const bf16_t* b_src[4];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint4 w = *(const uint4*)(L + (n + j) * r + q0);
-            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+  for (int j = 0; j < 4; ++j) {
+    const int row = (wave * 4 + j) * 8 + (lane >> 3);
+    const int unit = (lane & 7) ^ ((row >> 1) & 7);
+    const int32_t tok = tok_s[row];
+    a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + kbeg + unit * 8;
+    if (FORM == FORM_NT) {           // B tile [128 n][64 k], 128-byte rows
+      int64_t n = n0 + row;
+      if (n >= a.Nout) n = a.Nout - 1;
+      b_src[j] = a.Bop + n * a.ldb + kbeg + unit * 8;
+    } else {                         // B tile [64 k][128 n], 256-byte rows
+      const int k = (wave * 4 + j) * 4 + (lane >> 4);
+      int64_t n = n0 + (((lane & 15) ^ ((k & 3) << 2)) << 3);
+      if (n >= a.Nout) n = a.Nout - 8;
+      b_src[j] = a.Bop + (kbeg + k) * a.ldb + n;
+    }
+  }
+  const int64_t b_step = FORM == FORM_NT ? (int64_t)BK : (int64_t)BK * a.ldb;
+
+  const int frow = lane & 31, fk = lane >> 5;
+  const int a_row = wm * 64 + frow, b_row = wn * 64 + frow;
+  const int a_off = a_row * 128, a_swz = (a_row >> 1) & 7;
+  const int b_off = b_row * 128, b_swz = (b_row >> 1) & 7;
+  int btr[2];
+  {
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int kb = (g16 >> 1) * 8 + (i16 >> 2);
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-              lora[j] = fmaf(uu[i], __uint_as_float((ww[i >> 1] >> ((i & 1) * 16)) << 16), lora[j]);
-          }
-        }
+    for (int nt = 0; nt < 2; ++nt) {
+      const int ncol = wn * 64 + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
+      btr[nt] = kb * 256 + (((ncol >> 3) ^ ((kb & 3) << 2)) << 4) + (ncol & 7) * 2;
+    }
+  }
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+#ifdef EXP_SK_NOADVB
+#define SK_BSTEP 0
+#else
+#define SK_BSTEP b_step
+#endif
+#ifdef EXP_SK_NOA
+#define SK_NA 0
+#else
+#define SK_NA 4
+#endif
+#define SK_DMA(slot_)                                                                                     \
+  do {                                                                                                    \
+    char* _sb = smem + (slot_) * SK_SLOT + wave * 4096;                                                   \
+    _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                    \
+      __builtin_amdgcn_global_load_lds((gptr_t)b_src[_j], (lptr_t)(_sb + SK_A_BYTES + _j * 1024), 16, 0, 0); \
+      b_src[_j] += SK_BSTEP;                                                                              \
+    }                                                                                                     \
+    _Pragma("unroll") for (int _j = 0; _j < SK_NA; ++_j) {                                                \
+      __builtin_amdgcn_global_load_lds((gptr_t)a_src[_j], (lptr_t)(_sb + _j * 1024), 16, 0, 0);           \
+      a_src[_j] += BK;                                                                                    \
+    }                                                                                                     \
+  } while (0)
+
+  auto kstep = [&](const char* as, const char* bs, int ks) {
+    bf16x8 af[2], bfr[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+      af[mt] = *(const bf16x8*)(as + a_off + mt * (32 * 128) + (((ks * 2 + fk) ^ a_swz) << 4));
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      if (FORM == FORM_NT) {
+        bfr[nt] = *(const bf16x8*)(bs + b_off + nt * (32 * 128) + (((ks * 2 + fk) ^ b_swz) << 4));
       } else {
-        for (int q = 0; q < r; ++q)
-          for (int j = 0; j < 4; ++j) lora[j] = fmaf(u[q], bf16_bits_to_float(L[(n + j) * r + q]), lora[j]);
-      }
-    } else {                             // L[q * Nout + n]
-      for (int q = 0; q < r; ++q) {
-        const uint2 w = *(const uint2*)(L + (int64_t)q * a.Nout + n);
-        const float uq = u[q];
-        lora[0] = fmaf(uq, __uint_as_float(w.x << 16), lora[0]);
-        lora[1] = fmaf(uq, __uint_as_float(w.x & 0xffff0000u), lora[1]);
-        lora[2] = fmaf(uq, __uint_as_float(w.y << 16), lora[2]);
-        lora[3] = fmaf(uq, __uint_as_float(w.y & 0xffff0000u), lora[3]);
+        const char* p = bs + btr[nt] + ks * (16 * 256);   // k & 3 is unchanged by steps of 4
+        bfr[nt] = lds_read_frag_tr(p, p + 4 * 256);
       }
     }
-    for (int j = 0; j < 4; ++j) y[j] += lora[j];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+  };
+
+  SKSTAMP(0);
+  // One wave per SIMD: nothing but the instruction order hides LDS and DMA latency, so the loop
+  // is software-pipelined by hand (sched_barrier pins the order).  Fragments of k-step s + 1 are
+  // read while the MFMAs of k-step s run; the wait + barrier for the next k-tile sits before the
+  // last k-step, whose MFMAs cover the first fragment reads of the next tile and the DMA issue.
+#define SK_READ(base_, ks_, af_, bf_)                                                                     \
+  do {                                                                                                    \
+    const char* _as = (base_);                                                                            \
+    const char* _bs = _as + SK_A_BYTES;                                                                   \
+    af_[0] = *(const bf16x8*)(_as + a_off + ((((ks_) * 2 + fk) ^ a_swz) << 4));                           \
+    af_[1] = *(const bf16x8*)(_as + a_off + 32 * 128 + ((((ks_) * 2 + fk) ^ a_swz) << 4));                \
+    if (FORM == FORM_NT) {                                                                                \
+      bf_[0] = *(const bf16x8*)(_bs + b_off + ((((ks_) * 2 + fk) ^ b_swz) << 4));                         \
+      bf_[1] = *(const bf16x8*)(_bs + b_off + 32 * 128 + ((((ks_) * 2 + fk) ^ b_swz) << 4));              \
+    } else {                                                                                              \
+      const char* _p0 = _bs + btr[0] + (ks_) * (16 * 256);                                                \
+      const char* _p1 = _bs + btr[1] + (ks_) * (16 * 256);                                                \
+      bf_[0] = lds_read_frag_tr(_p0, _p0 + 4 * 256);                                                      \
+      bf_[1] = lds_read_frag_tr(_p1, _p1 + 4 * 256);                                                      \
+    }                                                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+  } while (0)
+#define SK_MMA1(af_, bf_, mt_, nt_)                                                                       \
+  do {                                                                                                    \
+    acc[mt_][nt_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[mt_], bf_[nt_], acc[mt_][nt_], 0, 0, 0);  \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+  } while (0)
+#define SK_MMA(af_, bf_) do { SK_MMA1(af_, bf_, 0, 0); SK_MMA1(af_, bf_, 0, 1); SK_MMA1(af_, bf_, 1, 1); SK_MMA1(af_, bf_, 1, 0); } while (0)
+#define SK_DMA_B(sb_, j_)                                                                                 \
+  do {                                                                                                    \
+    __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)((sb_) + SK_A_BYTES + (j_) * 1024), 16, 0, 0); \
+    b_src[j_] += SK_BSTEP;                                                                                \
+  } while (0)
+#define SK_DMA_A(sb_, j_)                                                                                 \
+  do {                                                                                                    \
+    __builtin_amdgcn_global_load_lds((gptr_t)a_src[j_], (lptr_t)((sb_) + (j_) * 1024), 16, 0, 0);         \
+    a_src[j_] += BK;                                                                                      \
+  } while (0)
+
+  // three k-tiles in flight (8 DMA instructions per wave each)
+  if (ntile > 0) SK_DMA(0);
+  if (ntile > 1) SK_DMA(1);
+  if (ntile > 2) SK_DMA(2);
+  bf16x8 fa0[2], fb0[2], fa1[2], fb1[2];
+  if (ntile > 0) {
+    if (ntile > 2) __builtin_amdgcn_s_waitcnt(VMCNT(2 * (4 + SK_NA)));
+    else if (ntile == 2) __builtin_amdgcn_s_waitcnt(VMCNT(4 + SK_NA));
+    else __builtin_amdgcn_s_waitcnt(VMCNT(0));
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#ifdef EXP_TIMING_SK
+    SKSTAMP(1); c_loop = clock64();
+#endif
+    SK_READ(smem, 0, fa0, fb0);
   }
-  const int64_t tok = a.perm ? a.perm[m] : m;
-  if (OUT_F32) {
-    *(float4*)((float*)a.out + tok * a.ldo + n) = make_float4(y[0], y[1], y[2], y[3]);
-  } else {
-    uint2 o;
-    o.x = float_to_bf16_bits(y[0]) | ((uint32_t)float_to_bf16_bits(y[1]) << 16);
-    o.y = float_to_bf16_bits(y[2]) | ((uint32_t)float_to_bf16_bits(y[3]) << 16);
-    *(uint2*)((bf16_t*)a.out + tok * a.ldo + n) = o;
+  // One k-step: the first MFMA (the compiler's wait for this step's fragments sits before it and
+  // drains the LDS queue, so no younger read may be outstanding here), then the reads of the next
+  // step into the other fragment set, then the remaining three MFMAs.
+#define SK_STEP(ua_, ub_, base_, ks_, la_, lb_)                                                           \
+  do {                                                                                                    \
+    SK_MMA1(ua_, ub_, 0, 0);                                                                              \
+    SK_READ(base_, ks_, la_, lb_);                                                                        \
+    SK_MMA1(ua_, ub_, 0, 1); SK_MMA1(ua_, ub_, 1, 1); SK_MMA1(ua_, ub_, 1, 0);                            \
+  } while (0)
+  // steady state: tile kt + 3 is requested during tile kt
+  int64_t kt = 0;
+  for (; kt + 3 < ntile; ++kt) {
+    const char* cur = smem + (int)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+    SK_STEP(fa0, fb0, cur, 1, fa1, fb1);
+    SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
+    SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
+    // this wave's part of tile kt + 1 has landed (tile kt + 2 may still be in flight) ...
+    __builtin_amdgcn_s_waitcnt(VMCNT(4 + SK_NA));
+    // ... everyone's has, and nobody still reads tile kt - 1, whose slot is filled next
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    char* sb = smem + (int)((kt + 3) & (SK_SLOTS - 1)) * SK_SLOT + wave * 4096;
+    SK_MMA1(fa1, fb1, 0, 0);
+    SK_READ(smem + (int)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT, 0, fa0, fb0);
+    SK_DMA_B(sb, 0); SK_DMA_B(sb, 1); SK_DMA_B(sb, 2);
+    SK_MMA1(fa1, fb1, 0, 1);
+    SK_DMA_B(sb, 3);
+#ifndef EXP_SK_NOA
+    SK_DMA_A(sb, 0); SK_DMA_A(sb, 1);
+#endif
+    SK_MMA1(fa1, fb1, 1, 1);
+#ifndef EXP_SK_NOA
+    SK_DMA_A(sb, 2); SK_DMA_A(sb, 3);
+#endif
+    SK_MMA1(fa1, fb1, 1, 0);
+  }
+  // drain: the last three tiles are already requested
+  for (; kt < ntile; ++kt) {
+    const char* cur = smem + (int)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+    SK_STEP(fa0, fb0, cur, 1, fa1, fb1);
+    SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
+    SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
+    __builtin_amdgcn_s_waitcnt(VMCNT(0));
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    // (after the last tile this reads a stale slot; those fragments are not used)
+    SK_STEP(fa1, fb1, smem + (int)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT, 0, fa0, fb0);
+  }
+  __syncthreads();
+#ifdef EXP_TIMING_SK
+  if (tid == 0) atomicAdd(&g_tim[4], (unsigned long long)(clock64() - c_loop));
+#endif
+  SKSTAMP(2);
+  // k tail of the last split: one masked tile through registers into slot 0
+  if (kbeg + ntile * BK < kend) {
+    const int64_t k0 = kbeg + ntile * BK;
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    char* as = smem;
+    char* bs = smem + SK_A_BYTES;
+    {
+      const int lc = tid & 7, lr = tid >> 3;
+      const bool ka = (k0 + lc * 8) < kend;
+      for (int i = 0; i < 4; ++i) {
+        const int row = lr + 32 * i;
+        const int32_t tok = tok_s[row];
+        uint4 v = zero4;
+        if (ka && tok >= 0) v = *(const uint4*)(a.Aop + (int64_t)tok * a.lda + k0 + lc * 8);
+        *(uint4*)(as + swz_rowk(row, lc)) = v;
+        if (FORM == FORM_NT) {
+          uint4 w = zero4;
+          if (ka && (n0 + row) < a.Nout) w = *(const uint4*)(a.Bop + (n0 + row) * a.ldb + k0 + lc * 8);
+          *(uint4*)(bs + swz_rowk(row, lc)) = w;
+        }
+      }
+    }
+    if (FORM == FORM_NN) {
+      const int lc = tid & 15, lr = tid >> 4;
+      for (int i = 0; i < 4; ++i) {
+        const int k = lr + 16 * i;
+        uint4 w = zero4;
+        if ((k0 + k) < kend && (n0 + lc * 8) < a.Nout) w = *(const uint4*)(a.Bop + (k0 + k) * a.ldb + n0 + lc * 8);
+        *(uint4*)(bs + k * 256 + ((lc ^ ((k & 3) << 2)) << 4)) = w;
+      }
+    }
+    __syncthreads();
+    const int ksteps = (int)((kend - k0 + 15) / 16);
+    for (int ks = 0; ks < ksteps; ++ks) kstep(as, bs, ks);
+  }
+  float* part = a.partials + ((int64_t)ks_idx * a.pm + m0 + wm * 64) * a.ldp + n0 + wn * 64 + (lane & 31);
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) part[(int64_t)row * a.ldp + nt * 32] = acc[mt][nt][v];
+    }
+#ifdef EXP_TIMING_SK
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  SKSTAMP(3);
+  if (tid == 0) {
+    atomicMax(&g_tim[6], (unsigned long long)((1ll << 62) - t_begin));
+    atomicMax(&g_tim[7], (unsigned long long)t_prev);
+  }
+#endif
+}
+
+// Second step of the split-K path: add the partial sums in split order, add the LoRA expand in
+// fp32 (u is fp32, so no two-term split is needed here) and scatter the rows.  A block owns one
+// row chunk (up to 8 consecutive grouped rows of one adapter) x 512 columns, 2 per thread, so the
+// adapter's factor is read once per chunk and every load of a block is issued up front.  With a
+// column-chunk count that is a multiple of 8, column chunk c of every row chunk runs on XCD
+// c mod 8, whose L2 then holds that slice of each factor.
+static constexpr int FIN_THREADS = 256;
+static constexpr int FIN_COLS = 2 * FIN_THREADS;
+
+template <int FORM, bool OUT_F32>
+__global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) {
+  constexpr int R = ROW_CHUNK;
+  constexpr int UPT = R * 128 / FIN_THREADS;        // u values staged per thread
+  __shared__ float u_s[R][128];
+  const int tid = threadIdx.x;
+  const int ncol = (int)((a.Nout + FIN_COLS - 1) / FIN_COLS);
+  const int col = blockIdx.x % ncol;
+  const RowChunk ch = a.chunks[blockIdx.x / ncol];
+  const int64_t n = (int64_t)col * FIN_COLS + 2 * tid;
+  const bool active = n < a.Nout;                   // Nout is a multiple of 8
+  const int64_t kstride = a.pm * a.ldp;
+  const bool lora_on = ch.t >= 0 && a.U != nullptr;
+  // A block's run time is a few dependent memory round trips plus the partial-sum traffic, so
+  // the loads are requested in the order of their dependence depth: adapter entry, then u and
+  // the factor (ranks up to 32 are prefetched into registers), then the partial sums.
+  AdapterEntry e;
+  e.A = nullptr; e.B = nullptr; e.rank = 0; e.scale = 0.f;
+  float ureg[UPT];
+  uint4 wa[4], wb[4];          // FORM_NT prefetch: rows n and n + 1 of the factor, 8 ranks per entry
+  uint32_t wn[32];             // FORM_NN prefetch: columns n, n + 1 of factor row q
+  const bf16_t* L = nullptr;
+  bool pref = false;
+  if (lora_on) {
+    e = a.table[ch.t];
+    L = (const bf16_t*)(a.which ? e.B : e.A);
+    const int r = e.rank;
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int j = (tid >> 7) + i * (FIN_THREADS >> 7), q = tid & 127;
+      ureg[i] = (j < ch.nrows && q < r) ? a.U[(int64_t)(ch.row0 + j) * a.r_stride + q] : 0.f;
+    }
+    pref = r <= 32 && (FORM == FORM_NN || (r & 7) == 0);
+    if (pref && active) {
+      if (FORM == FORM_NT) {               // L[n * r + q]
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt)
+          if (qt * 8 < r) {
+            wa[qt] = *(const uint4*)(L + n * r + qt * 8);
+            wb[qt] = *(const uint4*)(L + (n + 1) * r + qt * 8);
+          }
+      } else {                             // L[q * Nout + n]
+#pragma unroll
+        for (int q = 0; q < 32; ++q)
+          if (q < r) wn[q] = *(const uint32_t*)(L + (int64_t)q * a.Nout + n);
+      }
+    }
+  }
+  // partial sums of every row of the chunk, in split order; four splits (32 loads) at a time
+  float y0[R], y1[R];
+  {
+    const float* part = a.partials + (int64_t)ch.row0 * a.ldp + (active ? n : 0);
+#pragma unroll
+    for (int j = 0; j < R; ++j) { y0[j] = 0.f; y1[j] = 0.f; }
+    for (int ks0 = 0; ks0 < a.ksplit; ks0 += 4) {
+      float2 p[4][R];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int ks = ks0 + i < a.ksplit ? ks0 + i : a.ksplit - 1;
+        const float* pk = part + ks * kstride;
+#pragma unroll
+        for (int j = 0; j < R; ++j) p[i][j] = *(const float2*)(pk + (j < ch.nrows ? j : 0) * a.ldp);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool on = ks0 + i < a.ksplit;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+          if (on && j < ch.nrows) { y0[j] += p[i][j].x; y1[j] += p[i][j].y; }
+        }
+      }
+    }
+  }
+  if (lora_on) {
+    const int r = e.rank;
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) u_s[(tid >> 7) + i * (FIN_THREADS >> 7)][tid & 127] = ureg[i];
+    __syncthreads();
+    if (active) {
+      if (pref && FORM == FORM_NT) {
+#pragma unroll
+        for (int qt = 0; qt < 4; ++qt)
+          if (qt * 8 < r) {
+            const uint32_t aw[4] = {wa[qt].x, wa[qt].y, wa[qt].z, wa[qt].w}, bw[4] = {wb[qt].x, wb[qt].y, wb[qt].z, wb[qt].w};
+            float fa[8], fb[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              fa[i] = __uint_as_float((aw[i >> 1] >> ((i & 1) * 16)) << 16);
+              fb[i] = __uint_as_float((bw[i >> 1] >> ((i & 1) * 16)) << 16);
+            }
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+              float sa = 0.f, sb = 0.f;
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                const float uq = u_s[j][qt * 8 + i];
+                sa = fmaf(uq, fa[i], sa); sb = fmaf(uq, fb[i], sb);
+              }
+              y0[j] += sa; y1[j] += sb;
+            }
+          }
+      } else if (pref) {
+#pragma unroll
+        for (int q = 0; q < 32; ++q)
+          if (q < r) {
+            const float fa = __uint_as_float(wn[q] << 16), fb = __uint_as_float(wn[q] & 0xffff0000u);
+#pragma unroll
+            for (int j = 0; j < R; ++j) { y0[j] = fmaf(u_s[j][q], fa, y0[j]); y1[j] = fmaf(u_s[j][q], fb, y1[j]); }
+          }
+      } else if (FORM == FORM_NT) {        // any rank: stream the factor
+        for (int q = 0; q < r; ++q) {
+          const float fa = bf16_bits_to_float(L[n * r + q]), fb = bf16_bits_to_float(L[(n + 1) * r + q]);
+#pragma unroll
+          for (int j = 0; j < R; ++j) { y0[j] = fmaf(u_s[j][q], fa, y0[j]); y1[j] = fmaf(u_s[j][q], fb, y1[j]); }
+        }
+      } else {
+        for (int q = 0; q < r; ++q) {
+          const uint32_t w = *(const uint32_t*)(L + (int64_t)q * a.Nout + n);
+          const float fa = __uint_as_float(w << 16), fb = __uint_as_float(w & 0xffff0000u);
+#pragma unroll
+          for (int j = 0; j < R; ++j) { y0[j] = fmaf(u_s[j][q], fa, y0[j]); y1[j] = fmaf(u_s[j][q], fb, y1[j]); }
+        }
+      }
+    }
+  }
+  if (!active) return;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    if (j < ch.nrows) {
+      const int64_t m = ch.row0 + j;
+      const int64_t tok = a.perm ? a.perm[m] : m;
+      if (OUT_F32) *(float2*)((float*)a.out + tok * a.ldo + n) = make_float2(y0[j], y1[j]);
+      else *(uint32_t*)((bf16_t*)a.out + tok * a.ldo + n) = float_to_bf16_bits(y0[j]) | ((uint32_t)float_to_bf16_bits(y1[j]) << 16);
+    }
   }
 }
 
 template <int FORM, bool OUT_F32>
-static hipError_t launch_one(const GemmArgs& a, hipStream_t stream) {
+static hipError_t launch_one(const GemmArgs& a, int mode, hipEvent_t u_ready, hipStream_t stream) {
   static bool attr_set = false;
-  auto kern = gemm_bf16_kernel<FORM, OUT_F32>;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<FORM, OUT_F32>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<FORM>, hipFuncAttributeMaxDynamicSharedMemorySize, SK_LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int G = a.tiles_m * a.tiles_n;
-  hipLaunchKernelGGL(kern, dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
+  if (u_ready && mode == 0) {       // the GEMM kernel itself reads U
+    hipError_t e = hipStreamWaitEvent(stream, u_ready, 0);
+    if (e != hipSuccess) return e;
+  }
+  if (mode == 2)
+    hipLaunchKernelGGL(gemm_skinny_kernel<FORM>, dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32>), dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || a.ksplit == 1) return e;
-  const int64_t work = a.T * (a.Nout / 4);
-  hipLaunchKernelGGL((splitk_finish_kernel<FORM, OUT_F32>), dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, a);
+  if (e != hipSuccess || mode == 0) return e;
+  if (u_ready && (e = hipStreamWaitEvent(stream, u_ready, 0)) != hipSuccess) return e;
+  const int64_t fin_blocks = ((a.Nout + FIN_COLS - 1) / FIN_COLS) * (int64_t)a.n_chunks;
+  hipLaunchKernelGGL((splitk_finish_kernel<FORM, OUT_F32>), dim3((unsigned)fin_blocks), dim3(FIN_THREADS), 0, stream, a);
   return hipGetLastError();
 }
 
-size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout) {
-  int ksplit; int64_t kchunk;
-  gemm_splitk_plan(T, Kc, Nout, &ksplit, &kchunk);
-  if (ksplit <= 1) return 0;
-  const int64_t G = ((T + BM - 1) / BM) * ((Nout + BN - 1) / BN);
-  return (size_t)G * ksplit * BM * BN * sizeof(float);
-}
+// How a call is tiled.  mode 0: one 256 x 256 workgroup per tile; mode 1: 256 x 256 tiles with
+// the contraction split; mode 2: 256 x 64 tiles with the contraction split (small batches).
+struct GemmPlan { int mode, tiles_m, tiles_n, ksplit; int64_t kchunk, ldp, pm; size_t bytes; };
 
-// Split the contraction when the tiles alone cannot fill the 256 compute units.
-void gemm_splitk_plan(int64_t T, int64_t Kc, int64_t Nout, int* ksplit, int64_t* kchunk) {
-  const int64_t G = ((T + BM - 1) / BM) * ((Nout + BN - 1) / BN);
-  int s = 1;
-  if (G > 0 && G <= 128) {
-    s = (int)(256 / G);
-    const int64_t max_s = Kc / 128 > 0 ? Kc / 128 : 1;      // at least 128 contraction values per split
-    if (s > max_s) s = (int)max_s;
-    if (s > 32) s = 32;
-    if (s < 1) s = 1;
+static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout) {
+  GemmPlan p;
+  p.tiles_m = (int)((T + BM - 1) / BM);
+  p.tiles_n = (int)((Nout + BN - 1) / BN);
+  p.mode = 0; p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0; p.bytes = 0;
+  const int64_t G = (int64_t)p.tiles_m * p.tiles_n;
+  if (G <= 0 || G > 128) return p;
+  int64_t tile_w = BN, tile_h = BM;
+  if (G <= 32) {
+    p.mode = 2; tile_w = SK_BN; tile_h = SK_BM;
+    p.tiles_m = (int)((T + SK_BM - 1) / SK_BM);
+    p.tiles_n = (int)((Nout + SK_BN - 1) / SK_BN);
+  } else {
+    p.mode = 1;
   }
+  const int64_t Gt = (int64_t)p.tiles_m * p.tiles_n;
+  int64_t s = (256 + Gt - 1) / Gt;                          // enough workgroups for 256 compute units
+  const int64_t min_k = p.mode == 2 ? 256 : 128;            // contraction values per split, at least
+  const int64_t max_s = Kc / min_k > 0 ? Kc / min_k : 1;
+  if (s > max_s) s = max_s;
+  if (s > 32) s = 32;
+  if (s < 1) s = 1;
   int64_t kc = (Kc + s - 1) / s;
   kc = (kc + BK - 1) / BK * BK;
-  *kchunk = kc;
-  *ksplit = (int)((Kc + kc - 1) / kc);
+  p.kchunk = kc;
+  p.ksplit = (int)((Kc + kc - 1) / kc);
+  if (p.mode == 1 && p.ksplit == 1) { p.mode = 0; return p; }
+  p.ldp = (int64_t)p.tiles_n * tile_w;
+  p.pm = (int64_t)p.tiles_m * tile_h;
+  p.bytes = (size_t)p.ksplit * p.pm * p.ldp * sizeof(float);
+  return p;
+}
+
+size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout) {
+  if (T <= 0 || Nout <= 0) return 0;
+  return gemm_plan(T, Kc, Nout).bytes;
+}
+
+bool gemm_expand_in_finish(int64_t T, int64_t Kc, int64_t Nout, size_t partial_bytes) {
+  if (T <= 0 || Nout <= 0) return false;
+  const GemmPlan p = gemm_plan(T, Kc, Nout);
+  return p.mode != 0 && partial_bytes >= p.bytes;
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
                             int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
-                            int out_is_f32, float* partials, size_t partial_bytes, hipStream_t stream) {
+                            int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
+                            int n_chunks, hipEvent_t u_ready, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   GemmArgs a;
   a.Aop = Aop; a.lda = lda; a.Bop = Bop; a.ldb = ldb; a.T = T; a.Kc = Kc; a.Nout = Nout;
   a.perm = perm; a.seg_off = seg_off; a.n_adapters = n_adapters; a.table = table; a.which = which;
   a.U = U; a.r_stride = r_stride; a.out = out; a.ldo = ldo;
-  a.tiles_m = (int)((T + BM - 1) / BM);
-  a.tiles_n = (int)((Nout + BN - 1) / BN);
-  gemm_splitk_plan(T, Kc, Nout, &a.ksplit, &a.kchunk);
-  a.partials = partials;
-  if (a.ksplit > 1 && (partials == nullptr || partial_bytes < gemm_splitk_bytes(T, Kc, Nout))) {
-    a.ksplit = 1; a.kchunk = Kc;    // no scratch for partial sums: one workgroup per tile
+  GemmPlan p = gemm_plan(T, Kc, Nout);
+  if (p.mode != 0 && (partials == nullptr || partial_bytes < p.bytes || chunks == nullptr)) {
+    // no scratch for partial sums: one 256 x 256 workgroup per tile
+    p.mode = 0; p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0;
+    p.tiles_m = (int)((T + BM - 1) / BM);
+    p.tiles_n = (int)((Nout + BN - 1) / BN);
   }
-  if (form == FORM_NT) return out_is_f32 ? launch_one<FORM_NT, true>(a, stream) : launch_one<FORM_NT, false>(a, stream);
-  return out_is_f32 ? launch_one<FORM_NN, true>(a, stream) : launch_one<FORM_NN, false>(a, stream);
+  a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.ksplit = p.ksplit; a.kchunk = p.kchunk;
+  a.ldp = p.ldp; a.pm = p.pm; a.partials = partials; a.chunks = chunks; a.n_chunks = n_chunks;
+  if (form == FORM_NT)
+    return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, u_ready, stream) : launch_one<FORM_NT, false>(a, p.mode, u_ready, stream);
+  return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, u_ready, stream) : launch_one<FORM_NN, false>(a, p.mode, u_ready, stream);
 }
 
 }  // namespace marlaas
