@@ -29,10 +29,6 @@ struct marlaas_ctx {
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
   std::vector<Span> spans;       // event pairs recorded while profiling is on
-  // Second stream for work that is independent of the main GEMM (the LoRA shrink of a small
-  // batch runs beside it); forked from and joined to the caller's stream with these events.
-  hipStream_t side = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 };
 
 struct marlaas_segmap {
@@ -115,13 +111,6 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   marlaas_ctx* ctx = new (std::nothrow) marlaas_ctx();
   if (!ctx) return MARLAAS_ENOMEM;
   ctx->device = device;
-  if (hipSetDevice(device) != hipSuccess ||
-      hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess) {
-    marlaas_destroy(ctx);
-    return MARLAAS_EHIP;
-  }
   *out = ctx;
   return MARLAAS_OK;
 }
@@ -162,9 +151,6 @@ extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
   (void)hipSetDevice(ctx->device);
   drop_spans(ctx);
   for (auto& s : ctx->tables) (void)hipFree(s.dev);
-  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
-  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   delete ctx;
 }
 
@@ -291,6 +277,12 @@ static int max_rank_of(const marlaas_lora_desc* d) {
   return mr;
 }
 
+static int sum_ranks_of(const marlaas_lora_desc* d) {
+  int64_t sum = 0;
+  for (int t = 0; t < d->n_adapters; ++t) sum += d->ranks[t];
+  return sum > 0x7fffffff ? 0x7fffffff : (int)sum;
+}
+
 static int check_sizes(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   if (!d) return fail(ctx, MARLAAS_EINVAL, "descriptor is null");
   if (d->T < 0 || d->d_in <= 0 || d->d_out <= 0) return fail(ctx, MARLAAS_EINVAL, "negative or zero size");
@@ -333,13 +325,14 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   size_t off = 0;
   p.u_off = off; off += uv;
   size_t part = 0;
-  if (d->in_dtype == MARLAAS_BF16) part = gemm_splitk_bytes(d->T, d->d_in, d->d_out);
+  const int n_ext = sum_ranks_of(d);
+  if (d->in_dtype == MARLAAS_BF16) part = gemm_splitk_bytes(d->T, d->d_in, d->d_out, n_ext);
   if (want_bwd) {
     p.v_off = off; off += uv;
     if (d->in_dtype == MARLAAS_BF16) {
       const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs);
       const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs);
-      const size_t pg = gemm_splitk_bytes(d->T, d->d_out, d->d_in);
+      const size_t pg = gemm_splitk_bytes(d->T, d->d_out, d->d_in, n_ext);
       if (pa > part) part = pa;
       if (pb > part) part = pb;
       if (pg > part) part = pg;
@@ -394,6 +387,31 @@ static int adapter_table(marlaas_ctx* ctx, const marlaas_lora_desc* d, const Ada
   return cached_table(ctx, host.data(), host.size() * sizeof(AdapterEntry), (const void**)dev);
 }
 
+// Tables of the fused shrink: rank offsets and the (adapter, rank index) of every extended column.
+static int fuse_tables(marlaas_ctx* ctx, const marlaas_lora_desc* d, GemmFuse* f) {
+  const int n = d->n_adapters;
+  std::vector<int32_t> host((size_t)n + 1);
+  bool mult8 = true;
+  int32_t off = 0;
+  for (int t = 0; t < n; ++t) { host[t] = off; off += d->ranks[t]; if (d->ranks[t] & 7) mult8 = false; }
+  host[n] = off;
+  // offsets padded to an even count, so that the column pairs that follow stay 8-byte aligned
+  if (host.size() & 1) host.push_back(0);
+  const size_t cols_at = host.size();
+  host.resize(cols_at + 2 * (size_t)off);
+  for (int t = 0, e = 0; t < n; ++t)
+    for (int q = 0; q < d->ranks[t]; ++q, ++e) { host[cols_at + 2 * e] = t; host[cols_at + 2 * e + 1] = q; }
+  const void* dev = nullptr;
+  int rc = cached_table(ctx, host.data(), host.size() * sizeof(int32_t), &dev);
+  if (rc != MARLAAS_OK) return rc;
+  f->roff = (const int32_t*)dev;
+  f->cols = (const ExtCol*)((const int32_t*)dev + cols_at);
+  f->n_ext = off;
+  f->ranks_mult8 = mult8;
+  f->u_out = nullptr;
+  return MARLAAS_OK;
+}
+
 // ------------------------------------------------------------------ forward
 extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy,
                                 void* u_save, void* stream) {
@@ -428,23 +446,26 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
   const int form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
   const int out_f32 = d->out_dtype == MARLAAS_F32;
   if (d->in_dtype == MARLAAS_BF16) {
-    // A small batch leaves the expand to the split-K finish kernel, so the shrink is independent
-    // of the main GEMM kernel and runs beside it on the second stream (not while profiling:
-    // per-kernel times are taken one kernel at a time).
-    const bool beside = lora && !ctx->profile && ctx->side && !getenv("MARLAAS_SERIAL") && part && gemm_expand_in_finish(d->T, d->d_in, d->d_out, p.part_bytes);
-    hipStream_t sst = beside ? ctx->side : st;
-    if (beside) {
-      HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, st));
-      HIP_TRY(ctx, hipStreamWaitEvent(sst, ctx->ev_fork, 0));
+    // small batches: the GEMM computes the shrink itself and no shrink kernel runs
+    GemmFuse fuse;
+    bool fused = false;
+    if (lora && part) {
+      const int n_ext = sum_ranks_of(d);
+      bool mult8 = true;
+      for (int t = 0; t < d->n_adapters; ++t) if (d->ranks[t] & 7) mult8 = false;
+      fused = gemm_can_fuse_shrink(form, d->T, d->d_in, d->d_out, n_ext, mult8, p.part_bytes);
+      if (fused) {
+        if ((rc = fuse_tables(ctx, d, &fuse)) != MARLAAS_OK) return rc;
+        fuse.u_out = u;
+      }
     }
-    if (lora)
-      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, sst, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
-                                      map->max_seg, table, 0, form, u, rs, map->T_lora, sst));
-    if (beside) HIP_TRY(ctx, hipEventRecord(ctx->ev_join, sst));
+    if (lora && !fused)
+      PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
+                                      map->max_seg, table, 0, form, u, rs, map->T_lora, st));
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
-                                  beside ? ctx->ev_join : nullptr, st));
+                                  fused ? &fuse : nullptr, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -517,13 +538,27 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     if (need_u)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, 0, fform, u, rs, map->T_lora, st));
-    if (lora && (dX || want_grads))
+    // small batches: the dX GEMM computes v itself (and leaves it in `v` for the dA reduction)
+    GemmFuse fuse;
+    bool fused = false;
+    if (lora && dX && part) {
+      const int n_ext = sum_ranks_of(d);
+      bool mult8 = true;
+      for (int t = 0; t < d->n_adapters; ++t) if (d->ranks[t] & 7) mult8 = false;
+      fused = gemm_can_fuse_shrink(bform, d->T, d->d_out, d->d_in, n_ext, mult8, p.part_bytes);
+      if (fused) {
+        if ((rc = fuse_tables(ctx, d, &fuse)) != MARLAAS_OK) return rc;
+        fuse.u_out = v;
+      }
+    }
+    if (lora && (dX || want_grads) && !fused)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, 1, bform, v, rs, map->T_lora, st));
     if (dX && d->T > 0)
       PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
-                                    out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks, nullptr, st));
+                                    out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
+                                    fused ? &fuse : nullptr, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));

@@ -35,6 +35,11 @@ struct RowChunk {
   int32_t row0, nrows, t, pad;
 };
 
+// Extended column e of the fused shrink: rank q of adapter t (e = rank offset of t + q).
+struct ExtCol {
+  int32_t t, q;
+};
+
 // How a [contraction, output] operand is stored.
 //   FORM_NT: element (k, n) at ptr[n * ld + k]   (contraction index contiguous)
 //   FORM_NN: element (k, n) at ptr[k * ld + n]   (output index contiguous)
@@ -79,18 +84,28 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               const AdapterEntry* table, int which, int lora_form, float* u,
                               int r_stride, int64_t T_lora, hipStream_t stream);
 
+struct GemmFuse {
+  const ExtCol* cols;      // [n_ext] device
+  const int32_t* roff;     // [n_adapters + 1] device: rank offsets
+  int n_ext;               // sum of the ranks
+  bool ranks_mult8;        // every rank is a multiple of 8
+  float* u_out;            // [T][r_stride] device: receives scale_t * (X L_t) per grouped row
+};
+
 // out[perm[m], :] = Aop[perm[m], :] * Bop + (m in segment t) U[m, :] * L_t
-// u_ready (may be null): event after which U is valid; the kernel that reads U waits for it.
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
                             int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, hipEvent_t u_ready, hipStream_t stream);
-size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout);
-// true when a call with these sizes and this much scratch adds the LoRA term in a separate
-// finish kernel (so that U is not needed by the main GEMM kernel)
-bool gemm_expand_in_finish(int64_t T, int64_t Kc, int64_t Nout, size_t partial_bytes);
+                            int n_chunks, const GemmFuse* fuse, hipStream_t stream);
+// scratch for partial sums; n_ext = sum of the adapter ranks (0: no adapters)
+size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout, int n_ext);
+// Small batches: the GEMM can compute the shrink itself (as extra output columns over every
+// adapter's factor; the finish kernel keeps each row's own adapter).  When this holds the caller
+// skips the shrink launch and passes a GemmFuse; U is then ignored and u_out receives u.
+bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_ext, bool ranks_mult8,
+                          size_t partial_bytes);
 
 // out_t(c, q) (+)= sum_{m in seg t} X[perm[m], c] * V[m, q]
 // out_form FORM_NN: out_t[c * r_t + q]; FORM_NT: out_t[q * C + c].

@@ -60,6 +60,12 @@ struct GemmArgs {
   int64_t ldp;             // row stride of the partial sums (tiles_n * tile width)
   int64_t pm;              // rows of one split's partial sums (tiles_m * tile height)
   const RowChunk* chunks; int n_chunks;   // row chunks of the grouped order (finish kernel)
+  // Fused shrink of the small-batch path: every column tile also computes 32 columns of
+  // X * [all adapters' shrink factors] (extended column e = rank offset of adapter t + q); the
+  // finish kernel picks each row's own adapter, scales and writes u_out.
+  const ExtCol* ext_cols; const int32_t* ext_roff; int n_ext;   // n_ext = sum of the ranks; 0: not fused
+  float* u_part; int64_t ldu;   // [ks][pm][ldu] fp32 partial sums of the extended columns
+  float* u_out;                 // [T][r_stride] (may be null)
 };
 
 #ifndef EXP_NODMA
@@ -610,14 +616,15 @@ extern "C" int marlaas_debug_timing(unsigned long long* out8, int reset) {
 // them in flight (48 KB of weight per compute unit), which is what covers the HBM latency.  Each
 // wave owns 64 x 64.  The result always goes to fp32 partial rows; splitk_finish_kernel adds the
 // splits, the LoRA expand and the rounding.
-static constexpr int SK_BM = 128, SK_BN = 128;
+static constexpr int SK_BM = 128, SK_BN = 128, SK_BX = 32;
 static constexpr int SK_A_BYTES = SK_BM * BK * 2;         // 16 KB
 static constexpr int SK_B_BYTES = SK_BN * BK * 2;         // 16 KB
-static constexpr int SK_SLOT = SK_A_BYTES + SK_B_BYTES;   // 32 KB
+static constexpr int SK_X_BYTES = SK_BX * BK * 2;         // 4 KB: extended (shrink) columns
+static constexpr int SK_SLOT = SK_A_BYTES + SK_B_BYTES + SK_X_BYTES;   // 36 KB
 static constexpr int SK_SLOTS = 4;
 static constexpr int SK_LDS = SK_SLOTS * SK_SLOT + SK_BM * 4;
 
-template <int FORM>
+template <int FORM, bool EXT>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int32_t* tok_s = (int32_t*)(smem + SK_SLOTS * SK_SLOT);
@@ -649,14 +656,39 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
   }
   const int64_t m0 = (int64_t)tm * SK_BM;
   const int64_t n0 = (int64_t)tn * SK_BN;
+  const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
+  const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
+  const int64_t ntile = (kend - kbeg) / BK;
+  // (two dependent table loads: requested first, needed last)
+  // extended columns: one DMA instruction per wave per k-tile
+  const bf16_t* x_src = nullptr;
+  int64_t x_step = 0;
+  if (EXT) {
+    if (FORM == FORM_NT) {           // tile [32 e][64 k]: row = extended column, factor stored [r][Kc]
+      const int row = wave * 8 + (lane >> 3);
+      const int unit = (lane & 7) ^ ((row >> 1) & 7);
+      int e = tn * SK_BX + row;
+      if (e >= a.n_ext) e = a.n_ext - 1;
+      const ExtCol c = a.ext_cols[e];
+      const AdapterEntry en = a.table[c.t];
+      x_src = (const bf16_t*)(a.which ? en.A : en.B) + (int64_t)c.q * a.Kc + kbeg + unit * 8;
+      x_step = BK;
+    } else {                         // tile [64 k][32 e], 64-byte rows: factor stored [Kc][r], r % 8 == 0
+      const int k = wave * 16 + (lane >> 2);
+      int e = tn * SK_BX + (lane & 3) * 8;
+      if (e >= a.n_ext) e = a.n_ext - 8;
+      const ExtCol c = a.ext_cols[e];
+      const AdapterEntry en = a.table[c.t];
+      x_src = (const bf16_t*)(a.which ? en.A : en.B) + (kbeg + k) * en.rank + c.q;
+      x_step = (int64_t)BK * en.rank;
+    }
+  }
+
   if (tid < SK_BM) {
     const int64_t m = m0 + tid;
     tok_s[tid] = m < a.T ? (a.perm ? a.perm[m] : (int32_t)m) : -1;
   }
   __syncthreads();
-  const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
-  const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
-  const int64_t ntile = (kend - kbeg) / BK;
 
   // DMA sources: 4 instructions (1 KB each) per wave per operand per k-tile
   const bf16_t* a_src[4];
@@ -679,7 +711,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
   const int64_t b_step = FORM == FORM_NT ? (int64_t)BK : (int64_t)BK * a.ldb;
-
   const int frow = lane & 31, fk = lane >> 5;
   const int a_row = wm * 64 + frow, b_row = wn * 64 + frow;
   const int a_off = a_row * 128, a_swz = (a_row >> 1) & 7;
@@ -695,6 +726,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
 
+  const int x_off = frow * 128, x_swz = (frow >> 1) & 7;        // NT fragment of the extended tile
+  int xtr = 0;                                                   // NN: transposing read offset
+  {
+    const int g16 = lane >> 4, i16 = lane & 15;
+    const int kb = (g16 >> 1) * 8 + (i16 >> 2);
+    xtr = kb * 64 + ((g16 & 1) * 16 + 4 * (i16 & 3)) * 2;
+  }
+  f32x16 acc_x;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc_x[v] = 0.f;
   f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -725,6 +766,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       a_src[_j] += BK;                                                                                    \
     }                                                                                                     \
   } while (0)
+#define SK_DMA_X(slot_)                                                                                   \
+  do {                                                                                                    \
+    if (EXT) {                                                                                            \
+      __builtin_amdgcn_global_load_lds((gptr_t)x_src,                                                     \
+          (lptr_t)(smem + (slot_) * SK_SLOT + SK_A_BYTES + SK_B_BYTES + wave * 1024), 16, 0, 0);           \
+      x_src += x_step;                                                                                    \
+    }                                                                                                     \
+  } while (0)
 
   auto kstep = [&](const char* as, const char* bs, int ks) {
     bf16x8 af[2], bfr[2];
@@ -745,6 +794,17 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+    if (EXT) {
+      const char* xs = bs + SK_B_BYTES;
+      bf16x8 xf;
+      if (FORM == FORM_NT) {
+        xf = *(const bf16x8*)(xs + x_off + (((ks * 2 + fk) ^ x_swz) << 4));
+      } else {
+        const char* px = xs + xtr + ks * (16 * 64);
+        xf = lds_read_frag_tr(px, px + 4 * 64);
+      }
+      acc_x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wn ? af[1] : af[0], xf, acc_x, 0, 0, 0);
+    }
   };
 
   SKSTAMP(0);
@@ -767,14 +827,29 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       bf_[0] = lds_read_frag_tr(_p0, _p0 + 4 * 256);                                                      \
       bf_[1] = lds_read_frag_tr(_p1, _p1 + 4 * 256);                                                      \
     }                                                                                                     \
+    if (EXT) {                                                                                            \
+      const char* _xs = _bs + SK_B_BYTES;                                                                 \
+      if (FORM == FORM_NT) {                                                                              \
+        bf_[2] = *(const bf16x8*)(_xs + x_off + ((((ks_) * 2 + fk) ^ x_swz) << 4));                       \
+      } else {                                                                                            \
+        const char* _px = _xs + xtr + (ks_) * (16 * 64);                                                  \
+        bf_[2] = lds_read_frag_tr(_px, _px + 4 * 64);                                                     \
+      }                                                                                                   \
+    }                                                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                                    \
+  } while (0)
+#define SK_MMAX(af_, bf_)                                                                                 \
+  do {                                                                                                    \
+    if (EXT) {                                                                                            \
+      acc_x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wn ? af_[1] : af_[0], bf_[2], acc_x, 0, 0, 0);                   \
+      __builtin_amdgcn_sched_barrier(0);                                                                  \
+    }                                                                                                     \
   } while (0)
 #define SK_MMA1(af_, bf_, mt_, nt_)                                                                       \
   do {                                                                                                    \
     acc[mt_][nt_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_[mt_], bf_[nt_], acc[mt_][nt_], 0, 0, 0);  \
     __builtin_amdgcn_sched_barrier(0);                                                                    \
   } while (0)
-#define SK_MMA(af_, bf_) do { SK_MMA1(af_, bf_, 0, 0); SK_MMA1(af_, bf_, 0, 1); SK_MMA1(af_, bf_, 1, 1); SK_MMA1(af_, bf_, 1, 0); } while (0)
 #define SK_DMA_B(sb_, j_)                                                                                 \
   do {                                                                                                    \
     __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)((sb_) + SK_A_BYTES + (j_) * 1024), 16, 0, 0); \
@@ -786,15 +861,18 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     a_src[j_] += BK;                                                                                      \
   } while (0)
 
-  // three k-tiles in flight (8 DMA instructions per wave each)
+  // three k-tiles in flight (8 or 9 DMA instructions per wave each); the extended columns'
+  // source addresses arrive last (two dependent table loads), so their requests go last
   if (ntile > 0) SK_DMA(0);
   if (ntile > 1) SK_DMA(1);
   if (ntile > 2) SK_DMA(2);
-  bf16x8 fa0[2], fb0[2], fa1[2], fb1[2];
+  if (ntile > 0) SK_DMA_X(0);
+  if (ntile > 1) SK_DMA_X(1);
+  if (ntile > 2) SK_DMA_X(2);
+  bf16x8 fa0[2], fb0[3], fa1[2], fb1[3];
   if (ntile > 0) {
-    if (ntile > 2) __builtin_amdgcn_s_waitcnt(VMCNT(2 * (4 + SK_NA)));
-    else if (ntile == 2) __builtin_amdgcn_s_waitcnt(VMCNT(4 + SK_NA));
-    else __builtin_amdgcn_s_waitcnt(VMCNT(0));
+    // (all three: the per-tile counting of the loop needs each tile's requests to be adjacent)
+    __builtin_amdgcn_s_waitcnt(VMCNT(0));
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #ifdef EXP_TIMING_SK
     SKSTAMP(1); c_loop = clock64();
@@ -808,7 +886,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
   do {                                                                                                    \
     SK_MMA1(ua_, ub_, 0, 0);                                                                              \
     SK_READ(base_, ks_, la_, lb_);                                                                        \
-    SK_MMA1(ua_, ub_, 0, 1); SK_MMA1(ua_, ub_, 1, 1); SK_MMA1(ua_, ub_, 1, 0);                            \
+    SK_MMA1(ua_, ub_, 0, 1); SK_MMA1(ua_, ub_, 1, 1); SK_MMA1(ua_, ub_, 1, 0); SK_MMAX(ua_, ub_);         \
   } while (0)
   // steady state: tile kt + 3 is requested during tile kt
   int64_t kt = 0;
@@ -818,7 +896,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
     SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
     // this wave's part of tile kt + 1 has landed (tile kt + 2 may still be in flight) ...
-    __builtin_amdgcn_s_waitcnt(VMCNT(4 + SK_NA));
+    __builtin_amdgcn_s_waitcnt(VMCNT(4 + SK_NA + (EXT ? 1 : 0)));
     // ... everyone's has, and nobody still reads tile kt - 1, whose slot is filled next
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
@@ -836,6 +914,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     SK_DMA_A(sb, 2); SK_DMA_A(sb, 3);
 #endif
     SK_MMA1(fa1, fb1, 1, 0);
+    SK_DMA_X((int)((kt + 3) & (SK_SLOTS - 1)));
+    SK_MMAX(fa1, fb1);
   }
   // drain: the last three tiles are already requested
   for (; kt < ntile; ++kt) {
@@ -885,6 +965,28 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         *(uint4*)(bs + k * 256 + ((lc ^ ((k & 3) << 2)) << 4)) = w;
       }
     }
+    if (EXT) {
+      char* xs = bs + SK_B_BYTES;
+      if (FORM == FORM_NT) {
+        const int lc = tid & 7, row = tid >> 3;             // 32 rows x 8 units
+        int e = tn * SK_BX + row;
+        if (e >= a.n_ext) e = a.n_ext - 1;
+        const ExtCol c = a.ext_cols[e];
+        const AdapterEntry en = a.table[c.t];
+        uint4 w = zero4;
+        if ((k0 + lc * 8) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? en.A : en.B) + (int64_t)c.q * a.Kc + k0 + lc * 8);
+        *(uint4*)(xs + swz_rowk(row, lc)) = w;
+      } else {
+        const int lc = tid & 3, k = tid >> 2;               // 64 k-rows x 4 units
+        int e = tn * SK_BX + lc * 8;
+        if (e >= a.n_ext) e = a.n_ext - 8;
+        const ExtCol c = a.ext_cols[e];
+        const AdapterEntry en = a.table[c.t];
+        uint4 w = zero4;
+        if ((k0 + k) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? en.A : en.B) + (k0 + k) * en.rank + c.q);
+        *(uint4*)(xs + k * 64 + lc * 16) = w;
+      }
+    }
     __syncthreads();
     const int ksteps = (int)((kend - k0 + 15) / 16);
     for (int ks = 0; ks < ksteps; ++ks) kstep(as, bs, ks);
@@ -898,6 +1000,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) part[(int64_t)row * a.ldp + nt * 32] = acc[mt][nt][v];
     }
+  if (EXT) {
+    // this wave's 32 rows (row block 2 wm + wn of the tile) x the tile's 32 extended columns
+    float* up = a.u_part + ((int64_t)ks_idx * a.pm + m0 + wm * 64 + wn * 32) * a.ldu + tn * SK_BX + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) up[(int64_t)(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * a.ldu] = acc_x[v];
+  }
 #ifdef EXP_TIMING_SK
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   SKSTAMP(3);
@@ -929,7 +1037,7 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
   const int64_t n = (int64_t)col * FIN_COLS + 2 * tid;
   const bool active = n < a.Nout;                   // Nout is a multiple of 8
   const int64_t kstride = a.pm * a.ldp;
-  const bool lora_on = ch.t >= 0 && a.U != nullptr;
+  const bool lora_on = ch.t >= 0 && (a.U != nullptr || a.n_ext > 0);
   // A block's run time is a few dependent memory round trips plus the partial-sum traffic, so
   // the loads are requested in the order of their dependence depth: adapter entry, then u and
   // the factor (ranks up to 32 are prefetched into registers), then the partial sums.
@@ -944,10 +1052,34 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
     e = a.table[ch.t];
     L = (const bf16_t*)(a.which ? e.B : e.A);
     const int r = e.rank;
+    if (a.n_ext > 0) {
+      // fused shrink: u = scale * (sum over the splits of this adapter's extended columns)
+      const int roff = a.ext_roff[ch.t];
+      const int64_t ustride = a.pm * a.ldu;
 #pragma unroll
-    for (int i = 0; i < UPT; ++i) {
-      const int j = (tid >> 7) + i * (FIN_THREADS >> 7), q = tid & 127;
-      ureg[i] = (j < ch.nrows && q < r) ? a.U[(int64_t)(ch.row0 + j) * a.r_stride + q] : 0.f;
+      for (int i = 0; i < UPT; ++i) {
+        const int j = (tid >> 7) + i * (FIN_THREADS >> 7), q = tid & 127;
+        float sum = 0.f;
+        if (j < ch.nrows && q < r) {
+          const float* up = a.u_part + (int64_t)(ch.row0 + j) * a.ldu + roff + q;
+          for (int ks0 = 0; ks0 < a.ksplit; ks0 += 4) {
+            float pu[4];
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) pu[ii] = up[(ks0 + ii < a.ksplit ? ks0 + ii : a.ksplit - 1) * ustride];
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) if (ks0 + ii < a.ksplit) sum += pu[ii];
+          }
+          sum *= e.scale;
+          if (col == 0 && a.u_out) a.u_out[(int64_t)(ch.row0 + j) * a.r_stride + q] = sum;
+        }
+        ureg[i] = sum;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < UPT; ++i) {
+        const int j = (tid >> 7) + i * (FIN_THREADS >> 7), q = tid & 127;
+        ureg[i] = (j < ch.nrows && q < r) ? a.U[(int64_t)(ch.row0 + j) * a.r_stride + q] : 0.f;
+      }
     }
     pref = r <= 32 && (FORM == FORM_NN || (r & 7) == 0);
     if (pref && active) {
@@ -1055,42 +1187,42 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
 }
 
 template <int FORM, bool OUT_F32>
-static hipError_t launch_one(const GemmArgs& a, int mode, hipEvent_t u_ready, hipStream_t stream) {
+static hipError_t launch_one(const GemmArgs& a, int mode, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<FORM, OUT_F32>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<FORM>, hipFuncAttributeMaxDynamicSharedMemorySize, SK_LDS);
+    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<FORM, false>, hipFuncAttributeMaxDynamicSharedMemorySize, SK_LDS);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<FORM, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SK_LDS);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int G = a.tiles_m * a.tiles_n;
-  if (u_ready && mode == 0) {       // the GEMM kernel itself reads U
-    hipError_t e = hipStreamWaitEvent(stream, u_ready, 0);
-    if (e != hipSuccess) return e;
-  }
-  if (mode == 2)
-    hipLaunchKernelGGL(gemm_skinny_kernel<FORM>, dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
+  if (mode == 2 && a.n_ext > 0)
+    hipLaunchKernelGGL((gemm_skinny_kernel<FORM, true>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
+  else if (mode == 2)
+    hipLaunchKernelGGL((gemm_skinny_kernel<FORM, false>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
   else
     hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32>), dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || mode == 0) return e;
-  if (u_ready && (e = hipStreamWaitEvent(stream, u_ready, 0)) != hipSuccess) return e;
   const int64_t fin_blocks = ((a.Nout + FIN_COLS - 1) / FIN_COLS) * (int64_t)a.n_chunks;
   hipLaunchKernelGGL((splitk_finish_kernel<FORM, OUT_F32>), dim3((unsigned)fin_blocks), dim3(FIN_THREADS), 0, stream, a);
   return hipGetLastError();
 }
 
 // How a call is tiled.  mode 0: one 256 x 256 workgroup per tile; mode 1: 256 x 256 tiles with
-// the contraction split; mode 2: 256 x 64 tiles with the contraction split (small batches).
-struct GemmPlan { int mode, tiles_m, tiles_n, ksplit; int64_t kchunk, ldp, pm; size_t bytes; };
+// the contraction split; mode 2: 128 x 128 tiles with the contraction split (small batches),
+// which can also carry the shrink as 32 extended columns per column tile.
+struct GemmPlan { int mode, tiles_m, tiles_n, ksplit; int64_t kchunk, ldp, pm, ldu; size_t bytes, u_bytes; };
 
-static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout) {
+static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
   GemmPlan p;
   p.tiles_m = (int)((T + BM - 1) / BM);
   p.tiles_n = (int)((Nout + BN - 1) / BN);
-  p.mode = 0; p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0; p.bytes = 0;
+  p.mode = 0; p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0; p.bytes = 0; p.ldu = 0; p.u_bytes = 0;
   const int64_t G = (int64_t)p.tiles_m * p.tiles_n;
   if (G <= 0 || G > 128) return p;
   int64_t tile_w = BN, tile_h = BM;
@@ -1116,18 +1248,25 @@ static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout) {
   p.ldp = (int64_t)p.tiles_n * tile_w;
   p.pm = (int64_t)p.tiles_m * tile_h;
   p.bytes = (size_t)p.ksplit * p.pm * p.ldp * sizeof(float);
+  if (p.mode == 2 && n_ext > 0 && n_ext <= SK_BX * p.tiles_n) {
+    p.ldu = (int64_t)p.tiles_n * SK_BX;
+    p.u_bytes = (size_t)p.ksplit * p.pm * p.ldu * sizeof(float);
+  }
   return p;
 }
 
-size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout) {
+size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
   if (T <= 0 || Nout <= 0) return 0;
-  return gemm_plan(T, Kc, Nout).bytes;
+  const GemmPlan p = gemm_plan(T, Kc, Nout, n_ext);
+  return p.bytes + p.u_bytes;
 }
 
-bool gemm_expand_in_finish(int64_t T, int64_t Kc, int64_t Nout, size_t partial_bytes) {
-  if (T <= 0 || Nout <= 0) return false;
-  const GemmPlan p = gemm_plan(T, Kc, Nout);
-  return p.mode != 0 && partial_bytes >= p.bytes;
+bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_ext, bool ranks_mult8,
+                          size_t partial_bytes) {
+  if (T <= 0 || Nout <= 0 || n_ext <= 0) return false;
+  if (form == FORM_NN && !ranks_mult8) return false;     // 16-byte DMA units must not straddle adapters
+  const GemmPlan p = gemm_plan(T, Kc, Nout, n_ext);
+  return p.mode == 2 && p.u_bytes > 0 && partial_bytes >= p.bytes + p.u_bytes;
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
@@ -1135,13 +1274,22 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, hipEvent_t u_ready, hipStream_t stream) {
+                            int n_chunks, const GemmFuse* fuse, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   GemmArgs a;
   a.Aop = Aop; a.lda = lda; a.Bop = Bop; a.ldb = ldb; a.T = T; a.Kc = Kc; a.Nout = Nout;
   a.perm = perm; a.seg_off = seg_off; a.n_adapters = n_adapters; a.table = table; a.which = which;
   a.U = U; a.r_stride = r_stride; a.out = out; a.ldo = ldo;
-  GemmPlan p = gemm_plan(T, Kc, Nout);
+  GemmPlan p = gemm_plan(T, Kc, Nout, fuse ? fuse->n_ext : 0);
+  a.ext_cols = nullptr; a.ext_roff = nullptr; a.n_ext = 0; a.u_part = nullptr; a.ldu = 0; a.u_out = nullptr;
+  if (fuse) {
+    // the caller skipped the shrink: the conditions of gemm_can_fuse_shrink() must hold
+    if (!gemm_can_fuse_shrink(form, T, Kc, Nout, fuse->n_ext, fuse->ranks_mult8, partials ? partial_bytes : 0) || chunks == nullptr)
+      return hipErrorInvalidValue;
+    a.ext_cols = fuse->cols; a.ext_roff = fuse->roff; a.n_ext = fuse->n_ext;
+    a.u_part = partials + p.bytes / sizeof(float); a.ldu = p.ldu; a.u_out = fuse->u_out;
+    a.U = nullptr;
+  }
   if (p.mode != 0 && (partials == nullptr || partial_bytes < p.bytes || chunks == nullptr)) {
     // no scratch for partial sums: one 256 x 256 workgroup per tile
     p.mode = 0; p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0;
@@ -1151,8 +1299,8 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.ksplit = p.ksplit; a.kchunk = p.kchunk;
   a.ldp = p.ldp; a.pm = p.pm; a.partials = partials; a.chunks = chunks; a.n_chunks = n_chunks;
   if (form == FORM_NT)
-    return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, u_ready, stream) : launch_one<FORM_NT, false>(a, p.mode, u_ready, stream);
-  return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, u_ready, stream) : launch_one<FORM_NN, false>(a, p.mode, u_ready, stream);
+    return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, stream) : launch_one<FORM_NT, false>(a, p.mode, stream);
+  return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, stream) : launch_one<FORM_NN, false>(a, p.mode, stream);
 }
 
 }  // namespace marlaas
