@@ -68,27 +68,6 @@ struct GemmArgs {
   float* u_out;                 // [T][r_stride] (may be null)
 };
 
-#ifndef EXP_NODMA
-#define EXP_NODMA 0
-#endif
-#ifndef EXP_NOADV
-#define EXP_NOADV 0
-#endif
-#if defined(EXP_TIMING) || defined(EXP_TIMING_SK) || defined(EXP_TIMING_FIN)
-__device__ unsigned long long g_tim[8];
-__device__ long long g_stamps[4096 * 8];   // [block][stamp]: wall clock (10 ns units)
-#endif
-#ifdef EXP_TIMING
-#define TSTAMP(i) do { if (tid == 0) { const long long _t = clock64(); atomicAdd(&g_tim[i], (unsigned long long)(_t - t_prev)); t_prev = _t; } } while (0)
-#define TWAIT_BEGIN() long long _tw0 = 0, _tw1 = 0; do { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); _tw0 = clock64(); } while (0)
-#define TWAIT_MID() do { _tw1 = clock64(); } while (0)
-#define TWAIT_END() do { const long long _tw2 = clock64(); tw_vm += _tw1 - _tw0; tw_bar += _tw2 - _tw1; } while (0)
-#else
-#define TSTAMP(i) do {} while (0)
-#define TWAIT_BEGIN() do {} while (0)
-#define TWAIT_MID() do {} while (0)
-#define TWAIT_END() do {} while (0)
-#endif
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -156,10 +135,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS DMA targets stay scalar
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-#ifdef EXP_TIMING
-  long long t_prev = clock64();
-  long long tw_vm = 0, tw_bar = 0;
-#endif
 
   // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
   // tiles; inside a run, groups of 8 row tiles share their column tiles.
@@ -269,25 +244,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 // s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
 #define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 // raw barrier: LDS traffic of this wave is complete, DMA traffic is tracked by hand with vmcnt
-#ifndef EXP_NOBAR
-#define EXP_NOBAR 0
-#endif
-#if EXP_NOBAR
-#define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory")
-#else
 #define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
-#endif
 
 // one DMA instruction: part j (0..7) of operand `isb_` (0 = A, 1 = B) of the k-tile going to `slot_`
 #define RING_DMA1(slot_, isb_, j_)                                                                        \
   do {                                                                                                    \
     char* _sb = smem + (slot_) * SLOT_BYTES + dma_off + (j_) * 1024;                                      \
     if (isb_) {                                                                                           \
-      if (!EXP_NODMA) __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)(_sb + SLOT_B_OFF), 16, 0, 0); \
-      if (!EXP_NOADV) b_src[j_] += b_step;                                                                \
+      __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)(_sb + SLOT_B_OFF), 16, 0, 0); \
+      b_src[j_] += b_step;                                                                \
     } else {                                                                                              \
-      if (!EXP_NODMA) __builtin_amdgcn_global_load_lds((gptr_t)a_src[j_], (lptr_t)(_sb), 16, 0, 0);       \
-      if (!EXP_NOADV) a_src[j_] += BK;                                                                    \
+      __builtin_amdgcn_global_load_lds((gptr_t)a_src[j_], (lptr_t)(_sb), 16, 0, 0);       \
+      a_src[j_] += BK;                                                                    \
     }                                                                                                     \
   } while (0)
 
@@ -339,11 +307,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     RING_PHASE(fa1, fb1, 1, _slot, 2, fa0, fb0, 0, 0, 0);                                                 \
     RING_PHASE(fa0, fb0, 1, _slot, 3, fa1, fb1, 0, 0, 0);                                                 \
     if (has_next_) {                                                                                      \
-      TWAIT_BEGIN();                                                                                      \
       __builtin_amdgcn_s_waitcnt(VMCNT(0));                                                               \
-      TWAIT_MID();                                                                                        \
       RING_BARRIER();                                                                                     \
-      TWAIT_END();                                                                                        \
     }                                                                                                     \
     RING_PHASE(fa1, fb1, has_next_, _nslot, 0, fa0, fb0, dma_a_, _slot, 0);                               \
   } while (0)
@@ -462,7 +427,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       __builtin_amdgcn_s_waitcnt(VMCNT(0));
     }
     RING_BARRIER();
-    TSTAMP(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) RING_READ1(0, 0, i, fa0, fb0);
     int64_t kt = 0;
@@ -470,10 +434,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     if (kt + 1 < ntile) { RING_TILE(kt, 1, 0, 1); ++kt; }
     RING_TILE(kt, 0, 0, 0);
   }
-  TSTAMP(1);
-#ifdef EXP_TIMING
-  if (tid == 0) { atomicAdd(&g_tim[4], (unsigned long long)tw_vm); atomicAdd(&g_tim[5], (unsigned long long)tw_bar); }
-#endif
   __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
   char* As = smem;                 // one 64-wide A tile
   char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile
@@ -528,36 +488,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     return;
   }
 
-#ifdef EXP_NOEPI
-  {  // timing experiment only: one store per lane keeps the accumulators alive
-    float sum = 0.f;
-    for (int mt = 0; mt < MT; ++mt) for (int nt = 0; nt < NT; ++nt) for (int v = 0; v < 16; ++v) sum += acc[mt][nt][v];
-    const int32_t tok = tok_s[lane];
-    if (tok >= 0) ((bf16_t*)a.out)[(int64_t)tok * a.ldo + n0 + wave] = float_to_bf16_bits(sum);
-    return;
-  }
-#endif
-  TSTAMP(2);
-#ifdef EXP_OLDEPI
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = wm * (MT * 32) + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      const int32_t tok = tok_s[row];
-      if (tok < 0) continue;
-#pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const int64_t col = n0 + wn * (NT * 32) + nt * 32 + (lane & 31);
-        if (col < a.Nout) {
-          if (OUT_F32) ((float*)a.out)[(int64_t)tok * a.ldo + col] = acc[mt][nt][v];
-          else ((bf16_t*)a.out)[(int64_t)tok * a.ldo + col] = float_to_bf16_bits(acc[mt][nt][v]);
-        }
-      }
-    }
-  }
-  return;
-#endif
   // ---- epilogue: each wave turns its accumulators (one column per lane) into rows through a
   // private LDS strip, 32 rows at a time, so that every lane stores 16 contiguous bytes and a
   // row segment of the wave (128 columns) leaves as whole cache lines; rows are scattered back
@@ -594,19 +524,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
   }
-  TSTAMP(3);
 }
 
-#if defined(EXP_TIMING) || defined(EXP_TIMING_SK) || defined(EXP_TIMING_FIN)
-extern "C" int marlaas_debug_stamps(long long* out, int n) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_stamps), sizeof(long long) * n) == hipSuccess ? 0 : -1;
-}
-extern "C" int marlaas_debug_timing(unsigned long long* out8, int reset) {
-  if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(g_tim), sizeof(g_tim)) != hipSuccess) return -1;
-  if (reset) { unsigned long long z[8] = {0}; if (hipMemcpyToSymbol(HIP_SYMBOL(g_tim), z, sizeof z) != hipSuccess) return -1; }
-  return 0;
-}
-#endif
 
 // ---------------------------------------------------------------------------------------------
 // Small batches (decode): the weight is streamed once from HBM and is the dominant traffic.  With
@@ -623,6 +542,7 @@ static constexpr int SK_X_BYTES = SK_BX * BK * 2;         // 4 KB: extended (shr
 static constexpr int SK_SLOT = SK_A_BYTES + SK_B_BYTES + SK_X_BYTES;   // 36 KB
 static constexpr int SK_SLOTS = 4;
 static constexpr int SK_LDS = SK_SLOTS * SK_SLOT + SK_BM * 4;
+#define SK_NI (8 + (EXT ? 1 : 0))   // DMA instructions per wave per k-tile
 
 template <int FORM, bool EXT>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
@@ -632,14 +552,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-#ifdef EXP_TIMING_SK
-  long long t_prev = wall_clock64();
-  const long long t_begin = t_prev;
-  long long c_loop = 0;
-#define SKSTAMP(i) do { if (tid == 0) { const long long _t = wall_clock64(); atomicAdd(&g_tim[i], (unsigned long long)(_t - t_prev)); t_prev = _t; } } while (0)
-#else
-#define SKSTAMP(i) do {} while (0)
-#endif
   int tm, tn, ks_idx;
   {
     // consecutive workgroups of one XCD: the row tiles of one column tile (they share the weight
@@ -744,24 +656,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-#ifdef EXP_SK_NOADVB
-#define SK_BSTEP 0
-#else
-#define SK_BSTEP b_step
-#endif
-#ifdef EXP_SK_NOA
-#define SK_NA 0
-#else
-#define SK_NA 4
-#endif
 #define SK_DMA(slot_)                                                                                     \
   do {                                                                                                    \
     char* _sb = smem + (slot_) * SK_SLOT + wave * 4096;                                                   \
     _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                    \
       __builtin_amdgcn_global_load_lds((gptr_t)b_src[_j], (lptr_t)(_sb + SK_A_BYTES + _j * 1024), 16, 0, 0); \
-      b_src[_j] += SK_BSTEP;                                                                              \
+      b_src[_j] += b_step;                                                                              \
     }                                                                                                     \
-    _Pragma("unroll") for (int _j = 0; _j < SK_NA; ++_j) {                                                \
+    _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                \
       __builtin_amdgcn_global_load_lds((gptr_t)a_src[_j], (lptr_t)(_sb + _j * 1024), 16, 0, 0);           \
       a_src[_j] += BK;                                                                                    \
     }                                                                                                     \
@@ -807,7 +709,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     }
   };
 
-  SKSTAMP(0);
   // One wave per SIMD: nothing but the instruction order hides LDS and DMA latency, so the loop
   // is software-pipelined by hand (sched_barrier pins the order).  Fragments of k-step s + 1 are
   // read while the MFMAs of k-step s run; the wait + barrier for the next k-tile sits before the
@@ -853,7 +754,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #define SK_DMA_B(sb_, j_)                                                                                 \
   do {                                                                                                    \
     __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)((sb_) + SK_A_BYTES + (j_) * 1024), 16, 0, 0); \
-    b_src[j_] += SK_BSTEP;                                                                                \
+    b_src[j_] += b_step;                                                                                \
   } while (0)
 #define SK_DMA_A(sb_, j_)                                                                                 \
   do {                                                                                                    \
@@ -869,71 +770,157 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
   if (ntile > 0) SK_DMA_X(0);
   if (ntile > 1) SK_DMA_X(1);
   if (ntile > 2) SK_DMA_X(2);
-  bf16x8 fa0[2], fb0[3], fa1[2], fb1[3];
-  if (ntile > 0) {
-    // (all three: the per-tile counting of the loop needs each tile's requests to be adjacent)
-    __builtin_amdgcn_s_waitcnt(VMCNT(0));
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#ifdef EXP_TIMING_SK
-    SKSTAMP(1); c_loop = clock64();
-#endif
-    SK_READ(smem, 0, fa0, fb0);
-  }
-  // One k-step: the first MFMA (the compiler's wait for this step's fragments sits before it and
-  // drains the LDS queue, so no younger read may be outstanding here), then the reads of the next
-  // step into the other fragment set, then the remaining three MFMAs.
-#define SK_STEP(ua_, ub_, base_, ks_, la_, lb_)                                                           \
+  if constexpr (FORM == FORM_NT) {
+    // The compiler drains the whole LDS queue before the first use of any LDS result, which with
+    // one wave per SIMD exposes the LDS latency at every k-step.  Here the fragment reads are
+    // inline assembly (the compiler does not see them as pending), issued two k-steps ahead into
+    // four fragment sets, and the waits are written by hand: LDS results return in order, so
+    // "at most 2 x NR reads outstanding" means the set issued two steps ago is complete.
+    constexpr int NR = EXT ? 5 : 4;                 // reads per k-step
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+    uint32_t ra[4], rb[4], rx[4];                   // this lane's fragment addresses in slot 0, per k-step
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      ra[ks] = lds0 + a_off + (((ks * 2 + fk) ^ a_swz) << 4);
+      rb[ks] = lds0 + SK_A_BYTES + b_off + (((ks * 2 + fk) ^ b_swz) << 4);
+      rx[ks] = lds0 + SK_A_BYTES + SK_B_BYTES + x_off + (((ks * 2 + fk) ^ x_swz) << 4);
+    }
+    bf16x8 f0[5], f1[5], f2[5], f3[5];              // a0 a1 b0 b1 x
+#define SKP_READ(so_, ks_, f_)                                                                            \
   do {                                                                                                    \
-    SK_MMA1(ua_, ub_, 0, 0);                                                                              \
-    SK_READ(base_, ks_, la_, lb_);                                                                        \
-    SK_MMA1(ua_, ub_, 0, 1); SK_MMA1(ua_, ub_, 1, 1); SK_MMA1(ua_, ub_, 1, 0); SK_MMAX(ua_, ub_);         \
+    const uint32_t _a = ra[ks_] + (so_), _b = rb[ks_] + (so_);                                            \
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f_[0]) : "v"(_a));                                          \
+    asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(f_[1]) : "v"(_a));                              \
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f_[2]) : "v"(_b));                                          \
+    asm volatile("ds_read_b128 %0, %1 offset:4096" : "=v"(f_[3]) : "v"(_b));                              \
+    if (EXT) { const uint32_t _x = rx[ks_] + (so_); asm volatile("ds_read_b128 %0, %1" : "=v"(f_[4]) : "v"(_x)); } \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
   } while (0)
-  // steady state: tile kt + 3 is requested during tile kt
-  int64_t kt = 0;
-  for (; kt + 3 < ntile; ++kt) {
-    const char* cur = smem + (int)(kt & (SK_SLOTS - 1)) * SK_SLOT;
-    SK_STEP(fa0, fb0, cur, 1, fa1, fb1);
-    SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
-    SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
-    // this wave's part of tile kt + 1 has landed (tile kt + 2 may still be in flight) ...
-    __builtin_amdgcn_s_waitcnt(VMCNT(4 + SK_NA + (EXT ? 1 : 0)));
-    // ... everyone's has, and nobody still reads tile kt - 1, whose slot is filled next
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    char* sb = smem + (int)((kt + 3) & (SK_SLOTS - 1)) * SK_SLOT + wave * 4096;
-    SK_MMA1(fa1, fb1, 0, 0);
-    SK_READ(smem + (int)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT, 0, fa0, fb0);
-    SK_DMA_B(sb, 0); SK_DMA_B(sb, 1); SK_DMA_B(sb, 2);
-    SK_MMA1(fa1, fb1, 0, 1);
-    SK_DMA_B(sb, 3);
-#ifndef EXP_SK_NOA
-    SK_DMA_A(sb, 0); SK_DMA_A(sb, 1);
-#endif
-    SK_MMA1(fa1, fb1, 1, 1);
-#ifndef EXP_SK_NOA
-    SK_DMA_A(sb, 2); SK_DMA_A(sb, 3);
-#endif
-    SK_MMA1(fa1, fb1, 1, 0);
-    SK_DMA_X((int)((kt + 3) & (SK_SLOTS - 1)));
-    SK_MMAX(fa1, fb1);
-  }
-  // drain: the last three tiles are already requested
-  for (; kt < ntile; ++kt) {
-    const char* cur = smem + (int)(kt & (SK_SLOTS - 1)) * SK_SLOT;
-    SK_STEP(fa0, fb0, cur, 1, fa1, fb1);
-    SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
-    SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
-    __builtin_amdgcn_s_waitcnt(VMCNT(0));
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
-    // (after the last tile this reads a stale slot; those fragments are not used)
-    SK_STEP(fa1, fb1, smem + (int)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT, 0, fa0, fb0);
+#define SKP_WAIT(n_) do { asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(n_) : "memory"); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define SKP_MMA1(f_, mt_, nt_)                                                                            \
+  do {                                                                                                    \
+    acc[mt_][nt_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f_[mt_], f_[2 + nt_], acc[mt_][nt_], 0, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);                                                                    \
+  } while (0)
+#define SKP_MMAX(f_)                                                                                      \
+  do {                                                                                                    \
+    if (EXT) {                                                                                            \
+      acc_x = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wn ? f_[1] : f_[0], f_[4], acc_x, 0, 0, 0);          \
+      __builtin_amdgcn_sched_barrier(0);                                                                  \
+    }                                                                                                     \
+  } while (0)
+#define SKP_MMA(f_) do { SKP_MMA1(f_, 0, 0); SKP_MMA1(f_, 0, 1); SKP_MMA1(f_, 1, 1); SKP_MMA1(f_, 1, 0); SKP_MMAX(f_); } while (0)
+    if (ntile > 0) {
+      // (all three tiles: the per-tile counting of the loop needs each tile's requests adjacent)
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+      asm volatile("s_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      SKP_READ(0u, 0, f0);
+      SKP_READ(0u, 1, f1);
+    }
+    int64_t kt = 0;
+    // steady state: tile kt + 3 is requested during tile kt
+    for (; kt + 3 < ntile; ++kt) {
+      const uint32_t so = (uint32_t)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+      const uint32_t sn = (uint32_t)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT;
+      SKP_READ(so, 2, f2); SKP_WAIT(2 * NR); SKP_MMA(f0);
+      SKP_READ(so, 3, f3); SKP_WAIT(2 * NR); SKP_MMA(f1);
+      // this wave's part of tile kt + 1 has landed (tile kt + 2 may still be in flight); after the
+      // barrier everyone's has, and nobody still reads tile kt - 1, whose slot is filled next
+      // (every read of it was waited for before its MFMAs, a tile ago)
+      __builtin_amdgcn_s_waitcnt(VMCNT(SK_NI));
+      asm volatile("s_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      SKP_READ(sn, 0, f0); SKP_WAIT(2 * NR);
+      char* sb = smem + (int)((kt + 3) & (SK_SLOTS - 1)) * SK_SLOT + wave * 4096;
+      SKP_MMA1(f2, 0, 0);
+      SK_DMA_B(sb, 0); SK_DMA_B(sb, 1); SK_DMA_B(sb, 2);
+      SKP_MMA1(f2, 0, 1);
+      SK_DMA_B(sb, 3); SK_DMA_A(sb, 0); SK_DMA_A(sb, 1);
+      SKP_MMA1(f2, 1, 1);
+      SK_DMA_A(sb, 2); SK_DMA_A(sb, 3);
+      SK_DMA_X((int)((kt + 3) & (SK_SLOTS - 1)));
+      SKP_MMA1(f2, 1, 0);
+      SKP_MMAX(f2);
+      SKP_READ(sn, 1, f1); SKP_WAIT(2 * NR); SKP_MMA(f3);
+    }
+    // the last three tiles are already requested
+    for (; kt + 1 < ntile; ++kt) {
+      const uint32_t so = (uint32_t)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+      const uint32_t sn = (uint32_t)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT;
+      SKP_READ(so, 2, f2); SKP_WAIT(2 * NR); SKP_MMA(f0);
+      SKP_READ(so, 3, f3); SKP_WAIT(2 * NR); SKP_MMA(f1);
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+      asm volatile("s_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      SKP_READ(sn, 0, f0); SKP_WAIT(2 * NR); SKP_MMA(f2);
+      SKP_READ(sn, 1, f1); SKP_WAIT(2 * NR); SKP_MMA(f3);
+    }
+    // last tile: nothing follows
+    if (kt < ntile) {
+      const uint32_t so = (uint32_t)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+      SKP_READ(so, 2, f2); SKP_WAIT(2 * NR); SKP_MMA(f0);
+      SKP_READ(so, 3, f3); SKP_WAIT(2 * NR); SKP_MMA(f1);
+      SKP_WAIT(0);
+      SKP_MMA(f2);
+      SKP_MMA(f3);
+    }
+  } else {
+    bf16x8 fa0[2], fb0[3], fa1[2], fb1[3];
+    if (ntile > 0) {
+      // (all three: the per-tile counting of the loop needs each tile's requests to be adjacent)
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      SK_READ(smem, 0, fa0, fb0);
+    }
+    // One k-step: the first MFMA (the compiler's wait for this step's fragments sits before it and
+    // drains the LDS queue, so no younger read may be outstanding here), then the reads of the next
+    // step into the other fragment set, then the remaining three MFMAs.
+#define SK_STEP(ua_, ub_, base_, ks_, la_, lb_)                                                           \
+    do {                                                                                                    \
+      SK_MMA1(ua_, ub_, 0, 0);                                                                              \
+      SK_READ(base_, ks_, la_, lb_);                                                                        \
+      SK_MMA1(ua_, ub_, 0, 1); SK_MMA1(ua_, ub_, 1, 1); SK_MMA1(ua_, ub_, 1, 0); SK_MMAX(ua_, ub_);         \
+    } while (0)
+    // steady state: tile kt + 3 is requested during tile kt
+    int64_t kt = 0;
+    for (; kt + 3 < ntile; ++kt) {
+      const char* cur = smem + (int)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+      SK_STEP(fa0, fb0, cur, 1, fa1, fb1);
+      SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
+      SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
+      // this wave's part of tile kt + 1 has landed (tile kt + 2 may still be in flight) ...
+      __builtin_amdgcn_s_waitcnt(VMCNT(SK_NI));
+      // ... everyone's has, and nobody still reads tile kt - 1, whose slot is filled next
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      char* sb = smem + (int)((kt + 3) & (SK_SLOTS - 1)) * SK_SLOT + wave * 4096;
+      SK_MMA1(fa1, fb1, 0, 0);
+      SK_READ(smem + (int)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT, 0, fa0, fb0);
+      SK_DMA_B(sb, 0); SK_DMA_B(sb, 1); SK_DMA_B(sb, 2);
+      SK_MMA1(fa1, fb1, 0, 1);
+      SK_DMA_B(sb, 3);
+      SK_DMA_A(sb, 0); SK_DMA_A(sb, 1);
+      SK_MMA1(fa1, fb1, 1, 1);
+      SK_DMA_A(sb, 2); SK_DMA_A(sb, 3);
+      SK_MMA1(fa1, fb1, 1, 0);
+      SK_DMA_X((int)((kt + 3) & (SK_SLOTS - 1)));
+      SK_MMAX(fa1, fb1);
+    }
+    // drain: the last three tiles are already requested
+    for (; kt < ntile; ++kt) {
+      const char* cur = smem + (int)(kt & (SK_SLOTS - 1)) * SK_SLOT;
+      SK_STEP(fa0, fb0, cur, 1, fa1, fb1);
+      SK_STEP(fa1, fb1, cur, 2, fa0, fb0);
+      SK_STEP(fa0, fb0, cur, 3, fa1, fb1);
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      // (after the last tile this reads a stale slot; those fragments are not used)
+      SK_STEP(fa1, fb1, smem + (int)((kt + 1) & (SK_SLOTS - 1)) * SK_SLOT, 0, fa0, fb0);
+    }
   }
   __syncthreads();
-#ifdef EXP_TIMING_SK
-  if (tid == 0) atomicAdd(&g_tim[4], (unsigned long long)(clock64() - c_loop));
-#endif
-  SKSTAMP(2);
   // k tail of the last split: one masked tile through registers into slot 0
   if (kbeg + ntile * BK < kend) {
     const int64_t k0 = kbeg + ntile * BK;
@@ -1006,14 +993,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) up[(int64_t)(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * a.ldu] = acc_x[v];
   }
-#ifdef EXP_TIMING_SK
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  SKSTAMP(3);
-  if (tid == 0) {
-    atomicMax(&g_tim[6], (unsigned long long)((1ll << 62) - t_begin));
-    atomicMax(&g_tim[7], (unsigned long long)t_prev);
-  }
-#endif
 }
 
 // Second step of the split-K path: add the partial sums in split order, add the LoRA expand in
