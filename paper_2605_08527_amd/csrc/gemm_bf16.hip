@@ -123,9 +123,14 @@ __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
-      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfr[nt], acc[mt][nt], 0, 0, 0);
+      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
 }
 
+// The MFMAs of this kernel take the weight fragment as their first operand, so a block of the
+// accumulators is the transpose of the output block: lane l holds output row (token)
+// l % 32 and, in accumulator registers 4 g .. 4 g + 3, the four consecutive output columns
+// 8 g + 4 (l / 32) .. + 3.  Four consecutive columns of one row are contiguous in memory, so the
+// results leave in 8- or 16-byte pieces without a transpose through LDS.
 template <int FORM, bool OUT_F32>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -287,7 +292,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 #define RING_PHASE(ua_, ub_, do_ld_, ld_slot_, ld_ks_, la_, lb_, do_dma_, dma_slot_, dma_isb_)            \
   do {                                                                                                    \
     _Pragma("unroll") for (int _i = 0; _i < 16; ++_i) {                                                   \
-      acc[_i >> 2][_i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua_[_i >> 2], ub_[_i & 3],           \
+      acc[_i >> 2][_i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ub_[_i & 3], ua_[_i >> 2],           \
                                                                      acc[_i >> 2][_i & 3], 0, 0, 0);      \
       if ((do_ld_) && _i < 8) RING_READ1(ld_slot_, ld_ks_, _i, la_, lb_);                                 \
       if ((do_dma_) && _i >= 8) RING_DMA1(dma_slot_, dma_isb_, _i - 8);                                   \
@@ -473,40 +478,48 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   }
 
   if (a.ksplit > 1) {
-    // partial sums as plain fp32 rows: [ks][tiles_m * 256][tiles_n * 256]
+    // partial sums as plain fp32 rows: [ks][pm][ldp]
     const int64_t ldp = a.ldp;
-    float* part = a.partials + ((int64_t)ks_idx * a.pm + m0) * ldp + n0;
+    float* part = a.partials + ((int64_t)ks_idx * a.pm + m0 + wm * (MT * 32) + (lane & 31)) * ldp + n0 +
+                  wn * (NT * 32) + 4 * (lane >> 5);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = wm * (MT * 32) + mt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          part[(int64_t)row * ldp + wn * (NT * 32) + nt * 32 + (lane & 31)] = acc[mt][nt][v];
-      }
+        for (int g = 0; g < 4; ++g)
+          *(float4*)(part + (int64_t)(mt * 32) * ldp + nt * 32 + 8 * g) =
+              make_float4(acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2], acc[mt][nt][4 * g + 3]);
     return;
   }
 
-  // ---- epilogue: each wave turns its accumulators (one column per lane) into rows through a
-  // private LDS strip, 32 rows at a time, so that every lane stores 16 contiguous bytes and a
-  // row segment of the wave (128 columns) leaves as whole cache lines; rows are scattered back
-  // to token order.  LDS traffic of one wave is ordered, so no workgroup barrier is needed.
+  // ---- epilogue: a lane holds pieces of four consecutive columns of a row; storing those
+  // directly would write every cache line in 8-byte pieces, so each wave regroups 32 rows at a
+  // time through a private LDS strip and every lane stores 16 contiguous bytes: a row segment of
+  // the wave (128 columns) leaves as whole cache lines.  Rows are scattered back to token order.
+  // LDS traffic of one wave is ordered, so no workgroup barrier is needed.
   {
-    constexpr int EPITCH = OUT_F32 ? (128 * 4 + 16) : (128 * 2 + 16);
-    constexpr int ECHUNKS = OUT_F32 ? 32 : 16;          // 16-byte chunks per row segment
+    constexpr int ESZ = OUT_F32 ? 4 : 2;
+    constexpr int EPITCH = 128 * ESZ + 16;
+    constexpr int ECHUNKS = 128 * ESZ / 16;             // 16-byte chunks per row segment
     constexpr int EITERS = 32 * ECHUNKS / 64;
     char* ep = smem + wave * (32 * (128 * 4 + 16));
+    char* ew = ep + (lane & 31) * EPITCH + 4 * (lane >> 5) * ESZ;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row_l = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          const int col_l = nt * 32 + (lane & 31);
-          if (OUT_F32) *(float*)(ep + row_l * EPITCH + col_l * 4) = acc[mt][nt][v];
-          else *(bf16_t*)(ep + row_l * EPITCH + col_l * 2) = float_to_bf16_bits(acc[mt][nt][v]);
+        for (int g = 0; g < 4; ++g) {
+          char* dst = ew + (nt * 32 + 8 * g) * ESZ;
+          if (OUT_F32) {
+            *(float4*)dst = make_float4(acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2], acc[mt][nt][4 * g + 3]);
+          } else {
+            uint2 o;
+            o.x = float_to_bf16_bits(acc[mt][nt][4 * g]) | ((uint32_t)float_to_bf16_bits(acc[mt][nt][4 * g + 1]) << 16);
+            o.y = float_to_bf16_bits(acc[mt][nt][4 * g + 2]) | ((uint32_t)float_to_bf16_bits(acc[mt][nt][4 * g + 3]) << 16);
+            *(uint2*)dst = o;
+          }
         }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
@@ -515,7 +528,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
         const int row_l = c / ECHUNKS, ch = c % ECHUNKS;
         const uint4 val = *(const uint4*)(ep + row_l * EPITCH + ch * 16);
         const int32_t tok = tok_s[wm * (MT * 32) + mt * 32 + row_l];
-        const int64_t col = n0 + wn * (NT * 32) + ch * (OUT_F32 ? 4 : 8);
+        const int64_t col = n0 + wn * (NT * 32) + ch * (16 / ESZ);
         if (tok >= 0 && col < a.Nout) {
           if (OUT_F32) *(uint4*)((float*)a.out + (int64_t)tok * a.ldo + col) = val;
           else *(uint4*)((bf16_t*)a.out + (int64_t)tok * a.ldo + col) = val;

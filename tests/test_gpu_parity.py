@@ -108,6 +108,22 @@ def test_ragged_shapes_and_ranks(oracle, layout):
     _check_layer(oracle, w, bwd=True, tag="ragged")
 
 
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("ranks", [(8, 16, 24, 32), (1, 5, 12, 16, 7), (64, 64)])
+def test_small_batch_paths(oracle, layout, ranks):
+    """Few rows: the GEMM splits the contraction and, when the summed ranks fit its extended
+    columns (and, for operands stored output-contiguous, every rank is a multiple of 8),
+    computes the shrink itself; otherwise the separate shrink kernel runs.  The three rank sets
+    take the fused path in both layouts, in one layout only, and in neither (128 > 96 columns).
+    d_in = 520 leaves a contraction tail, T = 200 a ragged row tile, some rows have no adapter."""
+    rng = np.random.default_rng(21)
+    T = 200
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    w = wl.make_layer(17, T, 520, 384, list(ranks), [1.0 + 0.5 * i for i in range(len(ranks))], ids,
+                      dtype="bf16", layout=layout, want_dY=True)
+    _check_layer(oracle, w, bwd=True, tag="small%s" % (ranks,))
+
+
 def test_no_adapters_and_all_base_tokens(oracle):
     w = wl.make_layer(3, 300, 256, 512, [], [], np.full(300, -1, np.int32), dtype="bf16", want_dY=True)
     L = HipLayer(w, want_bwd=True)
