@@ -316,6 +316,7 @@ extern "C" int64_t marlaas_u_stride(const marlaas_lora_desc* d) {
 
 struct WsPlan {
   size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;   // part: reused by every kernel with partial sums
+  size_t wt_off = 0, wt_bytes = 0;   // transposed copy of the weight (large batches, output-contiguous storage)
 };
 
 static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
@@ -340,6 +341,12 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   }
   p.part_bytes = align_up(part, WS_ALIGN);
   p.part_off = off; off += p.part_bytes;
+  if (d->in_dtype == MARLAAS_BF16) {
+    size_t wt = d->layout == MARLAAS_LAYOUT_MATH ? gemm_wt_bytes(FORM_NN, d->T, d->d_in, d->d_out) : 0;
+    if (want_bwd && d->layout == MARLAAS_LAYOUT_TORCH) wt = gemm_wt_bytes(FORM_NN, d->T, d->d_out, d->d_in);
+    p.wt_bytes = align_up(wt, WS_ALIGN);
+    p.wt_off = off; off += p.wt_bytes;
+  }
   p.total = off;
   return p;
 }
@@ -465,7 +472,8 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
-                                  fused ? &fuse : nullptr, st));
+                                  fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
+                                  p.wt_bytes, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -558,7 +566,8 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
       PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                     out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
-                                    fused ? &fuse : nullptr, st));
+                                    fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
+                                    p.wt_bytes, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));

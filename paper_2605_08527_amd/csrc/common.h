@@ -98,7 +98,12 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, const GemmFuse* fuse, hipStream_t stream);
+                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
+                            hipStream_t stream);
+// Scratch for a transposed copy of the weight: a large batch whose weight is stored
+// [contraction][output] runs faster on a [output][contraction] copy made per call (the copy
+// costs two passes over the weight, the GEMM gains about a quarter).  0: not used for these sizes.
+size_t gemm_wt_bytes(int form, int64_t T, int64_t Kc, int64_t Nout);
 // scratch for partial sums; n_ext = sum of the adapter ranks (0: no adapters)
 size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout, int n_ext);
 // Small batches: the GEMM can compute the shrink itself (as extra output columns over every

@@ -131,7 +131,9 @@ __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks
 // l % 32 and, in accumulator registers 4 g .. 4 g + 3, the four consecutive output columns
 // 8 g + 4 (l / 32) .. + 3.  Four consecutive columns of one row are contiguous in memory, so the
 // results leave in 8- or 16-byte pieces without a transpose through LDS.
-template <int FORM, bool OUT_F32>
+// FORM: storage of the weight operand; LFORM: storage of the adapters' expand factors (they
+// differ when the weight was transposed into scratch for this call).
+template <int FORM, bool OUT_F32, int LFORM = FORM>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int32_t* tok_s = (int32_t*)(smem + RING_SLOTS * SLOT_BYTES);
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
               }
             }
             // B side: L_t stacked twice along the contraction
-            if (FORM == FORM_NT) {
+            if (LFORM == FORM_NT) {
 #pragma unroll
               for (int i = 0; i < LPASS; ++i) {
                 const int64_t n = n0 + lr + LROWS * i;
@@ -402,7 +404,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
               }
               *(uint4*)(La + swz_rowk(lr + LROWS * i, lc)) = pack8(o);
             }
-            if (FORM == FORM_NT) {
+            if (LFORM == FORM_NT) {
 #pragma unroll
               for (int i = 0; i < LPASS; ++i) *(uint4*)(Lb + swz_rowk(lr + LROWS * i, lc)) = lw[i];
             } else {
@@ -413,7 +415,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
             const int left = kext - kc;
             const int ksteps = left >= BK ? 4 : left / 16;
             for (int ks = 0; ks < ksteps; ++ks)
-              mma_kstep<FORM>(La, Lb, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
+              mma_kstep<LFORM>(La, Lb, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
             __syncthreads();
           }
         }
@@ -1178,6 +1180,48 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
   }
 }
 
+// dst[c][r] = src[r][c] for a bf16 matrix of R rows and C columns (both multiples of 8), 64 x 64
+// tiles.  Used to give a large-batch GEMM whose weight is stored output-contiguous the
+// contraction-contiguous form, whose LDS fragment reads are plain 16-byte reads.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, int64_t lds_,
+                                                             bf16_t* __restrict__ dst, int64_t ldd, int64_t R, int64_t C) {
+  __shared__ __attribute__((aligned(16))) bf16_t s[64][72];   // s[c][r]
+  const int tid = threadIdx.x, tx = tid & 7, ty = tid >> 3;
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = ty + 32 * i;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + r < R && c0 + tx * 8 < C) v = *(const uint4*)(src + (r0 + r) * lds_ + c0 + tx * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s[tx * 8 + j][r] = (bf16_t)(w[j >> 1] >> ((j & 1) * 16));
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = ty + 32 * i;
+    if (c0 + c < C && r0 + tx * 8 < R) *(uint4*)(dst + (c0 + c) * ldd + r0 + tx * 8) = *(const uint4*)&s[c][tx * 8];
+  }
+}
+
+// rows of a batch from which transposing the weight into scratch pays for itself
+static constexpr int64_t WT_MIN_ROWS = 4096;
+
+template <int FORM, bool OUT_F32, int LFORM = FORM>
+static hipError_t launch_wide(const GemmArgs& a, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<FORM, OUT_F32, LFORM>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32, LFORM>), dim3(a.tiles_m * a.tiles_n * a.ksplit), dim3(GEMM_THREADS),
+                     GEMM_LDS, stream, a);
+  return hipGetLastError();
+}
+
 template <int FORM, bool OUT_F32>
 static hipError_t launch_one(const GemmArgs& a, int mode, hipStream_t stream) {
   static bool attr_set = false;
@@ -1253,6 +1297,12 @@ size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
   return p.bytes + p.u_bytes;
 }
 
+size_t gemm_wt_bytes(int form, int64_t T, int64_t Kc, int64_t Nout) {
+  if (form != FORM_NN || T < WT_MIN_ROWS || Kc <= 0 || Nout <= 0 || Kc > 65535 * 64) return 0;
+  if (gemm_plan(T, Kc, Nout, 0).mode != 0) return 0;
+  return (size_t)Kc * Nout * sizeof(bf16_t);
+}
+
 bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_ext, bool ranks_mult8,
                           size_t partial_bytes) {
   if (T <= 0 || Nout <= 0 || n_ext <= 0) return false;
@@ -1266,7 +1316,8 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, const GemmFuse* fuse, hipStream_t stream) {
+                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
+                            hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   GemmArgs a;
   a.Aop = Aop; a.lda = lda; a.Bop = Bop; a.ldb = ldb; a.T = T; a.Kc = Kc; a.Nout = Nout;
@@ -1292,6 +1343,16 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   a.ldp = p.ldp; a.pm = p.pm; a.partials = partials; a.chunks = chunks; a.n_chunks = n_chunks;
   if (form == FORM_NT)
     return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, stream) : launch_one<FORM_NT, false>(a, p.mode, stream);
+  if (p.mode == 0 && wt_scratch != nullptr && wt_bytes >= gemm_wt_bytes(form, T, Kc, Nout) && gemm_wt_bytes(form, T, Kc, Nout) > 0) {
+    // large batch, weight stored [Kc][Nout]: transpose it into scratch ([Nout][Kc]) and run the
+    // contraction-contiguous kernel; the adapters' factors keep their storage
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((Nout + 63) / 64), (unsigned)((Kc + 63) / 64)), dim3(256), 0,
+                       stream, Bop, ldb, wt_scratch, Kc, Kc, Nout);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    a.Bop = wt_scratch; a.ldb = Kc;
+    return out_is_f32 ? launch_wide<FORM_NT, true, FORM_NN>(a, stream) : launch_wide<FORM_NT, false, FORM_NN>(a, stream);
+  }
   return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, stream) : launch_one<FORM_NN, false>(a, p.mode, stream);
 }
 
