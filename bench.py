@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--configs", default="1,2,3,4")
     ap.add_argument("--layout", default="torch", choices=["torch", "math"])
     ap.add_argument("--launch", default=None, choices=["graph", "eager"])
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies: a kernel of known HBM traffic for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     ap.add_argument("--rotate", type=int, default=20, help="distinct weight sets cycled in the decode config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -62,6 +65,29 @@ def algorithmic_work(T, K, N, ranks, counts, bwd, out_bytes=2):
     gemm_bwd_flops = 2.0 * T * K * N + 2.0 * tr * K
     return dict(flops=fwd_flops + bwd_flops, bytes=fwd_bytes + bwd_bytes,
                 gemm=dict(flops=(gemm_fwd["flops"] + gemm_bwd_flops) / 2.0, bytes=None), gemm_launches=2)
+
+
+def measured_traffic(cfg, kernel_names):
+    """HBM bytes per launch (fetch + write) of the named kernels, from the committed summary of the
+    rocprofv3 --pmc runs (profiles/hbm_traffic.md); None when the summary has no such row.  Kernels
+    that run once each per launch of the timed span (GEMM + finish) add up; variants of one kernel
+    (forward / backward instantiations) are averaged over their launches."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    total, found = 0.0, False
+    for name in kernel_names:
+        num = den = 0.0
+        for line in open(path):
+            cells = [c.strip() for c in line.split("|")]
+            if len(cells) >= 8 and cells[1] == str(cfg) and name in cells[2]:
+                launches = float(cells[3])
+                num += launches * (float(cells[5]) + float(cells[6]))
+                den += launches
+        if den:
+            total += num / den
+            found = True
+    return total if found else None
 
 
 def device_normal(shape, std, gen, torch):
@@ -196,12 +222,14 @@ def main():
             fused = kern["shrink"]["launches"] == 0
             ach = (work["bytes"] if fused else work["gemm"]["bytes"]) / (g["avg_ms"] * 1e-3) / 1e9
             roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                        traffic=None, kernel="gemm_skinny_kernel + splitk_finish_kernel" + (" (shrink fused)" if fused else ""),
+                        traffic=measured_traffic(1, ["gemm_skinny_kernel", "splitk_finish_kernel"]),
+                        kernel="gemm_skinny_kernel + splitk_finish_kernel" + (" (shrink fused)" if fused else ""),
                         avg_kernel_ms=g["avg_ms"])
         else:
             ach = work["gemm"]["flops"] / (g["avg_ms"] * 1e-3) / 1e12
             roof = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None, kernel="gemm_bf16_kernel",
+                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=measured_traffic(cfg, ["gemm_bf16_kernel"]),
+                        kernel="gemm_bf16_kernel",
                         avg_kernel_ms=g["avg_ms"])
         results[cfg] = dict(
             workload="config %d" % cfg, steps=steps, warmup=warmup, launch=launch, ms_per_step=ms,
@@ -213,6 +241,13 @@ def main():
             kernels={k: v for k, v in kern.items() if v["launches"]}, roofline=roof)
         del case
         torch.cuda.empty_cache()
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     head_cfg = 1 if 1 in results else cfgs[0]
     h = results[head_cfg]
     names = {1: "decode fwd: T=256, 4096x4096, 32 adapters r=16, Zipf(1.2) segments",
