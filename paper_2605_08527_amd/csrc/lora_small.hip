@@ -243,7 +243,6 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
 static constexpr int RD_THREADS = 256;
 static constexpr int RD_COLS = 256;    // columns of X per block (64 per wave)
 static constexpr int RD_TOK = 64;      // tokens staged per step
-static constexpr int RD_VPITCH = RD_TOK * 2 + 16;   // bytes per row of the transposed V tile
 
 struct ReduceArgs {
   const bf16_t* X; int64_t ldx; int64_t C;
@@ -261,12 +260,15 @@ __device__ __forceinline__ int swz_tokc(int tk, int unit) {
   return tk * 512 + ((unit ^ (f << 1)) << 4);
 }
 
-// grid: x = slabs * chunks_max, y = adapter
+// grid: x = slabs * chunks_max, y = adapter.  The kernel is bound by the one pass over X, so the
+// loop is software-pipelined through registers: while a 64-token step is multiplied out of LDS,
+// the X rows and V rows of the next step are already requested (and the gather indices of the
+// step after that), and only the LDS hand-over sits between two barriers.
 template <int OFORM, int NQT>
-__global__ __launch_bounds__(RD_THREADS, 2) void reduce_bf16_kernel(ReduceArgs a) {
+__global__ __launch_bounds__(RD_THREADS, NQT >= 8 ? 1 : 2) void reduce_bf16_kernel(ReduceArgs a) {
   extern __shared__ __attribute__((aligned(16))) char rsm[];
   char* Xs = rsm;                               // [RD_TOK][RD_COLS] bf16, swizzled
-  char* Vt = rsm + RD_TOK * RD_COLS * 2;        // [2][r_pad][RD_VPITCH]: hi, lo, transposed
+  char* Vh = rsm + RD_TOK * RD_COLS * 2;        // [RD_TOK][r_pad] bf16: leading halves of V
   const int t = blockIdx.y;
   const int slab = blockIdx.x % a.slabs, ch = blockIdx.x / a.slabs;
   const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
@@ -276,6 +278,8 @@ __global__ __launch_bounds__(RD_THREADS, 2) void reduce_bf16_kernel(ReduceArgs a
   const int end = (beg + a.tchunk) < hi ? (beg + a.tchunk) : hi;
   const AdapterEntry e = a.table[t];
   const int r = e.rank, r_pad = (r + 15) & ~15, nqt = r_pad >> 4;
+  const int vpitch = r_pad * 2 + 16;            // bytes per token row of a V tile
+  char* Vl = Vh + RD_TOK * vpitch;              // trailing halves (v - bf16(v))
   const int64_t c0 = (int64_t)slab * RD_COLS;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -284,43 +288,76 @@ __global__ __launch_bounds__(RD_THREADS, 2) void reduce_bf16_kernel(ReduceArgs a
   for (int i = 0; i < 4; ++i)
     for (int q = 0; q < NQT; ++q) acc[i][q] = f32x4{0.f, 0.f, 0.f, 0.f};
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  const int xu = tid & 31, xr = tid >> 5;     // X loader: unit along c, token row (+8 per step)
+  const int xu = tid & 31, xr = tid >> 5;     // X loader: unit along c, token row (+8 per pass)
   const bool col_ok = (c0 + xu * 8) < a.C;
-  const int vtok = tid & 63, vq0 = tid >> 6;  // V loader: token, first q (+4 per step)
+  const int vper = r_pad >> 2;                // float4 per V row (first r_pad ranks only)
 
-  for (int s = beg; s < end; s += RD_TOK) {
-    uint4 xv[8];
+  int tokn[8];                                // gather indices of the step after the requested one
+  uint4 xv[8];
+  float4 vv[NQT];
+  auto load_tok = [&](int s) {
+#pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int m = s + xr + 8 * i;
+      tokn[i] = m < end ? (a.perm ? a.perm[m] : m) : -1;
+    }
+  };
+  auto load_step = [&](int s) {               // uses tokn (already arrived)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
       xv[i] = zero4;
-      if (m < end && col_ok) {
-        const int64_t tok = a.perm ? a.perm[m] : m;
-        xv[i] = *(const uint4*)(a.X + tok * a.ldx + c0 + xu * 8);
+      if (tokn[i] >= 0 && col_ok) xv[i] = *(const uint4*)(a.X + (int64_t)tokn[i] * a.ldx + c0 + xu * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < NQT; ++i) {
+      vv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < nqt) {
+        const int f = tid + RD_THREADS * i;   // 64 * vper = 256 * nqt of them
+        const int row = f / vper, c4 = f - row * vper;
+        if (s + row < end) vv[i] = *(const float4*)(a.V + (int64_t)(s + row) * a.r_stride + c4 * 4);
       }
     }
-    __syncthreads();
+  };
+  if (!empty) {
+    load_tok(beg);
+    load_step(beg);
+    load_tok(beg + RD_TOK);
+  }
+  for (int s = beg; s < end; s += RD_TOK) {
+    __syncthreads();                          // the previous step's fragments have been read
+#pragma unroll
     for (int i = 0; i < 8; ++i) *(uint4*)(Xs + swz_tokc(xr + 8 * i, xu)) = xv[i];
-    {
-      const int m = s + vtok;
-      const float* vp = a.V + (int64_t)m * a.r_stride;
-      for (int q = vq0; q < r_pad; q += 4) {
-        const float f = (m < end && q < r) ? vp[q] : 0.f;
-        const bf16_t h = float_to_bf16_bits(f);
-        const bf16_t l = float_to_bf16_bits(f - bf16_bits_to_float(h));
-        *(bf16_t*)(Vt + q * RD_VPITCH + vtok * 2) = h;
-        *(bf16_t*)(Vt + (r_pad + q) * RD_VPITCH + vtok * 2) = l;
+#pragma unroll
+    for (int i = 0; i < NQT; ++i)
+      if (i < nqt) {
+        const int f = tid + RD_THREADS * i;
+        const int row = f / vper, c4 = f - row * vper;
+        const float fv[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+        bf16_t h[4], l[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float x = (c4 * 4 + j) < r ? fv[j] : 0.f;     // ranks beyond r are padding of the row
+          h[j] = float_to_bf16_bits(x);
+          l[j] = float_to_bf16_bits(x - bf16_bits_to_float(h[j]));
+        }
+        *(uint2*)(Vh + row * vpitch + c4 * 8) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+        *(uint2*)(Vl + row * vpitch + c4 * 8) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
       }
-    }
     __syncthreads();
+    if (s + RD_TOK < end) {                   // next step's rows, and the indices of the one after
+      load_step(s + RD_TOK);
+      load_tok(s + 2 * RD_TOK);
+    }
 #pragma unroll
     for (int kstep = 0; kstep < 2; ++kstep) {
+      typedef short4v __attribute__((address_space(3))) * lds_s4;
+      // a 16-lane group g needs tokens kstep*32 + g*8 + 0..7; within it lane li addresses 4
+      // consecutive columns of token row (li >> 2) and receives 4 consecutive tokens of one column
+      const int tk = kstep * 32 + g * 8 + (li >> 2);
       bf16x8 xa[4];
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        // lanes of group g need tokens kstep*32 + g*8 + 0..7 of column wave*64 + ct*16 + li
-        typedef short4v __attribute__((address_space(3))) * lds_s4;
         const int col = wave * 64 + ct * 16 + 4 * (li & 3);
-        const int tk = kstep * 32 + g * 8 + (li >> 2);
         short4v p0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Xs + swz_tokc(tk, col >> 3) + (col & 7) * 2));
         short4v p1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Xs + swz_tokc(tk + 4, col >> 3) + (col & 7) * 2));
         union { short s[8]; bf16x8 v; } u;
@@ -331,9 +368,24 @@ __global__ __launch_bounds__(RD_THREADS, 2) void reduce_bf16_kernel(ReduceArgs a
 #pragma unroll
       for (int qt = 0; qt < NQT; ++qt)
         if (qt < nqt) {
-          const int voff = (kstep * 32 + g * 8) * 2;
-          bf16x8 vh = *(const bf16x8*)(Vt + (qt * 16 + li) * RD_VPITCH + voff);
-          bf16x8 vl = *(const bf16x8*)(Vt + (r_pad + qt * 16 + li) * RD_VPITCH + voff);
+          const int voff = tk * vpitch + (qt * 16 + 4 * (li & 3)) * 2;
+          bf16x8 vh, vl;
+          {
+            short4v p0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Vh + voff));
+            short4v p1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Vh + voff + 4 * vpitch));
+            union { short s[8]; bf16x8 v; } u;
+            u.s[0] = p0[0]; u.s[1] = p0[1]; u.s[2] = p0[2]; u.s[3] = p0[3];
+            u.s[4] = p1[0]; u.s[5] = p1[1]; u.s[6] = p1[2]; u.s[7] = p1[3];
+            vh = u.v;
+          }
+          {
+            short4v p0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Vl + voff));
+            short4v p1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(Vl + voff + 4 * vpitch));
+            union { short s[8]; bf16x8 v; } u;
+            u.s[0] = p0[0]; u.s[1] = p0[1]; u.s[2] = p0[2]; u.s[3] = p0[3];
+            u.s[4] = p1[0]; u.s[5] = p1[1]; u.s[6] = p1[2]; u.s[7] = p1[3];
+            vl = u.v;
+          }
 #pragma unroll
           for (int ct = 0; ct < 4; ++ct) {
             acc[ct][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[ct], vh, acc[ct][qt], 0, 0, 0);
@@ -426,7 +478,7 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
     if (a.tchunk < RD_TOK) a.tchunk = RD_TOK;
   }
   a.partials = partials;
-  const size_t lds = (size_t)RD_TOK * RD_COLS * 2 + (size_t)2 * r_stride * RD_VPITCH;
+  const size_t lds = (size_t)RD_TOK * RD_COLS * 2 + (size_t)2 * RD_TOK * (r_stride * 2 + 16);   // r_stride >= every r_pad
   typedef void (*rkern_t)(ReduceArgs);
   const int nq = r_stride / 16;
   rkern_t kern;
