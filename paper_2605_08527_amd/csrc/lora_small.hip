@@ -24,8 +24,11 @@ struct ShrinkArgs {
 
 // grid: x = row blocks of the largest segment * ksplit, y = adapter
 // NQT: 16-wide output tiles held per wave (covers the largest padded rank of the call)
+// The kernel is bound by the one pass over X, so the loop is software-pipelined through
+// registers: the x fragments and the factor tile of step s + 1 are requested before the MFMAs
+// of step s; only the hand-over of the factor tile to LDS sits between two barriers.
 template <int LFORM, int NQT>
-__global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 2 : 4)) void shrink_bf16_kernel(ShrinkArgs a) {
+__global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 1 : 2)) void shrink_bf16_kernel(ShrinkArgs a) {
   extern __shared__ __attribute__((aligned(16))) char Ls[];   // [r_pad][SH_PITCH]
   const int t = blockIdx.y;
   const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
@@ -51,42 +54,70 @@ __global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 2 : 4)) void shrink_bf16_ke
   f32x4 acc[NQT];
   for (int q = 0; q < NQT; ++q) acc[q] = f32x4{0.f, 0.f, 0.f, 0.f};
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  constexpr int LREG = 2 * NQT;               // 16-byte pieces of the factor tile per thread
+  const bool vec_nn = (r & 7) == 0;           // FORM_NN: a k-row of the factor is whole 16-byte pieces
 
+  uint4 xn[2][4];                             // next step's x fragments
+  uint4 ln[LREG];                             // next step's part of the factor tile
+  // (a macro, not a lambda: the register arrays must not have their address taken)
+#define SH_REQUEST(k0_)                                                                                   \
+  do {                                                                                                    \
+    const int64_t _k0 = (k0_);                                                                            \
+    /* instruction (ms, j) covers 32 consecutive k, 8 per lane group: the four lanes of a row fetch */    \
+    /* 64 contiguous bytes */                                                                             \
+    _Pragma("unroll") for (int ms = 0; ms < 2; ++ms)                                                      \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                     \
+        const int64_t k = _k0 + ms * 128 + j * 32 + g * 8;                                                \
+        xn[ms][j] = zero4;                                                                                \
+        if (k < kend) xn[ms][j] = *(const uint4*)(xrow + k);                                              \
+      }                                                                                                   \
+    if (LFORM == FORM_NT) {          /* L_t[q * C + c]: thread (q = tid / 32 + 8 i, unit = tid % 32) */   \
+      const int64_t k = _k0 + (tid & 31) * 8;                                                             \
+      _Pragma("unroll") for (int i = 0; i < LREG; ++i) {                                                  \
+        const int q = (tid >> 5) + 8 * i;                                                                 \
+        ln[i] = zero4;                                                                                    \
+        if (q < r && k < kend) ln[i] = *(const uint4*)(L + (int64_t)q * a.C + k);                         \
+      }                                                                                                   \
+    } else if (vec_nn) {             /* L_t[c * r + q]: thread = one k, pieces of 8 ranks */              \
+      const int64_t k = _k0 + tid;                                                                        \
+      _Pragma("unroll") for (int i = 0; i < LREG; ++i) {                                                  \
+        ln[i] = zero4;                                                                                    \
+        if (k < kend && i * 8 < r) ln[i] = *(const uint4*)(L + k * r + i * 8);                            \
+      }                                                                                                   \
+    }                                                                                                     \
+  } while (0)
+  SH_REQUEST(kbeg);
   for (int64_t k0 = kbeg; k0 < kend; k0 += SH_KSTG) {
-    // x fragments of this step: instruction (ms, j) covers 32 consecutive k, 8 per lane group,
-    // so the four lanes of a row fetch 64 contiguous bytes
     uint4 xf[2][4];
+#pragma unroll
     for (int ms = 0; ms < 2; ++ms)
-      for (int j = 0; j < 4; ++j) {
-        const int64_t k = k0 + ms * 128 + j * 32 + g * 8;
-        xf[ms][j] = k < kend ? *(const uint4*)(xrow + k) : zero4;
-      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) xf[ms][j] = xn[ms][j];
     __syncthreads();   // previous step's reads of Ls are done
-    if (LFORM == FORM_NT) {          // L_t[q * C + c]
-      const int unit = tid & 31;
-      for (int q = tid >> 5; q < r_pad; q += 8) {
-        const int64_t k = k0 + unit * 8;
-        uint4 v = zero4;
-        if (q < r && k < kend) v = *(const uint4*)(L + (int64_t)q * a.C + k);
-        *(uint4*)(Ls + q * SH_PITCH + unit * 16) = v;
+    if (LFORM == FORM_NT) {
+#pragma unroll
+      for (int i = 0; i < LREG; ++i) {
+        const int q = (tid >> 5) + 8 * i;
+        if (q < r_pad) *(uint4*)(Ls + q * SH_PITCH + (tid & 31) * 16) = ln[i];
       }
-    } else {                          // L_t[c * r + q]
+    } else if (vec_nn) {
+#pragma unroll
+      for (int i = 0; i < LREG; ++i)
+        if (i * 8 < r_pad) {
+          const uint32_t w[4] = {ln[i].x, ln[i].y, ln[i].z, ln[i].w};
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            *(bf16_t*)(Ls + (i * 8 + j) * SH_PITCH + tid * 2) = (bf16_t)(w[j >> 1] >> ((j & 1) * 16));
+        }
+    } else {                          // odd ranks: element-wise, not pipelined
       const int64_t k = k0 + tid;
       const bool ok = k < kend;
       const bf16_t* lp = L + k * r;
-      if ((r & 7) == 0) {
-        for (int q0 = 0; q0 < r_pad; q0 += 8) {
-          uint4 v = (ok && q0 < r) ? *(const uint4*)(lp + q0) : zero4;
-          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-          for (int j = 0; j < 8; ++j)
-            *(bf16_t*)(Ls + (q0 + j) * SH_PITCH + tid * 2) = (bf16_t)(w[j >> 1] >> ((j & 1) * 16));
-        }
-      } else {
-        for (int q = 0; q < r_pad; ++q)
-          *(bf16_t*)(Ls + q * SH_PITCH + tid * 2) = (ok && q < r) ? lp[q] : (bf16_t)0;
-      }
+      for (int q = 0; q < r_pad; ++q)
+        *(bf16_t*)(Ls + q * SH_PITCH + tid * 2) = (ok && q < r) ? lp[q] : (bf16_t)0;
     }
     __syncthreads();
+    if (k0 + SH_KSTG < kend) SH_REQUEST(k0 + SH_KSTG);
 #pragma unroll
     for (int ms = 0; ms < 2; ++ms)
 #pragma unroll
@@ -147,7 +178,8 @@ __global__ __launch_bounds__(64 * SS_WAVES) void shrink_small_nt_kernel(ShrinkAr
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int64_t k = k0 + g * 32 + j * 8;
-      xf[j] = k < kend ? *(const uint4*)(xrow + k) : zero4;
+      xf[j] = zero4;
+      if (k < kend) xf[j] = *(const uint4*)(xrow + k);
     }
 #pragma unroll
     for (int qt = 0; qt < 8; ++qt)
@@ -157,7 +189,8 @@ __global__ __launch_bounds__(64 * SS_WAVES) void shrink_small_nt_kernel(ShrinkAr
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int64_t k = k0 + g * 32 + j * 8;
-          lf[j] = (q < r && k < kend) ? *(const uint4*)(L + (int64_t)q * a.C + k) : zero4;
+          lf[j] = zero4;
+          if (q < r && k < kend) lf[j] = *(const uint4*)(L + (int64_t)q * a.C + k);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -200,7 +233,7 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
   a.which = which; a.u = u; a.r_stride = r_stride;
   const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
-  if (lora_form == FORM_NT && real_blocks < 512) {
+  if (lora_form == FORM_NT && real_blocks <= 96) {
     a.ksplit = 1; a.kchunk = 0;
     const size_t lds = (size_t)SS_WAVES * (r_stride / 16) * 64 * sizeof(f32x4);
     hipLaunchKernelGGL(shrink_small_nt_kernel<0>, dim3((max_seg + 15) / 16, n_adapters), dim3(64 * SS_WAVES), lds,
