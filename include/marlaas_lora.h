@@ -108,9 +108,11 @@ void marlaas_segmap_destroy(marlaas_segmap* map);
 int marlaas_segmap_export(const marlaas_segmap* map, int32_t* perm, int32_t* seg_off);
 
 /*
- * Scratch memory.  The hot path allocates nothing: the caller hands over one
- * device buffer (e.g. a torch tensor) that must stay alive and unused by others
- * while calls on this ctx are in flight.  marlaas_workspace_bytes returns the
+ * Scratch memory.  The caller hands over one device buffer (e.g. a torch
+ * tensor) that must stay alive and unused by others while calls on this ctx
+ * are in flight.  Apart from it the passes only keep small per-adapter tables
+ * (pointers, ranks, scales) on the device: uploaded (hipMalloc + copy) the
+ * first time a table's content is seen, then reused from a cache.  marlaas_workspace_bytes returns the
  * size needed by marlaas_lora_fwd (want_bwd = 0) or by fwd and bwd
  * (want_bwd = 1) for this descriptor (only sizes, ranks, dtypes and map are
  * read), or 0 if the descriptor is invalid.
@@ -127,6 +129,10 @@ int marlaas_set_workspace(marlaas_ctx* ctx, void* dev_ptr, size_t bytes);
  * u_save (nullable): device fp32 [T, marlaas_u_stride(desc)]; receives
  * s_t (x A_t) per token in the grouped order of the map, for reuse by
  * marlaas_lora_bwd (its content is otherwise opaque).
+ * Results do not depend on timing, with one exception: when few tokens carry
+ * adapters and the shrink runs as its own kernel, its contraction is split
+ * over workgroups and summed with fp32 atomics, so u (and what depends on it)
+ * can differ in the last bits between runs.
  */
 int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, void* y, int64_t ldy,
                      void* u_save, void* stream);
@@ -155,7 +161,8 @@ int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, const void
  */
 typedef enum {
   MARLAAS_KERNEL_SHRINK = 1,  /* u = s_t x A_t  /  v = s_t dY B_t^T */
-  MARLAAS_KERNEL_GEMM = 2,    /* base product with the fused expand */
+  MARLAAS_KERNEL_GEMM = 2,    /* base product with the fused expand (small batches: also the shrink,
+                                 the split-K finish kernel and no separate SHRINK span) */
   MARLAAS_KERNEL_REDUCE = 3   /* dA_t / dB_t reductions */
 } marlaas_kernel;
 int marlaas_profile_enable(marlaas_ctx* ctx, int on);
