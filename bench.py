@@ -140,7 +140,7 @@ def one_step(case, i, api):
         api.marlaas_lora_fwd(case["ctx"], s["desc"], case["y"])
 
 
-def time_case(case, steps, warmup, launch, torch, api):
+def time_case(case, steps, warmup, launch, torch, api, profile=True):
     for i in range(warmup):
         one_step(case, i, api)
     torch.cuda.synchronize()
@@ -162,6 +162,8 @@ def time_case(case, steps, warmup, launch, torch, api):
             one_step(case, i, api)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
+    if not profile:
+        return wall_ms / steps, None
     # per-kernel durations: a second pass of the same steps with every launch bracketed by events
     api.marlaas_profile_enable(case["ctx"], True)
     for i in range(steps):
@@ -214,6 +216,23 @@ def main():
         launch = args.launch or ("graph" if cfg == 1 else "eager")
         case = build_case(cfg, args, torch, api, wl)
         ms, kern = time_case(case, steps, warmup, launch, torch, api)
+        extra = {}
+        if cfg == 1 and len(case["sets"]) > 1:
+            # the same steps on one weight set only: everything stays in the memory-side cache
+            hot = dict(case, sets=case["sets"][:1])
+            extra["hot_cache_ms_per_step"] = time_case(hot, steps, warmup, launch, torch, api, profile=False)[0]
+        if cfg == 4:
+            # the timed steps reuse a prebuilt segment map; building it (three small kernels and a
+            # read-back of the offsets) costs this much per batch
+            ids_dev = torch.from_numpy(case["ids"]).cuda()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                m = api.marlaas_segmap_build(case["ctx"], ids_dev, case["n"])
+                del m
+            torch.cuda.synchronize()
+            extra["segmap_build_ms"] = (time.perf_counter() - t0) * 1e3 / 10
+            extra["ms_per_step_with_segmap_build"] = ms + extra["segmap_build_ms"]
         work = algorithmic_work(case["T"], case["K"], case["N"], case["ranks"], case["counts"], case["bwd"])
         g = kern["gemm"]
         if cfg == 1:
@@ -238,7 +257,7 @@ def main():
             frac_mfma_peak=work["flops"] / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
             frac_hbm_peak=work["bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             T=case["T"], d_in=case["K"], d_out=case["N"], n_adapters=case["n"],
-            kernels={k: v for k, v in kern.items() if v["launches"]}, roofline=roof)
+            kernels={k: v for k, v in kern.items() if v["launches"]}, roofline=roof, **extra)
         del case
         torch.cuda.empty_cache()
     if args.calibrate_copy:
