@@ -46,3 +46,31 @@ def test_full_size_sampled(oracle, cfg, n_extra, adapters):
             assert_close(to_host(dA[t]), dA_ref[s].T, "cfg%d dA[%d]" % (cfg, t))
             assert_close(to_host(dB[t]), dB_ref[s].T, "cfg%d dB[%d]" % (cfg, t))
         assert all(bool(torch.isfinite(g).all()) for g in dA + dB)
+
+
+@pytest.mark.parametrize("layout", [wl.MATH, wl.TORCH])
+def test_partial_last_round_of_tiles(oracle, layout):
+    """17 x 16 = 272 tiles of 256 x 256: one more than a full round of workgroups, the last row
+    tile holding the end of the grouped order (the last adapters and the rows without an
+    adapter).  Forward and backward, both layouts (one of which transposes the weight into
+    scratch at this size), fp32 outputs, sampled rows."""
+    rng = np.random.default_rng(31)
+    T, K, N, ranks = 4352, 1024, 4096, [16, 8, 32, 16, 24, 16]
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    w = wl.make_layer(23, T, K, N, ranks, [2.0, 1.0, 0.5, 2.0, 1.0, 0.5], ids, dtype="bf16", layout=layout, want_dY=True)
+    L = HipLayer(w, out_dtype=torch.float32, want_bwd=True)
+    rows = _sample_rows(ids, 64, 7)
+    rows_t = torch.from_numpy(rows).cuda()
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    y, u = L.fwd(save_u=True)
+    assert_close(to_host(y[rows_t]), oracle.fwd(*args, layout=layout, rows=rows), "tail y")
+    assert bool(torch.isfinite(y).all())
+    dX, dA, dB = L.bwd(u_saved=u)
+    sel = [0, 5]
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=layout, rows=rows, adapters=sel)
+    assert_close(to_host(dX[rows_t]), dX_ref, "tail dX")
+    assert bool(torch.isfinite(dX).all())
+    for s, t in enumerate(sel):
+        ga, gb = (dA_ref[s].T, dB_ref[s].T) if layout == wl.TORCH else (dA_ref[s], dB_ref[s])
+        assert_close(to_host(dA[t]), ga, "tail dA[%d]" % t)
+        assert_close(to_host(dB[t]), gb, "tail dB[%d]" % t)
