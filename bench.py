@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--configs", default="1,2,3,4")
     ap.add_argument("--layout", default="torch", choices=["torch", "math"])
     ap.add_argument("--launch", default=None, choices=["graph", "eager"])
+    ap.add_argument("--no-vendor-reference", action="store_true",
+                    help="skip timing torch.mm (the vendor GEMM library) on the base product x W of each workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies: a kernel of known HBM traffic for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -178,6 +180,40 @@ def time_case(case, steps, warmup, launch, torch, api, profile=True):
     return wall_ms / steps, kern
 
 
+def vendor_reference(case, steps, warmup, launch, torch):
+    """Context, not part of the product path: the base product alone (no adapters) through torch.mm,
+    i.e. the vendor GEMM library, on the same operands and with the same launch mode.  For
+    forward + backward workloads: x W and dY W^T."""
+    sets = case["sets"]
+    y = case["y"]
+    tl = case["layout"] == 1           # torch layout: W[d_out, d_in]
+
+    def step(i):
+        s = sets[i % len(sets)]
+        torch.mm(s["x"], s["W"].t() if tl else s["W"], out=y)
+        if case["bwd"]:
+            torch.mm(case["dY"], s["W"] if tl else s["W"].t(), out=case["dX"])
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    graph = None
+    if launch == "graph":
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(steps):
+                step(i)
+        graph.replay()
+        torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(steps):
+            step(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def cpu_baseline_decode(args, wl):
     """The fp64 oracle, as it stands, on the full decode configuration."""
     from oracle import lora_oracle
@@ -217,6 +253,8 @@ def main():
         case = build_case(cfg, args, torch, api, wl)
         ms, kern = time_case(case, steps, warmup, launch, torch, api)
         extra = {}
+        if not args.no_vendor_reference:
+            extra["vendor_base_gemm_only_ms_per_step"] = vendor_reference(case, steps, warmup, launch, torch)
         if cfg == 1 and len(case["sets"]) > 1:
             # the same steps on one weight set only: everything stays in the memory-side cache
             hot = dict(case, sets=case["sets"][:1])
@@ -285,6 +323,9 @@ def main():
     }
     if not args.no_cpu_baseline and head_cfg == 1:
         line["cpu_baseline"] = cpu_baseline_decode(args, wl)
+    for k in ("vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step"):
+        if k in h:
+            line[k] = h[k]
     line["others"] = [dict(results[c], workload=names[c]) for c in cfgs if c != head_cfg]
     line["kernels"] = h["kernels"]
     print(json.dumps(line))
