@@ -124,6 +124,55 @@ def test_small_batch_paths(oracle, layout, ranks):
     _check_layer(oracle, w, bwd=True, tag="small%s" % (ranks,))
 
 
+def _padded(t, pad):
+    """The same values as a view into a wider row-major buffer (leading dimension = width + pad)."""
+    buf = torch.full((t.shape[0], t.shape[1] + pad), float("nan"), dtype=t.dtype, device=t.device)
+    buf[:, :t.shape[1]] = t
+    return buf[:, :t.shape[1]]
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("T", [96, 1500])
+def test_padded_leading_dimensions(oracle, layout, T):
+    """x, W, dY, y and dX as views into wider buffers (leading dimensions larger than the row
+    length, padding filled with NaN): T = 96 takes the small-batch kernels, T = 1500 the 256 x 256
+    kernel with split contraction."""
+    rng = np.random.default_rng(9)
+    ranks = [16, 8, 32]
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    w = wl.make_layer(29, T, 328, 1032, ranks, [2.0, 1.0, 0.5], ids, dtype="bf16", layout=layout, want_dY=True)
+    y_ref, dX_ref, dA_ref, dB_ref = _oracle_all(oracle, w, True)
+    L = HipLayer(w, want_bwd=True)
+    L.x, L.W, L.dY = _padded(L.x, 24), _padded(L.W, 8), _padded(L.dY, 40)
+    L.desc = api.LoraDesc(L.x, L.W, L.A, L.B, w["ranks"], w["scales"], L.map, layout=layout, out_dtype=torch.float32)
+    ybuf = torch.full((T, L.N + 16), float("nan"), dtype=torch.float32, device="cuda")
+    dxbuf = torch.full((T, L.K + 8), float("nan"), dtype=torch.float32, device="cuda")
+    y, dX = ybuf[:, :L.N], dxbuf[:, :L.K]
+    dA = [torch.full(tuple(a.shape), float("nan"), dtype=torch.float32, device="cuda") for a in L.A]
+    dB = [torch.full(tuple(b.shape), float("nan"), dtype=torch.float32, device="cuda") for b in L.B]
+    api.marlaas_lora_fwd(L.ctx, L.desc, y)
+    api.marlaas_lora_bwd(L.ctx, L.desc, L.dY, dX=dX, dA=dA, dB=dB)
+    torch.cuda.synchronize()
+    assert_close(to_host(y.contiguous()), y_ref, "ld y")
+    assert_close(to_host(dX.contiguous()), dX_ref, "ld dX")
+    assert bool(torch.isnan(ybuf[:, L.N:]).all()) and bool(torch.isnan(dxbuf[:, L.K:]).all())   # padding untouched
+    for t in range(L.n):
+        assert_close(to_host(dA[t]), dA_ref[t], "ld dA[%d]" % t)
+        assert_close(to_host(dB[t]), dB_ref[t], "ld dB[%d]" % t)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_many_adapters_few_tokens_each(oracle, layout):
+    """300 adapters (ranks 4, 8, 12, 16 in turn) over 700 tokens: most segments hold one to four
+    tokens, some adapters none; exercises the per-adapter grids and the row-chunk list."""
+    rng = np.random.default_rng(41)
+    n, T = 300, 700
+    ranks = [4 * (1 + t % 4) for t in range(n)]
+    ids = rng.integers(-1, n, size=T).astype(np.int32)
+    w = wl.make_layer(37, T, 256, 384, ranks, [1.0 + (t % 3) for t in range(n)], ids, dtype="bf16", layout=layout, want_dY=True)
+    _check_layer(oracle, w, bwd=True, tag="n300")
+
+
 def test_no_adapters_and_all_base_tokens(oracle):
     w = wl.make_layer(3, 300, 256, 512, [], [], np.full(300, -1, np.int32), dtype="bf16", want_dY=True)
     L = HipLayer(w, want_bwd=True)
