@@ -611,22 +611,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
 
-  if (tid < SK_BM) {
-    const int64_t m = m0 + tid;
-    tok_s[tid] = m < a.T ? (a.perm ? a.perm[m] : (int32_t)m) : -1;
-  }
-  __syncthreads();
-
-  // DMA sources: 4 instructions (1 KB each) per wave per operand per k-tile
+  // DMA sources: 4 instructions (1 KB each) per wave per operand per k-tile.  The weight requests
+  // do not depend on the token indices, so the first three k-tiles of the weight go out before
+  // the indices are even loaded (three k-tiles stay in flight throughout).
   const bf16_t* a_src[4];
   const bf16_t* b_src[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int row = (wave * 4 + j) * 8 + (lane >> 3);
-    const int unit = (lane & 7) ^ ((row >> 1) & 7);
-    const int32_t tok = tok_s[row];
-    a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + kbeg + unit * 8;
     if (FORM == FORM_NT) {           // B tile [128 n][64 k], 128-byte rows
+      const int row = (wave * 4 + j) * 8 + (lane >> 3);
+      const int unit = (lane & 7) ^ ((row >> 1) & 7);
       int64_t n = n0 + row;
       if (n >= a.Nout) n = a.Nout - 1;
       b_src[j] = a.Bop + n * a.ldb + kbeg + unit * 8;
@@ -638,6 +632,37 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     }
   }
   const int64_t b_step = FORM == FORM_NT ? (int64_t)BK : (int64_t)BK * a.ldb;
+#pragma unroll
+  for (int s3 = 0; s3 < 3; ++s3)
+    if (s3 < ntile) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        __builtin_amdgcn_global_load_lds((gptr_t)b_src[j], (lptr_t)(smem + s3 * SK_SLOT + SK_A_BYTES + wave * 4096 + j * 1024), 16, 0, 0);
+        b_src[j] += b_step;
+      }
+    }
+
+  if (tid < SK_BM) {
+    const int64_t m = m0 + tid;
+    tok_s[tid] = m < a.T ? (a.perm ? a.perm[m] : (int32_t)m) : -1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = (wave * 4 + j) * 8 + (lane >> 3);
+    const int unit = (lane & 7) ^ ((row >> 1) & 7);
+    const int32_t tok = tok_s[row];
+    a_src[j] = a.Aop + (int64_t)(tok < 0 ? tok_s[0] : tok) * a.lda + kbeg + unit * 8;
+  }
+#pragma unroll
+  for (int s3 = 0; s3 < 3; ++s3)
+    if (s3 < ntile) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        __builtin_amdgcn_global_load_lds((gptr_t)a_src[j], (lptr_t)(smem + s3 * SK_SLOT + wave * 4096 + j * 1024), 16, 0, 0);
+        a_src[j] += BK;
+      }
+    }
   const int frow = lane & 31, fk = lane >> 5;
   const int a_row = wm * 64 + frow, b_row = wn * 64 + frow;
   const int a_off = a_row * 128, a_swz = (a_row >> 1) & 7;
@@ -671,18 +696,6 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-#define SK_DMA(slot_)                                                                                     \
-  do {                                                                                                    \
-    char* _sb = smem + (slot_) * SK_SLOT + wave * 4096;                                                   \
-    _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                    \
-      __builtin_amdgcn_global_load_lds((gptr_t)b_src[_j], (lptr_t)(_sb + SK_A_BYTES + _j * 1024), 16, 0, 0); \
-      b_src[_j] += b_step;                                                                              \
-    }                                                                                                     \
-    _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                \
-      __builtin_amdgcn_global_load_lds((gptr_t)a_src[_j], (lptr_t)(_sb + _j * 1024), 16, 0, 0);           \
-      a_src[_j] += BK;                                                                                    \
-    }                                                                                                     \
-  } while (0)
 #define SK_DMA_X(slot_)                                                                                   \
   do {                                                                                                    \
     if (EXT) {                                                                                            \
@@ -777,11 +790,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     a_src[j_] += BK;                                                                                      \
   } while (0)
 
-  // three k-tiles in flight (8 or 9 DMA instructions per wave each); the extended columns'
-  // source addresses arrive last (two dependent table loads), so their requests go last
-  if (ntile > 0) SK_DMA(0);
-  if (ntile > 1) SK_DMA(1);
-  if (ntile > 2) SK_DMA(2);
+  // (three k-tiles of A and B are in flight already;) the extended columns' source addresses
+  // arrive last (two dependent table loads), so their requests go last
   if (ntile > 0) SK_DMA_X(0);
   if (ntile > 1) SK_DMA_X(1);
   if (ntile > 2) SK_DMA_X(2);
