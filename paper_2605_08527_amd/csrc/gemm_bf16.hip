@@ -1,26 +1,31 @@
-// Base GEMM on the bf16 matrix cores with the LoRA expand fused in as extra
-// contraction steps:
+// Base GEMM on the bf16 matrix cores with the LoRA expand fused in:
 //
-//   out[tok(m), :] = Aop[tok(m), :] * Bop  +  [u_hi(m) | u_lo(m)] * [L_t ; L_t]
+//   out[tok(m), :] = Aop[tok(m), :] * Bop  +  u(m) * L_t          (m in the segment of adapter t)
 //
 // m runs over tokens grouped by adapter (tok = perm), Bop is the shared frozen
-// base weight (paper Sec. 1 principle (1)), u = s_t * (x A_t) comes from the
-// shrink kernel in fp32 and is split here into two bf16 terms, and L_t is the
-// adapter's output-side factor (B_t in forward, A_t in backward).  Rows of a
-// tile that belong to another adapter are fed zeros for the extra steps, so a
-// tile may straddle any number of segments.
+// base weight (paper Sec. 1 principle (1)), u = s_t * (x A_t) is the fp32 result
+// of the shrink, and L_t is the adapter's output-side factor (B_t in forward,
+// A_t in backward).
 //
-// Tile: 256 x 256 per workgroup of 4 waves (2 x 2), each wave 128 x 128 as
-// 4 x 4 MFMA 32x32x16 accumulators (a large wave tile keeps LDS read traffic,
-// which competes with the DMA writes for LDS bandwidth, under the MFMA rate).
-// The contraction runs in k-tiles of 64 that go from global memory straight
-// into LDS (16 bytes per lane, no register staging; every row segment is one
-// whole 128-byte line, which halves the L2 requests of a 32-wide tile) through
-// two 64 KB slots.  The parts of a k-tile are requested while the previous one
-// is multiplied, at least two MFMA phases before they are needed; the single
-// barrier per k-tile sits before the last phase, so the first fragment reads of
-// the next tile overlap MFMAs.  16-byte units are XOR-swizzled so that DMA
-// writes and fragment reads are bank-conflict free.
+// gemm_bf16_kernel (large batches): the expand enters as extra contraction
+// steps [u_hi | u_lo] * [L_t ; L_t] (u split into two bf16 terms); rows of a
+// tile that belong to another adapter are fed zeros for these steps, so a tile
+// may straddle any number of segments.  Tile: 256 x 256 per workgroup of 4 waves
+// (2 x 2), each wave 128 x 128 as 4 x 4 MFMA 32x32x16 accumulators.  The
+// contraction runs in k-tiles of 64 that go from global memory straight into LDS
+// (16 bytes per lane, no register staging; every row segment is one whole
+// 128-byte line) through two 64 KB slots.  The parts of a k-tile are requested
+// while the previous one is multiplied, at least three MFMA phases before they
+// are needed; the single barrier per k-tile sits before the last phase, so the
+// first fragment reads of the next tile overlap MFMAs.  16-byte units are
+// XOR-swizzled so that DMA writes and fragment reads are bank-conflict free.
+//
+// gemm_skinny_kernel + splitk_finish_kernel (small batches, decode): 128 x 128
+// tiles with the contraction split over workgroups, fp32 partial sums, and the
+// shrink computed by the same kernel as 32 extended columns per column tile;
+// the finish kernel adds the splits, applies the expand in fp32 and scatters
+// the rows.  transpose_bf16_kernel: per-call transposed copy of a weight that
+// is stored output-contiguous, for large batches.
 #include "common.h"
 
 namespace marlaas {
