@@ -221,6 +221,27 @@ def test_hip_graph_replay_matches_eager():
         (L.x.float() @ L.W.float().t()).sum().item()     # unrelated eager work between replays
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_random_shapes(oracle, seed):
+    """Three seeded random problems per seed: T from a list that straddles the tile heights, d_in
+    and d_out any multiples of 8 up to 1272, 0-9 adapters with ranks from 1 to 128, either
+    layout, token order shuffled or grouped; forward and backward (with and without the saved
+    intermediate) against the oracle."""
+    rng = np.random.default_rng(100 + seed)
+    for case in range(3):
+        T = int(rng.choice([1, 2, 7, 16, 63, 64, 65, 128, 200, 257, 511, 900, 1300, 2049]))
+        K, N = 8 * int(rng.integers(1, 160)), 8 * int(rng.integers(1, 160))
+        n = int(rng.integers(0, 10))
+        ranks = [int(rng.choice([1, 3, 4, 8, 16, 24, 32, 40, 64, 128])) for _ in range(n)]
+        scales = [float(rng.choice([0.25, 0.5, 1.0, 2.0])) for _ in range(n)]
+        layout = int(rng.integers(0, 2))
+        ids = rng.integers(-1, max(n, 1), size=T).astype(np.int32) if n else np.full(T, -1, np.int32)
+        if rng.random() < 0.3:
+            ids = np.sort(ids)
+        w = wl.make_layer(1000 * seed + case, T, K, N, ranks, scales, ids, dtype="bf16", layout=layout, want_dY=True)
+        _check_layer(oracle, w, bwd=True, tag="rand s%d c%d T=%d K=%d N=%d ranks=%s layout=%d" % (seed, case, T, K, N, ranks, layout))
+
+
 def test_no_adapters_and_all_base_tokens(oracle):
     w = wl.make_layer(3, 300, 256, 512, [], [], np.full(300, -1, np.int32), dtype="bf16", want_dY=True)
     L = HipLayer(w, want_bwd=True)
