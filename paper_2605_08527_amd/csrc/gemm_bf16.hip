@@ -28,6 +28,8 @@
 // is stored output-contiguous, for large batches.
 #include "common.h"
 
+#include <atomic>
+
 namespace marlaas {
 
 static constexpr int BM = 256, BN = 256, BK = 64;
@@ -1223,15 +1225,23 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
 // rows of a batch from which transposing the weight into scratch pays for itself
 static constexpr int64_t WT_MIN_ROWS = 4096;
 
+// Raise a kernel's dynamic LDS limit once per device (done: bit i set = device i has it).
+static hipError_t allow_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
 template <int FORM, bool OUT_F32, int LFORM = FORM>
 static hipError_t launch_wide(const GemmArgs& a, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<FORM, OUT_F32, LFORM>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> done{0};
+  hipError_t e0 = allow_lds((const void*)gemm_bf16_kernel<FORM, OUT_F32, LFORM>, GEMM_LDS, done);
+  if (e0 != hipSuccess) return e0;
   hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32, LFORM>), dim3(a.tiles_m * a.tiles_n * a.ksplit), dim3(GEMM_THREADS),
                      GEMM_LDS, stream, a);
   return hipGetLastError();
@@ -1239,17 +1249,11 @@ static hipError_t launch_wide(const GemmArgs& a, hipStream_t stream) {
 
 template <int FORM, bool OUT_F32>
 static hipError_t launch_one(const GemmArgs& a, int mode, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<FORM, OUT_F32>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<FORM, false>, hipFuncAttributeMaxDynamicSharedMemorySize, SK_LDS);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)gemm_skinny_kernel<FORM, true>, hipFuncAttributeMaxDynamicSharedMemorySize, SK_LDS);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> done_wide{0}, done_sk{0}, done_skx{0};
+  hipError_t e0 = allow_lds((const void*)gemm_bf16_kernel<FORM, OUT_F32>, GEMM_LDS, done_wide);
+  if (e0 == hipSuccess) e0 = allow_lds((const void*)gemm_skinny_kernel<FORM, false>, SK_LDS, done_sk);
+  if (e0 == hipSuccess) e0 = allow_lds((const void*)gemm_skinny_kernel<FORM, true>, SK_LDS, done_skx);
+  if (e0 != hipSuccess) return e0;
   const int G = a.tiles_m * a.tiles_n;
   if (mode == 2 && a.n_ext > 0)
     hipLaunchKernelGGL((gemm_skinny_kernel<FORM, true>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
