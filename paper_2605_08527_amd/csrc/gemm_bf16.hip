@@ -1273,41 +1273,72 @@ static hipError_t launch_one(const GemmArgs& a, int mode, hipStream_t stream) {
 // which can also carry the shrink as 32 extended columns per column tile.
 struct GemmPlan { int mode, tiles_m, tiles_n, ksplit; int64_t kchunk, ldp, pm, ldu; size_t bytes, u_bytes; };
 
-static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
+static constexpr int CUS = 256;        // compute units; every GEMM kernel here runs one workgroup on each
+
+// The plan for a given mode and (requested) number of contraction splits.
+static GemmPlan plan_for(int mode, int64_t s, int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
   GemmPlan p;
-  p.tiles_m = (int)((T + BM - 1) / BM);
-  p.tiles_n = (int)((Nout + BN - 1) / BN);
-  p.mode = 0; p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0; p.bytes = 0; p.ldu = 0; p.u_bytes = 0;
-  const int64_t G = (int64_t)p.tiles_m * p.tiles_n;
-  if (G <= 0 || G > 128) return p;
-  int64_t tile_w = BN, tile_h = BM;
-  if (G <= 32) {
-    p.mode = 2; tile_w = SK_BN; tile_h = SK_BM;
-    p.tiles_m = (int)((T + SK_BM - 1) / SK_BM);
-    p.tiles_n = (int)((Nout + SK_BN - 1) / SK_BN);
-  } else {
-    p.mode = 1;
-  }
-  const int64_t Gt = (int64_t)p.tiles_m * p.tiles_n;
-  int64_t s = (256 + Gt - 1) / Gt;                          // enough workgroups for 256 compute units
-  const int64_t min_k = p.mode == 2 ? 256 : 128;            // contraction values per split, at least
-  const int64_t max_s = Kc / min_k > 0 ? Kc / min_k : 1;
-  if (s > max_s) s = max_s;
-  if (s > 32) s = 32;
-  if (s < 1) s = 1;
+  const int64_t tile_h = mode == 2 ? SK_BM : BM, tile_w = mode == 2 ? SK_BN : BN;
+  p.mode = mode;
+  p.tiles_m = (int)((T + tile_h - 1) / tile_h);
+  p.tiles_n = (int)((Nout + tile_w - 1) / tile_w);
+  p.ksplit = 1; p.kchunk = Kc; p.ldp = 0; p.pm = 0; p.bytes = 0; p.ldu = 0; p.u_bytes = 0;
+  if (mode == 0) return p;
   int64_t kc = (Kc + s - 1) / s;
   kc = (kc + BK - 1) / BK * BK;
   p.kchunk = kc;
   p.ksplit = (int)((Kc + kc - 1) / kc);
-  if (p.mode == 1 && p.ksplit == 1) { p.mode = 0; return p; }
   p.ldp = (int64_t)p.tiles_n * tile_w;
   p.pm = (int64_t)p.tiles_m * tile_h;
   p.bytes = (size_t)p.ksplit * p.pm * p.ldp * sizeof(float);
-  if (p.mode == 2 && n_ext > 0 && n_ext <= SK_BX * p.tiles_n) {
+  if (mode == 2 && n_ext > 0 && n_ext <= SK_BX * p.tiles_n) {
     p.ldu = (int64_t)p.tiles_n * SK_BX;
     p.u_bytes = (size_t)p.ksplit * p.pm * p.ldu * sizeof(float);
   }
   return p;
+}
+
+// Estimated run time of a plan in microseconds, from rates measured with one workgroup per
+// compute unit: time per 64-deep k-tile (128 x 128 tiles are bound by the LDS fill rate, less so
+// when fewer than 256 workgroups share it), a fixed cost per round of workgroups, a separate
+// shrink launch where the GEMM does not carry it, and the partial sums written once and read
+// once at about 5 TB/s.  Only the ordering of the candidates matters.
+static double plan_cost(const GemmPlan& p, int n_ext) {
+  const int64_t wgs = (int64_t)p.tiles_m * p.tiles_n * p.ksplit;
+  const int64_t rounds = (wgs + CUS - 1) / CUS;
+  const int64_t ktiles = (p.kchunk + BK - 1) / BK;
+  double us;
+  if (p.mode == 2) {
+    const double share = 0.75 + 0.25 * (wgs < CUS ? (double)wgs / CUS : 1.0);
+    us = (double)rounds * (ktiles * 0.9 * share + 4.5);
+  } else {
+    us = (double)rounds * (ktiles * (p.mode == 1 ? 1.6 : 2.0) + 16.0);
+  }
+  if (n_ext > 0 && p.u_bytes == 0) us += 7.0;
+  if (p.mode != 0) us += 3.5 + 2.0 * (double)(p.bytes + p.u_bytes) / 5.0e6;
+  return us;
+}
+
+static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
+  GemmPlan best = plan_for(0, 1, T, Kc, Nout, n_ext);
+  const int64_t G = (int64_t)best.tiles_m * best.tiles_n;
+  if (G <= 0 || G > CUS / 2) return best;          // at least half a round of 256 x 256 tiles: no split
+  double best_us = plan_cost(best, n_ext);
+  for (int mode = 1; mode <= 2; ++mode) {
+    const int64_t min_k = mode == 2 ? 256 : 128;    // contraction values per split, at least
+    int64_t max_s = Kc / min_k;
+    if (max_s > 32) max_s = 32;
+    int last = 0;
+    for (int64_t s = 1; s <= max_s; ++s) {
+      const GemmPlan p = plan_for(mode, s, T, Kc, Nout, n_ext);
+      if (p.ksplit == last) continue;               // rounding the chunk to whole k-tiles gave the same split
+      last = p.ksplit;
+      if ((int64_t)p.tiles_m * p.tiles_n * p.ksplit > 4 * CUS) break;
+      const double us = plan_cost(p, n_ext);
+      if (us < best_us) { best_us = us; best = p; }
+    }
+  }
+  return best;
 }
 
 size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {

@@ -74,3 +74,33 @@ def test_partial_last_round_of_tiles(oracle, layout):
         ga, gb = (dA_ref[s].T, dB_ref[s].T) if layout == wl.TORCH else (dA_ref[s], dB_ref[s])
         assert_close(to_host(dA[t]), ga, "tail dA[%d]" % t)
         assert_close(to_host(dB[t]), gb, "tail dB[%d]" % t)
+
+
+@pytest.mark.parametrize("layout", [wl.MATH, wl.TORCH])
+@pytest.mark.parametrize("T", [640, 1536])
+def test_mid_size_batches(oracle, layout, T):
+    """Between decode and prefill (a few hundred to a few thousand rows against a 2048 x 4096
+    weight) the planner weighs 128 x 128 tiles with or without a split contraction against
+    256 x 256 tiles with one; at these two sizes the forward and the backward GEMM (whose
+    contraction is twice as deep) end up on different ones.  Zipf-sized segments, sampled rows."""
+    rng = np.random.default_rng(41)
+    K, N, ranks = 2048, 4096, [16] * 12
+    p = 1.0 / np.arange(1, len(ranks) + 1) ** 1.2
+    ids = rng.choice(len(ranks), size=T, p=p / p.sum()).astype(np.int32)
+    w = wl.make_layer(37, T, K, N, ranks, [2.0] * len(ranks), ids, dtype="bf16", layout=layout, want_dY=True)
+    L = HipLayer(w, out_dtype=torch.float32, want_bwd=True)
+    rows = _sample_rows(ids, 48, 11)
+    rows_t = torch.from_numpy(rows).cuda()
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    y, u = L.fwd(save_u=True)
+    assert_close(to_host(y[rows_t]), oracle.fwd(*args, layout=layout, rows=rows), "mid y")
+    assert bool(torch.isfinite(y).all())
+    dX, dA, dB = L.bwd(u_saved=u)
+    sel = [0, len(ranks) - 1]
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=layout, rows=rows, adapters=sel)
+    assert_close(to_host(dX[rows_t]), dX_ref, "mid dX")
+    assert bool(torch.isfinite(dX).all())
+    for s, t in enumerate(sel):
+        ga, gb = (dA_ref[s].T, dB_ref[s].T) if layout == wl.TORCH else (dA_ref[s], dB_ref[s])
+        assert_close(to_host(dA[t]), ga, "mid dA[%d]" % t)
+        assert_close(to_host(dB[t]), gb, "mid dB[%d]" % t)

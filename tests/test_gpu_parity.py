@@ -135,8 +135,8 @@ def _padded(t, pad):
 @pytest.mark.parametrize("T", [96, 1500])
 def test_padded_leading_dimensions(oracle, layout, T):
     """x, W, dY, y and dX as views into wider buffers (leading dimensions larger than the row
-    length, padding filled with NaN): T = 96 takes the small-batch kernels, T = 1500 the 256 x 256
-    kernel with split contraction."""
+    length, padding filled with NaN): one row tile of the small-batch kernel (T = 96) and a dozen
+    (T = 1500)."""
     rng = np.random.default_rng(9)
     ranks = [16, 8, 32]
     ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
