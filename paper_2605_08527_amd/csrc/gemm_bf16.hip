@@ -296,15 +296,17 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   } while (0)
 
 // 16 MFMAs on (ua_, ub_) with, in their shadow, the 8 fragment reads of (ld_slot_, ld_ks_) into
-// (la_, lb_) and 8 DMA instructions; sched_barrier pins this order (one wave per SIMD: nothing
-// else hides the issue latency of LDS and DMA instructions).
+// (la_, lb_) and 8 DMA instructions, one after every other MFMA from the start of the phase (a
+// burst of 8 in the second half of the phase measured 2 % slower: four waves then ask the
+// address unit for 4 KB per 32 cycles, twice what it takes); sched_barrier pins this order (one
+// wave per SIMD: nothing else hides the issue latency of LDS and DMA instructions).
 #define RING_PHASE(ua_, ub_, do_ld_, ld_slot_, ld_ks_, la_, lb_, do_dma_, dma_slot_, dma_isb_)            \
   do {                                                                                                    \
     _Pragma("unroll") for (int _i = 0; _i < 16; ++_i) {                                                   \
       acc[_i >> 2][_i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ub_[_i & 3], ua_[_i >> 2],           \
                                                                      acc[_i >> 2][_i & 3], 0, 0, 0);      \
       if ((do_ld_) && _i < 8) RING_READ1(ld_slot_, ld_ks_, _i, la_, lb_);                                 \
-      if ((do_dma_) && _i >= 8) RING_DMA1(dma_slot_, dma_isb_, _i - 8);                                   \
+      if ((do_dma_) && (_i & 1) == 0) RING_DMA1(dma_slot_, dma_isb_, _i >> 1);                            \
       __builtin_amdgcn_sched_barrier(0);                                                                  \
     }                                                                                                     \
   } while (0)
