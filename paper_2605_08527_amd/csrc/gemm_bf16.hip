@@ -11,7 +11,8 @@
 // steps [u_hi | u_lo] * [L_t ; L_t] (u split into two bf16 terms); rows of a
 // tile that belong to another adapter are fed zeros for these steps, so a tile
 // may straddle any number of segments.  Tile: 256 x 256 per workgroup of 4 waves
-// (2 x 2), each wave 128 x 128 as 4 x 4 MFMA 32x32x16 accumulators.  The
+// (2 x 2), each wave 128 x 128 as 8 x 8 MFMA 16x16x32 accumulators (the same
+// loop with 32x32x16 MFMAs measured 3 to 6 % slower on the large configurations).  The
 // contraction runs in k-tiles of 64 that go from global memory straight into LDS
 // (16 bytes per lane, no register staging; every row segment is one whole
 // 128-byte line) through two 64 KB slots.  The parts of a k-tile are requested
@@ -36,7 +37,7 @@ static constexpr int BM = 256, BN = 256, BK = 64;
 static constexpr int WAVES_M = 2, WAVES_N = 2;             // wave grid inside the tile
 static constexpr int NWAVES = WAVES_M * WAVES_N;
 static constexpr int GEMM_THREADS = 64 * NWAVES;
-static constexpr int MT = BM / WAVES_M / 32, NT = BN / WAVES_N / 32;   // 32x32 MFMA tiles per wave
+static constexpr int MT = BM / WAVES_M / 16, NT = BN / WAVES_N / 16;   // 16x16 MFMA tiles per wave (8 x 8)
 static constexpr int DPW = 32 / NWAVES;                    // DMA instructions per wave, operand and k-tile
 static constexpr int LROWS = GEMM_THREADS / 8;             // rows per pass of the register-staged loaders
 static constexpr int LPASS = BM / LROWS;
@@ -83,8 +84,9 @@ __device__ __forceinline__ int swz_rowk(int row, int unit) {
   return row * 128 + ((unit ^ ((row >> 1) & 7)) << 4);
 }
 // LDS byte offset of 16-byte unit `unit` (of 32) of k-row `k` in a [64][256] bf16 tile.
+__device__ __forceinline__ int kn_swz(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 __device__ __forceinline__ int swz_kn(int k, int unit) {
-  return k * 512 + ((unit ^ ((k & 3) << 2)) << 4);
+  return k * 512 + ((unit ^ kn_swz(k)) << 4);
 }
 
 // 8 consecutive contraction values of one column from a [k][n] tile: two
@@ -106,23 +108,23 @@ __device__ __forceinline__ uint4 pack8(const bf16_t* o) {
   return pk;
 }
 
-// One 16-wide contraction step of the wave's block from a 64-wide LDS tile pair (as, bs).
+// One 32-wide contraction step of the wave's block from a 64-wide LDS tile pair (as, bs).
 template <int FORM>
 __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks, int a_off_row,
-                                          int a_swz, int fk, int b_off_row, int b_swz,
-                                          const int (&btr)[NT], f32x16 (&acc)[MT][NT]) {
+                                          int a_swz, int fg, int b_off_row, int b_swz,
+                                          const int (&btr)[NT], f32x4 (&acc)[MT][NT]) {
   bf16x8 af[MT], bfr[NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
-    af[mt] = *(const bf16x8*)(as + a_off_row + mt * (32 * 128) + (((ks * 2 + fk) ^ a_swz) << 4));
+    af[mt] = *(const bf16x8*)(as + a_off_row + mt * (16 * 128) + (((ks * 4 + fg) ^ a_swz) << 4));
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     if (FORM == FORM_NT) {
-      bfr[nt] = *(const bf16x8*)(bs + b_off_row + nt * (32 * 128) + (((ks * 2 + fk) ^ b_swz) << 4));
+      bfr[nt] = *(const bf16x8*)(bs + b_off_row + nt * (16 * 128) + (((ks * 4 + fg) ^ b_swz) << 4));
     } else {
       // btr[nt]: byte offset of this lane's (k = kb, column) element for ks = 0; a k-step moves
-      // 16 rows down (the swizzle only depends on k & 3, unchanged by steps of 4)
-      const char* p = bs + btr[nt] + ks * (16 * 512);
+      // 32 rows down (the swizzle depends on k & 3 and k & 8 only)
+      const char* p = bs + btr[nt] + ks * (32 * 512);
       bfr[nt] = lds_read_frag_tr(p, p + 4 * 512);
     }
   }
@@ -130,14 +132,13 @@ __device__ __forceinline__ void mma_kstep(const char* as, const char* bs, int ks
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
-      acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
+      acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[nt], af[mt], acc[mt][nt], 0, 0, 0);
 }
 
 // The MFMAs of this kernel take the weight fragment as their first operand, so a block of the
-// accumulators is the transpose of the output block: lane l holds output row (token)
-// l % 32 and, in accumulator registers 4 g .. 4 g + 3, the four consecutive output columns
-// 8 g + 4 (l / 32) .. + 3.  Four consecutive columns of one row are contiguous in memory, so the
-// results leave in 8- or 16-byte pieces without a transpose through LDS.
+// accumulators is the transpose of the output block: in a 16 x 16 block lane l holds output
+// row (token) l % 16 and the four consecutive output columns 4 (l / 16) .. + 3.  Four consecutive
+// columns of one row are contiguous in memory, so the results leave in 8- or 16-byte pieces.
 // FORM: storage of the weight operand; LFORM: storage of the adapters' expand factors (they
 // differ when the weight was transposed into scratch for this call).
 template <int FORM, bool OUT_F32, int LFORM = FORM>
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < DPW; ++j) {
       const int k = (wave * DPW + j) * 2 + (lane >> 5);
-      const int unit = (lane & 31) ^ ((k & 3) << 2);
+      const int unit = (lane & 31) ^ kn_swz(k);
       int64_t n = n0 + unit * 8;
       if (n >= a.Nout) n = a.Nout - 8;
       b_src[j] = a.Bop + (kbeg + k) * a.ldb + n;
@@ -224,36 +225,38 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   }
   const int dma_off = wave * DPW * 1024;   // this wave's first KB inside an operand part of a slot
 
-  // ---- fragment geometry (all tiles are 64 wide)
-  const int frow = lane & 31;          // row inside a 32-row MFMA tile
-  const int fk = lane >> 5;            // which 8-wide half of the 16-wide k step
-  const int a_row = wm * (MT * 32) + frow;
-  const int b_row = wn * (NT * 32) + frow;
+  // ---- fragment geometry (all tiles are 64 wide): 16 rows x 32 contraction values per MFMA
+  // operand, lane l supplies row l % 16, values 8 (l / 16) .. + 7
+  const int frow = lane & 15;          // row inside a 16-row MFMA tile
+  const int fg = lane >> 4;            // which 8-wide quarter of the 32-wide k step
+  const int a_row = wm * (MT * 16) + frow;
+  const int b_row = wn * (NT * 16) + frow;
   const int a_off_row = a_row * 128;
-  const int a_swz = (a_row >> 1) & 7;  // rows 32 apart share the swizzle
+  const int a_swz = (a_row >> 1) & 7;  // rows 16 apart share the swizzle
   const int b_off_row = b_row * 128;
   const int b_swz = (b_row >> 1) & 7;
   int btr[NT];
   {
-    const int g16 = lane >> 4, i16 = lane & 15;
-    const int kb = (g16 >> 1) * 8 + (i16 >> 2);
+    // transposing reads of a [k][n] tile: the 16 lanes of group fg fetch the 4 x 16 block of rows
+    // 8 fg .. + 3 (lane i: row i / 4, columns 4 (i % 4) .. + 3) and each receives its own column
+    const int kb = fg * 8 + (frow >> 2);
     for (int nt = 0; nt < NT; ++nt) {
-      const int ncol = wn * (NT * 32) + nt * 32 + (g16 & 1) * 16 + 4 * (i16 & 3);
+      const int ncol = wn * (NT * 16) + nt * 16 + 4 * (frow & 3);
       btr[nt] = swz_kn(kb, ncol >> 3) + (ncol & 7) * 2;
     }
   }
 
-  f32x16 acc[MT][NT];
+  f32x4 acc[MT][NT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
   const int64_t ntile = (kend - kbeg) / BK;
 
-  static_assert(MT == 4 && NT == 4 && DPW == 8, "the interleaved schedule below is written for 4 x 4 MFMA tiles per wave");
+  static_assert(MT == 8 && NT == 8 && DPW == 8, "the interleaved schedule below is written for 8 x 8 MFMA tiles per wave");
 
 // s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
 #define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
@@ -278,55 +281,65 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) RING_DMA1(slot_, isb_, _j);                        \
   } while (0)
 
-// fragment i (0..3 = A rows, 4..7 = B columns) of k-step ks_ of the k-tile in `slot_`
-#define RING_READ1(slot_, ks_, i_, af_, bf_)                                                              \
+// x fragment (row block mt_) / weight fragment (column block nt_) of k-step ks_ (0, 1) of the
+// k-tile in `slot_`
+#define RING_READ_X(slot_, ks_, mt_, dst_)                                                                \
   do {                                                                                                    \
     const char* _as = smem + (slot_) * SLOT_BYTES;                                                        \
-    const char* _bs = _as + SLOT_B_OFF;                                                                   \
-    if ((i_) < 4) {                                                                                       \
-      af_[(i_) & 3] = *(const bf16x8*)(_as + a_off_row + ((i_) & 3) * (32 * 128) +                        \
-                                       ((((ks_) * 2 + fk) ^ a_swz) << 4));                                \
-    } else if (FORM == FORM_NT) {                                                                         \
-      bf_[(i_) & 3] = *(const bf16x8*)(_bs + b_off_row + ((i_) & 3) * (32 * 128) +                        \
-                                       ((((ks_) * 2 + fk) ^ b_swz) << 4));                                \
+    dst_ = *(const bf16x8*)(_as + a_off_row + (mt_) * (16 * 128) + ((((ks_) * 4 + fg) ^ a_swz) << 4));    \
+  } while (0)
+#define RING_READ_W(slot_, ks_, nt_, dst_)                                                                \
+  do {                                                                                                    \
+    const char* _bs = smem + (slot_) * SLOT_BYTES + SLOT_B_OFF;                                           \
+    if (FORM == FORM_NT) {                                                                                \
+      dst_ = *(const bf16x8*)(_bs + b_off_row + (nt_) * (16 * 128) + ((((ks_) * 4 + fg) ^ b_swz) << 4));  \
     } else {                                                                                              \
-      const char* _p = _bs + btr[(i_) & 3] + (ks_) * (16 * 512);                                          \
-      bf_[(i_) & 3] = lds_read_frag_tr(_p, _p + 4 * 512);                                                 \
+      const char* _p = _bs + btr[nt_] + (ks_) * (32 * 512);                                               \
+      dst_ = lds_read_frag_tr(_p, _p + 4 * 512);                                                          \
     }                                                                                                     \
   } while (0)
 
-// 16 MFMAs on (ua_, ub_) with, in their shadow, the 8 fragment reads of (ld_slot_, ld_ks_) into
-// (la_, lb_) and 8 DMA instructions, one after every other MFMA from the start of the phase (a
-// burst of 8 in the second half of the phase measured 2 % slower: four waves then ask the
-// address unit for 4 KB per 32 cycles, twice what it takes); sched_barrier pins this order (one
-// wave per SIMD: nothing else hides the issue latency of LDS and DMA instructions).
-#define RING_PHASE(ua_, ub_, do_ld_, ld_slot_, ld_ks_, la_, lb_, do_dma_, dma_slot_, dma_isb_)            \
+// One phase: the 32 MFMAs of row blocks 4 h_ .. 4 h_ + 3 (x fragments ux_) against all eight
+// column blocks (weight fragments uw_).  In their shadow, at every other MFMA: up to 4 x fragment
+// reads (row blocks 4 lxh_ .., k-step lxks_ of slot lxslot_, into lx_) and nw_ weight fragment
+// reads (column blocks lwn0_ .., k-step lwks_ of slot lwslot_, into lw_), and the 8 DMA
+// instructions of one operand part at every fourth MFMA.  sched_barrier pins the order (one wave
+// per SIMD: nothing else hides the issue latency of LDS and DMA instructions).
+#define RING_PHASE(h_, ux_, uw_, nx_, lxslot_, lxks_, lxh_, lx_, nw_, lwslot_, lwks_, lwn0_, lw_,          \
+                   do_dma_, dma_slot_, dma_isb_)                                                          \
   do {                                                                                                    \
-    _Pragma("unroll") for (int _i = 0; _i < 16; ++_i) {                                                   \
-      acc[_i >> 2][_i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ub_[_i & 3], ua_[_i >> 2],           \
-                                                                     acc[_i >> 2][_i & 3], 0, 0, 0);      \
-      if ((do_ld_) && _i < 8) RING_READ1(ld_slot_, ld_ks_, _i, la_, lb_);                                 \
-      if ((do_dma_) && (_i & 1) == 0) RING_DMA1(dma_slot_, dma_isb_, _i >> 1);                            \
+    _Pragma("unroll") for (int _i = 0; _i < 32; ++_i) {                                                   \
+      acc[4 * (h_) + (_i >> 3)][_i & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                        \
+          uw_[_i & 7], ux_[_i >> 3], acc[4 * (h_) + (_i >> 3)][_i & 7], 0, 0, 0);                         \
+      if ((_i & 1) == 0) {                                                                                \
+        const int _r = _i >> 1;                                                                           \
+        if (_r < (nx_)) RING_READ_X(lxslot_, lxks_, 4 * (lxh_) + _r, lx_[_r]);                            \
+        else if (_r - (nx_) < (nw_)) RING_READ_W(lwslot_, lwks_, (lwn0_) + _r - (nx_), lw_[(lwn0_) + _r - (nx_)]); \
+      }                                                                                                   \
+      if ((do_dma_) && (_i & 3) == 1) RING_DMA1(dma_slot_, dma_isb_, _i >> 2);                            \
       __builtin_amdgcn_sched_barrier(0);                                                                  \
     }                                                                                                     \
   } while (0)
 
-// One k-tile kt (slot kt & 1), four phases of 16 MFMAs.  Phase 0 also requests the B part of
-// tile kt + 1 (its A part was requested one tile earlier).  Before phase 3 every wave waits for
-// its own DMA (all of tile kt + 1) and meets the others: tile kt + 1 is then complete, and no
-// wave still reads tile kt from LDS (its last fragments are in registers), so phase 3 reads the
-// first fragments of tile kt + 1 and requests the A part of tile kt + 2 into the slot of tile kt.
+// One k-tile kt (slot kt & 1): two 32-wide k-steps, each in two phases (row blocks 0-3, 4-7).
+// x fragments alternate between two sets of four, weight fragments between two sets of eight.
+// Phase 0 also requests the B part of tile kt + 1 (its A part was requested one tile earlier).
+// Before phase 3 every wave waits for its own DMA (all of tile kt + 1) and meets the others: tile
+// kt + 1 is then complete, and no wave still reads tile kt from LDS (its last fragments are in
+// registers), so phase 3 reads the first fragments of tile kt + 1 and requests the A part of tile
+// kt + 2 into the slot of tile kt.
 #define RING_TILE(kt_, dma_b_, dma_a_, has_next_)                                                         \
   do {                                                                                                    \
     const int _slot = (int)((kt_) & 1), _nslot = _slot ^ 1;                                               \
-    RING_PHASE(fa0, fb0, 1, _slot, 1, fa1, fb1, dma_b_, _nslot, 1);                                       \
-    RING_PHASE(fa1, fb1, 1, _slot, 2, fa0, fb0, 0, 0, 0);                                                 \
-    RING_PHASE(fa0, fb0, 1, _slot, 3, fa1, fb1, 0, 0, 0);                                                 \
+    RING_PHASE(0, xa0, wb0, 4, _slot, 0, 1, xa1, 4, _slot, 1, 0, wb1, dma_b_, _nslot, 1);                 \
+    RING_PHASE(1, xa1, wb0, 4, _slot, 1, 0, xa0, 4, _slot, 1, 4, wb1, 0, 0, 0);                           \
+    RING_PHASE(0, xa0, wb1, 4, _slot, 1, 1, xa1, 0, 0, 0, 0, wb0, 0, 0, 0);                               \
     if (has_next_) {                                                                                      \
       __builtin_amdgcn_s_waitcnt(VMCNT(0));                                                               \
       RING_BARRIER();                                                                                     \
     }                                                                                                     \
-    RING_PHASE(fa1, fb1, has_next_, _nslot, 0, fa0, fb0, dma_a_, _slot, 0);                               \
+    RING_PHASE(1, xa1, wb1, (has_next_) ? 4 : 0, _nslot, 0, 0, xa0, (has_next_) ? 8 : 0, _nslot, 0, 0, wb0, \
+               dma_a_, _slot, 0);                                                                         \
   } while (0)
 
   // loader geometry of the register-staged tiles (k tail and LoRA steps)
@@ -422,9 +435,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
             }
             __syncthreads();
             const int left = kext - kc;
-            const int ksteps = left >= BK ? 4 : left / 16;
+            const int ksteps = left >= BK ? 2 : 1;       // kext is a multiple of 32
             for (int ks = 0; ks < ksteps; ++ks)
-              mma_kstep<LFORM>(La, Lb, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
+              mma_kstep<LFORM>(La, Lb, ks, a_off_row, a_swz, fg, b_off_row, b_swz, btr, acc);
             __syncthreads();
           }
         }
@@ -435,7 +448,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   // ---- main loop over full k-tiles
   if (ntile > 0) {
-    bf16x8 fa0[MT], fb0[NT], fa1[MT], fb1[NT];
+    bf16x8 xa0[4], xa1[4], wb0[NT], wb1[NT];
     if (ntile > 1) {
       RING_DMA(1, 0);
       __builtin_amdgcn_s_waitcnt(VMCNT(DPW));     // tile 0 landed, the A part of tile 1 in flight
@@ -444,7 +457,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     }
     RING_BARRIER();
 #pragma unroll
-    for (int i = 0; i < 8; ++i) RING_READ1(0, 0, i, fa0, fb0);
+    for (int i = 0; i < 4; ++i) RING_READ_X(0, 0, i, xa0[i]);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) RING_READ_W(0, 0, i, wb0[i]);
     int64_t kt = 0;
     for (; kt + 2 < ntile; ++kt) RING_TILE(kt, 1, 1, 1);
     if (kt + 1 < ntile) { RING_TILE(kt, 1, 0, 1); ++kt; }
@@ -482,25 +497,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       }
     }
     __syncthreads();
-    const int ksteps = (int)((kend - k0 + 15) / 16);
+    const int ksteps = (int)((kend - k0 + 31) / 32);
     for (int ks = 0; ks < ksteps; ++ks)
-      mma_kstep<FORM>(As, Bs, ks, a_off_row, a_swz, fk, b_off_row, b_swz, btr, acc);
+      mma_kstep<FORM>(As, Bs, ks, a_off_row, a_swz, fg, b_off_row, b_swz, btr, acc);
     __syncthreads();
   }
 
   if (a.ksplit > 1) {
     // partial sums as plain fp32 rows: [ks][pm][ldp]
     const int64_t ldp = a.ldp;
-    float* part = a.partials + ((int64_t)ks_idx * a.pm + m0 + wm * (MT * 32) + (lane & 31)) * ldp + n0 +
-                  wn * (NT * 32) + 4 * (lane >> 5);
+    float* part = a.partials + ((int64_t)ks_idx * a.pm + m0 + wm * (MT * 16) + (lane & 15)) * ldp + n0 +
+                  wn * (NT * 16) + 4 * (lane >> 4);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *(float4*)(part + (int64_t)(mt * 32) * ldp + nt * 32 + 8 * g) =
-              make_float4(acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2], acc[mt][nt][4 * g + 3]);
+        *(float4*)(part + (int64_t)(mt * 16) * ldp + nt * 16) =
+            make_float4(acc[mt][nt][0], acc[mt][nt][1], acc[mt][nt][2], acc[mt][nt][3]);
     return;
   }
 
@@ -515,20 +528,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     constexpr int ECHUNKS = 128 * ESZ / 16;             // 16-byte chunks per row segment
     constexpr int EITERS = 32 * ECHUNKS / 64;
     char* ep = smem + wave * (32 * (128 * 4 + 16));
-    char* ew = ep + (lane & 31) * EPITCH + 4 * (lane >> 5) * ESZ;
+    char* ew = ep + (lane & 15) * EPITCH + 4 * (lane >> 4) * ESZ;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+    for (int mp = 0; mp < MT / 2; ++mp) {            // 32 rows (two row blocks) per pass
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+      for (int mh = 0; mh < 2; ++mh)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          char* dst = ew + (nt * 32 + 8 * g) * ESZ;
+        for (int nt = 0; nt < NT; ++nt) {
+          const f32x4 c = acc[2 * mp + mh][nt];
+          char* dst = ew + mh * (16 * EPITCH) + (nt * 16) * ESZ;
           if (OUT_F32) {
-            *(float4*)dst = make_float4(acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2], acc[mt][nt][4 * g + 3]);
+            *(float4*)dst = make_float4(c[0], c[1], c[2], c[3]);
           } else {
             uint2 o;
-            o.x = float_to_bf16_bits(acc[mt][nt][4 * g]) | ((uint32_t)float_to_bf16_bits(acc[mt][nt][4 * g + 1]) << 16);
-            o.y = float_to_bf16_bits(acc[mt][nt][4 * g + 2]) | ((uint32_t)float_to_bf16_bits(acc[mt][nt][4 * g + 3]) << 16);
+            o.x = float_to_bf16_bits(c[0]) | ((uint32_t)float_to_bf16_bits(c[1]) << 16);
+            o.y = float_to_bf16_bits(c[2]) | ((uint32_t)float_to_bf16_bits(c[3]) << 16);
             *(uint2*)dst = o;
           }
         }
@@ -538,8 +552,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
         const int c = it * 64 + lane;
         const int row_l = c / ECHUNKS, ch = c % ECHUNKS;
         const uint4 val = *(const uint4*)(ep + row_l * EPITCH + ch * 16);
-        const int32_t tok = tok_s[wm * (MT * 32) + mt * 32 + row_l];
-        const int64_t col = n0 + wn * (NT * 32) + ch * (16 / ESZ);
+        const int32_t tok = tok_s[wm * (MT * 16) + mp * 32 + row_l];
+        const int64_t col = n0 + wn * (NT * 16) + ch * (16 / ESZ);
         if (tok >= 0 && col < a.Nout) {
           if (OUT_F32) *(uint4*)((float*)a.out + (int64_t)tok * a.ldo + col) = val;
           else *(uint4*)((bf16_t*)a.out + (int64_t)tok * a.ldo + col) = val;
