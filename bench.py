@@ -12,7 +12,7 @@ region.  The token->adapter map is built once, outside the timed region (a
 serving engine builds it once per batch and reuses it for every layer).
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--configs 1,2,3,4]
-                  [--layout torch|math] [--launch graph|eager] [--no-cpu-baseline]
+                  [--layout torch|math] [--launch graph|eager] [--no-cpu-baseline] [--no-multi-projection]
 """
 import argparse
 import json
@@ -44,6 +44,10 @@ def parse_args():
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     ap.add_argument("--rotate", type=int, default=20, help="distinct weight sets cycled in the decode config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--multi-projection-only", action="store_true",
+                    help="time only the q/k/v multi-projection decode workload and print its line (for profiles)")
+    ap.add_argument("--no-multi-projection", action="store_true",
+                    help="skip the q/k/v multi-projection measurement of the decode configuration")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -214,6 +218,76 @@ def vendor_reference(case, steps, warmup, launch, torch):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def multi_projection_decode(case, args, steps, warmup, torch, api):
+    """The decode batch against a block's q / k / v projections (d_out 4096, 1024, 1024: grouped-query
+    attention of an 8B-class model), each with its own adapters of rank 16: one
+    marlaas_lora_fwd_multi call per step against three marlaas_lora_fwd calls, HIP-graph replay over
+    rotating weight sets like the headline.  Roofline as for the headline: algorithmic bytes of the
+    step over the duration of the one GEMM + finish span."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77 + args.seed)
+    T, K, n, ranks, layout = case["T"], case["K"], case["n"], case["ranks"], case["layout"]
+    Ns = (4096, 1024, 1024)
+    ctx, segmap = case["ctx"], case["segmap"]
+    scales = [2.0] * n
+    sets = []
+    for s in case["sets"][:max(2, len(case["sets"]) // 2)]:
+        projs = []
+        for N in Ns:
+            W = device_normal((N, K) if layout else (K, N), K ** -0.5, gen, torch)
+            A = [device_normal((int(r), K) if layout else (K, int(r)), K ** -0.5, gen, torch) for r in ranks]
+            B = [device_normal((N, int(r)) if layout else (int(r), N), float(r) ** -0.5, gen, torch) for r in ranks]
+            projs.append(dict(W=W, A=A, B=B, desc=api.LoraDesc(s["x"], W, A, B, ranks, scales, segmap, layout=layout,
+                                                              out_dtype=torch.bfloat16)))
+        sets.append(projs)
+    ys = [torch.empty((T, N), dtype=torch.bfloat16, device="cuda") for N in Ns]
+    descs0 = [pr["desc"] for pr in sets[0]]
+    ws = torch.empty(max(api.marlaas_workspace_bytes_multi(descs0), 256), dtype=torch.uint8, device="cuda")
+    old_ws = case["ws"]
+    api.marlaas_set_workspace(ctx, ws)
+
+    def fused_step(i):
+        api.marlaas_lora_fwd_multi(ctx, [pr["desc"] for pr in sets[i % len(sets)]], ys)
+
+    def separate_step(i):
+        for pr, y in zip(sets[i % len(sets)], ys):
+            api.marlaas_lora_fwd(ctx, pr["desc"], y)
+
+    out = {}
+    for name, step in (("fused", fused_step), ("separate", separate_step)):
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(steps):
+                step(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        out[name + "_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
+    api.marlaas_profile_enable(ctx, True)
+    for i in range(steps):
+        fused_step(i)
+    torch.cuda.synchronize()
+    ms, cnt = api.marlaas_profile_read(ctx, api.MARLAAS_KERNEL_GEMM)
+    api.marlaas_profile_enable(ctx, False)
+    api.marlaas_set_workspace(ctx, old_ws)
+    present = case["counts"] > 0
+    nbytes = sum(2.0 * (K * N + 0.0) + 2.0 * T * N + 2.0 * float(np.sum(ranks[present])) * (K + N) for N in Ns) + 2.0 * T * K
+    span_ms = ms / cnt if cnt else None
+    out.update(workload="decode q/k/v: T=%d, %d -> %s, %d adapters r=16 per projection" % (T, K, list(Ns), n),
+               gemm_launches_per_step=cnt / steps, tokens_per_s=T / (out["fused_ms_per_step"] * 1e-3),
+               roofline=dict(bound="hbm", achieved=nbytes / (span_ms * 1e-3) / 1e9 if span_ms else None, peak=HBM_PEAK_GBS,
+                             unit="GB/s", frac=nbytes / (span_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if span_ms else None,
+                             traffic=None, kernel="gemm_skinny_kernel + splitk_finish_kernel (three projections, shrink fused)",
+                             avg_kernel_ms=span_ms))
+    return out
+
+
 def cpu_baseline_decode(args, wl):
     """The fp64 oracle, as it stands, on the full decode configuration."""
     from oracle import lora_oracle
@@ -243,6 +317,20 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cfgs = [int(c) for c in args.configs.split(",") if c]
+    if args.multi_projection_only:
+        steps = args.steps if args.steps is not None else 200
+        warmup = args.warmup if args.warmup is not None else 40
+        case = build_case(1, args, torch, api, wl)
+        m = multi_projection_decode(case, args, steps, warmup, torch, api)
+        print(json.dumps({
+            "metric": "mixed-LoRA layer tokens/s at 32 adapters (with TFLOP/s and % of MFMA / HBM peak)",
+            "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": m["fused_ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": m["workload"], "layout": args.layout, "launch": "graph", "out_dtype": "bf16",
+                       "weight_sets_rotated": max(2, args.rotate // 2), "segmap": "prebuilt, outside the timed region"},
+            "roofline": m["roofline"], "separate_calls_ms_per_step": m["separate_ms_per_step"]}))
+        return
     results = {}
     for cfg in cfgs:
         if cfg not in (1, 2, 3, 4):
@@ -259,6 +347,8 @@ def main():
             # the same steps on one weight set only: everything stays in the memory-side cache
             hot = dict(case, sets=case["sets"][:1])
             extra["hot_cache_ms_per_step"] = time_case(hot, steps, warmup, launch, torch, api, profile=False)[0]
+        if cfg == 1 and not args.no_multi_projection:
+            extra["multi_projection"] = multi_projection_decode(case, args, steps, warmup, torch, api)
         if cfg == 4:
             # the timed steps reuse a prebuilt segment map; building it (three small kernels and a
             # read-back of the offsets) costs this much per batch
@@ -323,7 +413,7 @@ def main():
     }
     if not args.no_cpu_baseline and head_cfg == 1:
         line["cpu_baseline"] = cpu_baseline_decode(args, wl)
-    for k in ("vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step"):
+    for k in ("vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection"):
         if k in h:
             line[k] = h[k]
     line["others"] = [dict(results[c], workload=names[c]) for c in cfgs if c != head_cfg]

@@ -138,6 +138,26 @@ int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, void* y, i
                      void* u_save, void* stream);
 
 /*
+ * Forward of several projections of the same input in one call (a transformer
+ * block's q / k / v, or gate / up: what a rollout engine with multi-LoRA
+ * batching, paper Sec. 1, launches per layer for every decode step):
+ *   y_p[T, d_out_p] = x W_p + s_{t,p} (x A_{t,p}) B_{t,p},   p = 0 .. n_proj - 1.
+ * descs: HOST array of n_proj descriptors that agree in T, d_in, x, ldx, both
+ * dtypes, layout, n_adapters and map; W, d_out, A, B, ranks and scales are per
+ * projection.  y, ldy: HOST arrays of n_proj device pointers / leading
+ * dimensions.  The result is that of n_proj calls of marlaas_lora_fwd (up to
+ * summation order).  Small bf16 batches whose summed ranks fit the GEMM's
+ * extended columns run as ONE GEMM launch over the concatenated columns plus one
+ * finish launch; every other case runs the projections one after the other.
+ * Scratch: marlaas_workspace_bytes_multi(descs, n_proj) bytes set with
+ * marlaas_set_workspace (0 if the descriptors are invalid or disagree).
+ */
+#define MARLAAS_MAX_PROJ 8
+size_t marlaas_workspace_bytes_multi(const marlaas_lora_desc* descs, int32_t n_proj);
+int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc* descs, int32_t n_proj,
+                           void* const* y, const int64_t* ldy, void* stream);
+
+/*
  * Backward for a loss with dL/dy = dY[T, d_out] (in_dtype, leading dimension lddy):
  *   dX[T, d_in] (out_dtype, lddx) = dY W^T + v A_t^T,   v = s_t dY B_t^T
  *   dA_t = sum_{i in seg(t)} x_i^T v_i,   dB_t = s_t sum_{i in seg(t)} (x_i A_t)^T dY_i

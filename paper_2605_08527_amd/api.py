@@ -21,6 +21,7 @@ EXPORTS = [
     "marlaas_create", "marlaas_destroy", "marlaas_strerror", "marlaas_last_error",
     "marlaas_segmap_build", "marlaas_segmap_destroy", "marlaas_segmap_export",
     "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd",
+    "marlaas_workspace_bytes_multi", "marlaas_lora_fwd_multi",
     "marlaas_u_stride", "marlaas_profile_enable", "marlaas_profile_read",
 ]
 MARLAAS_KERNEL_SHRINK, MARLAAS_KERNEL_GEMM, MARLAAS_KERNEL_REDUCE = 1, 2, 3
@@ -74,6 +75,11 @@ def load():
     lib.marlaas_lora_bwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
                                      ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp]
     lib.marlaas_lora_bwd.restype = ctypes.c_int
+    lib.marlaas_workspace_bytes_multi.argtypes = [ctypes.POINTER(marlaas_lora_desc), i32]
+    lib.marlaas_workspace_bytes_multi.restype = ctypes.c_size_t
+    lib.marlaas_lora_fwd_multi.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), i32, ctypes.POINTER(ctypes.c_void_p),
+                                           ctypes.POINTER(i64), vp]
+    lib.marlaas_lora_fwd_multi.restype = ctypes.c_int
     lib.marlaas_u_stride.argtypes = [ctypes.POINTER(marlaas_lora_desc)]
     lib.marlaas_u_stride.restype = i64
     lib.marlaas_profile_enable.argtypes = [vp, ctypes.c_int]
@@ -234,6 +240,25 @@ def marlaas_set_workspace(ctx, tensor):
 def marlaas_lora_fwd(ctx, desc, y, u_save=None, stream=None):
     ldy = y.stride(0) if y.shape[0] > 0 else y.shape[1]
     _check(ctx, load().marlaas_lora_fwd(ctx.handle, desc.ref, _ptr(y), ldy, _ptr(u_save), _stream_ptr(stream)))
+
+
+def _desc_array(descs):
+    arr = (marlaas_lora_desc * len(descs))()
+    for i, d in enumerate(descs):
+        arr[i] = d.c            # plain copy of the struct; the LoraDesc objects keep its host arrays alive
+    return arr
+
+
+def marlaas_workspace_bytes_multi(descs):
+    return int(load().marlaas_workspace_bytes_multi(_desc_array(descs), len(descs)))
+
+
+def marlaas_lora_fwd_multi(ctx, descs, ys, stream=None):
+    """Forward of several projections of one input (same x, map, dtypes, layout): ys[p] receives projection p."""
+    n = len(descs)
+    yp = (ctypes.c_void_p * n)(*[y.data_ptr() for y in ys])
+    ld = (ctypes.c_int64 * n)(*[(y.stride(0) if y.shape[0] > 0 else y.shape[1]) for y in ys])
+    _check(ctx, load().marlaas_lora_fwd_multi(ctx.handle, _desc_array(descs), n, yp, ld, _stream_ptr(stream)))
 
 
 def marlaas_lora_bwd(ctx, desc, dY, dX=None, dA=None, dB=None, u_saved=None, accumulate=False, stream=None):

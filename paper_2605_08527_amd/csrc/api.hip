@@ -485,6 +485,131 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
   return MARLAAS_OK;
 }
 
+// ------------------------------------------------------------------ forward, several projections
+// What the projections of one call must share.
+static int check_multi(marlaas_ctx* ctx, const marlaas_lora_desc* descs, int32_t n_proj) {
+  if (!descs || n_proj < 1 || n_proj > MARLAAS_MAX_PROJ) return fail(ctx, MARLAAS_EINVAL, "n_proj must be 1..%d", MARLAAS_MAX_PROJ);
+  for (int p = 0; p < n_proj; ++p) {
+    int rc = check_sizes(ctx, &descs[p]);
+    if (rc != MARLAAS_OK) return rc;
+    const marlaas_lora_desc& a = descs[0];
+    const marlaas_lora_desc& b = descs[p];
+    if (b.T != a.T || b.d_in != a.d_in || b.x != a.x || b.ldx != a.ldx || b.in_dtype != a.in_dtype ||
+        b.out_dtype != a.out_dtype || b.layout != a.layout || b.n_adapters != a.n_adapters || b.map != a.map)
+      return fail(ctx, MARLAAS_ESHAPE, "projection %d differs from projection 0 in T, d_in, x, dtypes, layout, n_adapters or map", p);
+  }
+  return MARLAAS_OK;
+}
+
+static void multi_proj_host(const marlaas_lora_desc* descs, int32_t n_proj, void* const* y, const int64_t* ldy,
+                            std::vector<ProjEntry>* out, int* n_ext, bool* mult8) {
+  out->assign((size_t)n_proj, ProjEntry());
+  memset(out->data(), 0, out->size() * sizeof(ProjEntry));
+  int32_t tile0 = 0, fin0 = 0;
+  int64_t ext = 0;
+  *mult8 = true;
+  for (int p = 0; p < n_proj; ++p) {
+    ProjEntry& e = (*out)[p];
+    e.W = descs[p].W; e.ldw = descs[p].ldw; e.Nout = descs[p].d_out;
+    e.out = y ? y[p] : nullptr; e.ldo = ldy ? ldy[p] : 0;
+    e.tile0 = tile0; e.fin0 = fin0; e.tab0 = p * descs[p].n_adapters;
+    tile0 += (int32_t)((descs[p].d_out + 127) / 128);
+    fin0 += (int32_t)((descs[p].d_out + 511) / 512);
+    for (int t = 0; t < descs[p].n_adapters; ++t) { ext += descs[p].ranks[t]; if (descs[p].ranks[t] & 7) *mult8 = false; }
+  }
+  *n_ext = ext > 0x7fffffff ? 0x7fffffff : (int)ext;
+}
+
+extern "C" size_t marlaas_workspace_bytes_multi(const marlaas_lora_desc* descs, int32_t n_proj) {
+  if (check_multi(nullptr, descs, n_proj) != MARLAAS_OK) return 0;
+  size_t need = 0;
+  for (int p = 0; p < n_proj; ++p) {
+    const size_t one = plan_workspace(&descs[p], 0).total;
+    if (one > need) need = one;
+  }
+  if (n_proj > 1 && descs[0].in_dtype == MARLAAS_BF16) {
+    std::vector<ProjEntry> proj;
+    int n_ext = 0; bool mult8 = true;
+    multi_proj_host(descs, n_proj, nullptr, nullptr, &proj, &n_ext, &mult8);
+    const bool lora = descs[0].n_adapters > 0 && descs[0].map->T_lora > 0;
+    const size_t fused = align_up(gemm_multi_bytes(descs[0].T, descs[0].d_in, proj.data(), n_proj, lora ? n_ext : 0), WS_ALIGN);
+    if (fused > need) need = fused;
+  }
+  return need;
+}
+
+extern "C" int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc* descs, int32_t n_proj,
+                                      void* const* y, const int64_t* ldy, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  int rc = check_multi(ctx, descs, n_proj);
+  if (rc != MARLAAS_OK) return rc;
+  if (!y || !ldy) return fail(ctx, MARLAAS_EINVAL, "y / ldy arrays are null");
+  const marlaas_lora_desc* d0 = &descs[0];
+  if (d0->T == 0) return MARLAAS_OK;
+  const int64_t osz = d0->out_dtype == MARLAAS_BF16 ? 2 : 4;
+  for (int p = 0; p < n_proj; ++p) {
+    if ((rc = check_tensors(ctx, &descs[p])) != MARLAAS_OK) return rc;
+    if (!y[p]) return fail(ctx, MARLAAS_EINVAL, "y[%d] is null", p);
+    if (!aligned16(y[p]) || ldy[p] < descs[p].d_out || (ldy[p] * osz) % 16) return fail(ctx, MARLAAS_EALIGN, "y[%d] / ldy[%d]", p, p);
+  }
+  const marlaas_segmap* map = d0->map;
+  const bool lora = d0->n_adapters > 0 && map->T_lora > 0;
+  const int form = d0->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
+  std::vector<ProjEntry> proj;
+  int n_ext = 0; bool mult8 = true;
+  multi_proj_host(descs, n_proj, y, ldy, &proj, &n_ext, &mult8);
+  if (!lora) n_ext = 0;
+  bool fused = n_proj > 1 && d0->in_dtype == MARLAAS_BF16 && ctx->ws != nullptr;
+  if (fused) fused = gemm_multi_ok(form, d0->T, d0->d_in, proj.data(), n_proj, n_ext, mult8, ctx->ws_bytes);
+  if (!fused) {
+    // sizes outside the fused path: one projection after the other (same stream, same scratch)
+    for (int p = 0; p < n_proj; ++p)
+      if ((rc = marlaas_lora_fwd(ctx, &descs[p], y[p], ldy[p], nullptr, stream)) != MARLAAS_OK) return rc;
+    return MARLAAS_OK;
+  }
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = (hipStream_t)stream;
+  const int n = d0->n_adapters;
+  // combined tables: adapters as [projection][adapter], extended columns over all of them
+  const AdapterEntry* table = nullptr;
+  GemmFuse fuse;
+  if (lora) {
+    std::vector<AdapterEntry> host((size_t)n_proj * n);
+    memset(host.data(), 0, host.size() * sizeof(AdapterEntry));
+    for (int p = 0; p < n_proj; ++p)
+      for (int t = 0; t < n; ++t) {
+        AdapterEntry& e = host[(size_t)p * n + t];
+        e.A = descs[p].A[t]; e.B = descs[p].B[t]; e.rank = descs[p].ranks[t]; e.scale = descs[p].scales[t];
+      }
+    if ((rc = cached_table(ctx, host.data(), host.size() * sizeof(AdapterEntry), (const void**)&table)) != MARLAAS_OK) return rc;
+    std::vector<int32_t> ft((size_t)n_proj * n + 1);
+    int32_t off = 0;
+    for (int p = 0; p < n_proj; ++p)
+      for (int t = 0; t < n; ++t) { ft[(size_t)p * n + t] = off; off += descs[p].ranks[t]; }
+    ft[(size_t)n_proj * n] = off;
+    if (ft.size() & 1) ft.push_back(0);
+    const size_t cols_at = ft.size();
+    ft.resize(cols_at + 2 * (size_t)off);
+    size_t e = 0;
+    for (int p = 0; p < n_proj; ++p)
+      for (int t = 0; t < n; ++t)
+        for (int q = 0; q < descs[p].ranks[t]; ++q, ++e) { ft[cols_at + 2 * e] = p * n + t; ft[cols_at + 2 * e + 1] = q; }
+    const void* dev = nullptr;
+    if ((rc = cached_table(ctx, ft.data(), ft.size() * sizeof(int32_t), &dev)) != MARLAAS_OK) return rc;
+    fuse.roff = (const int32_t*)dev;
+    fuse.cols = (const ExtCol*)((const int32_t*)dev + cols_at);
+    fuse.n_ext = off; fuse.ranks_mult8 = mult8; fuse.u_out = nullptr;
+  }
+  const ProjEntry* proj_dev = nullptr;
+  if ((rc = cached_table(ctx, proj.data(), proj.size() * sizeof(ProjEntry), (const void**)&proj_dev)) != MARLAAS_OK) return rc;
+  const int32_t* perm = map->identity ? nullptr : map->perm_dev;
+  PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16_multi((const bf16_t*)d0->x, d0->ldx, form, d0->T, d0->d_in, perm,
+                                      map->seg_off_dev, n, table, proj.data(), proj_dev, n_proj,
+                                      d0->out_dtype == MARLAAS_F32, (float*)ctx->ws, ctx->ws_bytes, map->chunks_dev,
+                                      map->n_chunks, lora ? &fuse : nullptr, st));
+  return MARLAAS_OK;
+}
+
 // ------------------------------------------------------------------ backward
 extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY, int64_t lddy,
                                 const void* u_saved, void* dX, int64_t lddx, void* const* dA,

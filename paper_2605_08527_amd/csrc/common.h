@@ -40,6 +40,18 @@ struct ExtCol {
   int32_t t, q;
 };
 
+// One projection of a fused multi-projection forward (small batches): its weight, its output and
+// where it sits in the concatenated column space (each projection padded to whole column tiles).
+struct ProjEntry {
+  const void* W; int64_t ldw;     // weight operand, stored in the call's form
+  int64_t Nout;                   // output columns of this projection
+  void* out; int64_t ldo;
+  int32_t tile0;                  // first column tile (128 wide) in the concatenated space
+  int32_t fin0;                   // first column chunk (512 wide) of the finish kernel's grid
+  int32_t tab0;                   // index of this projection's first adapter in the combined table
+  int32_t pad;
+};
+
 // How a [contraction, output] operand is stored.
 //   FORM_NT: element (k, n) at ptr[n * ld + k]   (contraction index contiguous)
 //   FORM_NN: element (k, n) at ptr[k * ld + n]   (output index contiguous)
@@ -100,6 +112,20 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
                             hipStream_t stream);
+// Several projections of the same input in one pass (small batches only: 128 x 128 tiles with
+// the shrink carried as extended columns, or no adapters at all).  `proj_host` / `proj_dev` hold the
+// same n_proj entries; `table` is the combined adapter table ([projection][adapter]), `fuse` (null:
+// no adapters) the combined extended-column tables, ExtCol::t indexing the combined table.
+// gemm_multi_ok tells whether the sizes qualify; otherwise the caller runs the projections one by one.
+bool gemm_multi_ok(int form, int64_t T, int64_t Kc, const ProjEntry* proj_host, int n_proj, int n_ext,
+                   bool ranks_mult8, size_t partial_bytes);
+size_t gemm_multi_bytes(int64_t T, int64_t Kc, const ProjEntry* proj_host, int n_proj, int n_ext);
+hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int64_t T, int64_t Kc,
+                                  const int32_t* perm, const int32_t* seg_off, int n_adapters,
+                                  const AdapterEntry* table, const ProjEntry* proj_host,
+                                  const ProjEntry* proj_dev, int n_proj, int out_is_f32, float* partials,
+                                  size_t partial_bytes, const RowChunk* chunks, int n_chunks,
+                                  const GemmFuse* fuse, hipStream_t stream);
 // Scratch for a transposed copy of the weight: a large batch whose weight is stored
 // [contraction][output] runs faster on a [output][contraction] copy made per call (the copy
 // costs two passes over the weight, the GEMM gains about a quarter).  0: not used for these sizes.

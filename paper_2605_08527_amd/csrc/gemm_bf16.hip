@@ -74,6 +74,11 @@ struct GemmArgs {
   const ExtCol* ext_cols; const int32_t* ext_roff; int n_ext;   // n_ext = sum of the ranks; 0: not fused
   float* u_part; int64_t ldu;   // [ks][pm][ldu] fp32 partial sums of the extended columns
   float* u_out;                 // [T][r_stride] (may be null)
+  // Several projections in one pass (small-batch kernels only; n_proj <= 1: the fields above
+  // describe the only projection).  Column tile tn belongs to the last projection whose tile0 <=
+  // tn; `table`, `ext_roff` and ExtCol::t then index [projection][adapter].
+  const ProjEntry* proj; int n_proj;
+  int fin_cols;                 // column chunks of the finish kernel's grid, all projections
 };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -605,7 +610,17 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     tn = rest / a.ksplit;
   }
   const int64_t m0 = (int64_t)tm * SK_BM;
-  const int64_t n0 = (int64_t)tn * SK_BN;
+  const int64_t pn0 = (int64_t)tn * SK_BN;       // column of this tile in the partial sums
+  // the projection this column tile belongs to (wave-uniform)
+  const bf16_t* Bop = a.Bop;
+  int64_t ldb = a.ldb, Nout = a.Nout, n0 = pn0;
+  if (a.n_proj > 1) {
+    int p = 0;
+    for (int q = 1; q < a.n_proj; ++q) if (tn >= a.proj[q].tile0) p = q;
+    const ProjEntry pe = a.proj[p];
+    Bop = (const bf16_t*)pe.W; ldb = pe.ldw; Nout = pe.Nout;
+    n0 = (int64_t)(tn - pe.tile0) * SK_BN;
+  }
   const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
   const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
   const int64_t ntile = (kend - kbeg) / BK;
@@ -645,16 +660,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       const int row = (wave * 4 + j) * 8 + (lane >> 3);
       const int unit = (lane & 7) ^ ((row >> 1) & 7);
       int64_t n = n0 + row;
-      if (n >= a.Nout) n = a.Nout - 1;
-      b_src[j] = a.Bop + n * a.ldb + kbeg + unit * 8;
+      if (n >= Nout) n = Nout - 1;
+      b_src[j] = Bop + n * ldb + kbeg + unit * 8;
     } else {                         // B tile [64 k][128 n], 256-byte rows
       const int k = (wave * 4 + j) * 4 + (lane >> 4);
       int64_t n = n0 + (((lane & 15) ^ ((k & 3) << 2)) << 3);
-      if (n >= a.Nout) n = a.Nout - 8;
-      b_src[j] = a.Bop + (kbeg + k) * a.ldb + n;
+      if (n >= Nout) n = Nout - 8;
+      b_src[j] = Bop + (kbeg + k) * ldb + n;
     }
   }
-  const int64_t b_step = FORM == FORM_NT ? (int64_t)BK : (int64_t)BK * a.ldb;
+  const int64_t b_step = FORM == FORM_NT ? (int64_t)BK : (int64_t)BK * ldb;
 #pragma unroll
   for (int s3 = 0; s3 < 3; ++s3)
     if (s3 < ntile) {
@@ -986,7 +1001,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         *(uint4*)(as + swz_rowk(row, lc)) = v;
         if (FORM == FORM_NT) {
           uint4 w = zero4;
-          if (ka && (n0 + row) < a.Nout) w = *(const uint4*)(a.Bop + (n0 + row) * a.ldb + k0 + lc * 8);
+          if (ka && (n0 + row) < Nout) w = *(const uint4*)(Bop + (n0 + row) * ldb + k0 + lc * 8);
           *(uint4*)(bs + swz_rowk(row, lc)) = w;
         }
       }
@@ -996,7 +1011,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       for (int i = 0; i < 4; ++i) {
         const int k = lr + 16 * i;
         uint4 w = zero4;
-        if ((k0 + k) < kend && (n0 + lc * 8) < a.Nout) w = *(const uint4*)(a.Bop + (k0 + k) * a.ldb + n0 + lc * 8);
+        if ((k0 + k) < kend && (n0 + lc * 8) < Nout) w = *(const uint4*)(Bop + (k0 + k) * ldb + n0 + lc * 8);
         *(uint4*)(bs + k * 256 + ((lc ^ ((k & 3) << 2)) << 4)) = w;
       }
     }
@@ -1026,7 +1041,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
     const int ksteps = (int)((kend - k0 + 15) / 16);
     for (int ks = 0; ks < ksteps; ++ks) kstep(as, bs, ks);
   }
-  float* part = a.partials + ((int64_t)ks_idx * a.pm + m0 + wm * 64) * a.ldp + n0 + wn * 64 + (lane & 31);
+  float* part = a.partials + ((int64_t)ks_idx * a.pm + m0 + wm * 64) * a.ldp + pn0 + wn * 64 + (lane & 31);
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -1058,11 +1073,23 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
   constexpr int UPT = R * 128 / FIN_THREADS;        // u values staged per thread
   __shared__ float u_s[R][128];
   const int tid = threadIdx.x;
-  const int ncol = (int)((a.Nout + FIN_COLS - 1) / FIN_COLS);
-  const int col = blockIdx.x % ncol;
+  const int ncol = a.fin_cols;
+  int col = blockIdx.x % ncol;
   const RowChunk ch = a.chunks[blockIdx.x / ncol];
+  // the projection this column chunk belongs to (block-uniform)
+  int64_t Nout = a.Nout, ldo = a.ldo, pcol0 = 0;
+  void* outp = a.out;
+  int tab0 = 0;
+  if (a.n_proj > 1) {
+    int p = 0;
+    for (int q = 1; q < a.n_proj; ++q) if (col >= a.proj[q].fin0) p = q;
+    const ProjEntry pe = a.proj[p];
+    Nout = pe.Nout; ldo = pe.ldo; outp = pe.out; tab0 = pe.tab0;
+    pcol0 = (int64_t)pe.tile0 * SK_BN;
+    col -= pe.fin0;
+  }
   const int64_t n = (int64_t)col * FIN_COLS + 2 * tid;
-  const bool active = n < a.Nout;                   // Nout is a multiple of 8
+  const bool active = n < Nout;                     // Nout is a multiple of 8
   const int64_t kstride = a.pm * a.ldp;
   const bool lora_on = ch.t >= 0 && (a.U != nullptr || a.n_ext > 0);
   // A block's run time is a few dependent memory round trips plus the partial-sum traffic, so
@@ -1076,12 +1103,12 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
   const bf16_t* L = nullptr;
   bool pref = false;
   if (lora_on) {
-    e = a.table[ch.t];
+    e = a.table[tab0 + ch.t];
     L = (const bf16_t*)(a.which ? e.B : e.A);
     const int r = e.rank;
     if (a.n_ext > 0) {
       // fused shrink: u = scale * (sum over the splits of this adapter's extended columns)
-      const int roff = a.ext_roff[ch.t];
+      const int roff = a.ext_roff[tab0 + ch.t];
       const int64_t ustride = a.pm * a.ldu;
 #pragma unroll
       for (int i = 0; i < UPT; ++i) {
@@ -1120,14 +1147,14 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
       } else {                             // L[q * Nout + n]
 #pragma unroll
         for (int q = 0; q < 32; ++q)
-          if (q < r) wn[q] = *(const uint32_t*)(L + (int64_t)q * a.Nout + n);
+          if (q < r) wn[q] = *(const uint32_t*)(L + (int64_t)q * Nout + n);
       }
     }
   }
   // partial sums of every row of the chunk, in split order; four splits (32 loads) at a time
   float y0[R], y1[R];
   {
-    const float* part = a.partials + (int64_t)ch.row0 * a.ldp + (active ? n : 0);
+    const float* part = a.partials + (int64_t)ch.row0 * a.ldp + pcol0 + (active ? n : 0);
 #pragma unroll
     for (int j = 0; j < R; ++j) { y0[j] = 0.f; y1[j] = 0.f; }
     for (int ks0 = 0; ks0 < a.ksplit; ks0 += 4) {
@@ -1193,7 +1220,7 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
         }
       } else {
         for (int q = 0; q < r; ++q) {
-          const uint32_t w = *(const uint32_t*)(L + (int64_t)q * a.Nout + n);
+          const uint32_t w = *(const uint32_t*)(L + (int64_t)q * Nout + n);
           const float fa = __uint_as_float(w << 16), fb = __uint_as_float(w & 0xffff0000u);
 #pragma unroll
           for (int j = 0; j < R; ++j) { y0[j] = fmaf(u_s[j][q], fa, y0[j]); y1[j] = fmaf(u_s[j][q], fb, y1[j]); }
@@ -1207,8 +1234,8 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
     if (j < ch.nrows) {
       const int64_t m = ch.row0 + j;
       const int64_t tok = a.perm ? a.perm[m] : m;
-      if (OUT_F32) *(float2*)((float*)a.out + tok * a.ldo + n) = make_float2(y0[j], y1[j]);
-      else *(uint32_t*)((bf16_t*)a.out + tok * a.ldo + n) = float_to_bf16_bits(y0[j]) | ((uint32_t)float_to_bf16_bits(y1[j]) << 16);
+      if (OUT_F32) *(float2*)((float*)outp + tok * ldo + n) = make_float2(y0[j], y1[j]);
+      else *(uint32_t*)((bf16_t*)outp + tok * ldo + n) = float_to_bf16_bits(y0[j]) | ((uint32_t)float_to_bf16_bits(y1[j]) << 16);
     }
   }
 }
@@ -1279,7 +1306,7 @@ static hipError_t launch_one(const GemmArgs& a, int mode, hipStream_t stream) {
     hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32>), dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || mode == 0) return e;
-  const int64_t fin_blocks = ((a.Nout + FIN_COLS - 1) / FIN_COLS) * (int64_t)a.n_chunks;
+  const int64_t fin_blocks = (int64_t)a.fin_cols * a.n_chunks;
   hipLaunchKernelGGL((splitk_finish_kernel<FORM, OUT_F32>), dim3((unsigned)fin_blocks), dim3(FIN_THREADS), 0, stream, a);
   return hipGetLastError();
 }
@@ -1391,6 +1418,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   a.U = U; a.r_stride = r_stride; a.out = out; a.ldo = ldo;
   GemmPlan p = gemm_plan(T, Kc, Nout, fuse ? fuse->n_ext : 0);
   a.ext_cols = nullptr; a.ext_roff = nullptr; a.n_ext = 0; a.u_part = nullptr; a.ldu = 0; a.u_out = nullptr;
+  a.proj = nullptr; a.n_proj = 1; a.fin_cols = (int)((Nout + FIN_COLS - 1) / FIN_COLS);
   if (fuse) {
     // the caller skipped the shrink: the conditions of gemm_can_fuse_shrink() must hold
     if (!gemm_can_fuse_shrink(form, T, Kc, Nout, fuse->n_ext, fuse->ranks_mult8, partials ? partial_bytes : 0) || chunks == nullptr)
@@ -1420,6 +1448,63 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
     return out_is_f32 ? launch_wide<FORM_NT, true, FORM_NN>(a, stream) : launch_wide<FORM_NT, false, FORM_NN>(a, stream);
   }
   return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, stream) : launch_one<FORM_NN, false>(a, p.mode, stream);
+}
+
+// ---- several projections in one pass
+static int64_t multi_tiles(const ProjEntry* proj, int n_proj) {
+  int64_t tiles = 0;
+  for (int p = 0; p < n_proj; ++p) tiles += (proj[p].Nout + SK_BN - 1) / SK_BN;
+  return tiles;
+}
+
+size_t gemm_multi_bytes(int64_t T, int64_t Kc, const ProjEntry* proj_host, int n_proj, int n_ext) {
+  if (T <= 0 || n_proj <= 0) return 0;
+  const GemmPlan p = gemm_plan(T, Kc, multi_tiles(proj_host, n_proj) * SK_BN, n_ext);
+  return p.mode == 2 ? p.bytes + p.u_bytes : 0;
+}
+
+bool gemm_multi_ok(int form, int64_t T, int64_t Kc, const ProjEntry* proj_host, int n_proj, int n_ext,
+                   bool ranks_mult8, size_t partial_bytes) {
+  if (T <= 0 || n_proj < 2 || n_ext < 0) return false;
+  if (n_ext > 0 && form == FORM_NN && !ranks_mult8) return false;
+  const int64_t tiles = multi_tiles(proj_host, n_proj);
+  if (tiles * SK_BN > (1 << 24)) return false;
+  const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext);
+  if (p.mode != 2 || (n_ext > 0 && p.u_bytes == 0)) return false;
+  return partial_bytes >= p.bytes + p.u_bytes;
+}
+
+hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int64_t T, int64_t Kc,
+                                  const int32_t* perm, const int32_t* seg_off, int n_adapters,
+                                  const AdapterEntry* table, const ProjEntry* proj_host,
+                                  const ProjEntry* proj_dev, int n_proj, int out_is_f32, float* partials,
+                                  size_t partial_bytes, const RowChunk* chunks, int n_chunks,
+                                  const GemmFuse* fuse, hipStream_t stream) {
+  const int n_ext = fuse ? fuse->n_ext : 0;
+  if (!gemm_multi_ok(form, T, Kc, proj_host, n_proj, n_ext, fuse ? fuse->ranks_mult8 : true,
+                     partials ? partial_bytes : 0) || chunks == nullptr || proj_dev == nullptr)
+    return hipErrorInvalidValue;
+  const int64_t tiles = multi_tiles(proj_host, n_proj);
+  const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext);
+  GemmArgs a;
+  a.Aop = Aop; a.lda = lda; a.Bop = (const bf16_t*)proj_host[0].W; a.ldb = proj_host[0].ldw;
+  a.T = T; a.Kc = Kc; a.Nout = proj_host[0].Nout;
+  a.perm = perm; a.seg_off = seg_off; a.n_adapters = n_adapters; a.table = table; a.which = 1;
+  a.U = nullptr; a.r_stride = 0; a.out = proj_host[0].out; a.ldo = proj_host[0].ldo;
+  a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.ksplit = p.ksplit; a.kchunk = p.kchunk;
+  a.partials = partials; a.ldp = p.ldp; a.pm = p.pm; a.chunks = chunks; a.n_chunks = n_chunks;
+  a.ext_cols = nullptr; a.ext_roff = nullptr; a.n_ext = 0; a.u_part = nullptr; a.ldu = 0; a.u_out = nullptr;
+  if (fuse) {
+    a.ext_cols = fuse->cols; a.ext_roff = fuse->roff; a.n_ext = n_ext;
+    a.u_part = partials + p.bytes / sizeof(float); a.ldu = p.ldu;
+  }
+  a.proj = proj_dev; a.n_proj = n_proj;
+  int fin_cols = 0;
+  for (int q = 0; q < n_proj; ++q) fin_cols += (int)((proj_host[q].Nout + FIN_COLS - 1) / FIN_COLS);
+  a.fin_cols = fin_cols;
+  if (form == FORM_NT)
+    return out_is_f32 ? launch_one<FORM_NT, true>(a, 2, stream) : launch_one<FORM_NT, false>(a, 2, stream);
+  return out_is_f32 ? launch_one<FORM_NN, true>(a, 2, stream) : launch_one<FORM_NN, false>(a, 2, stream);
 }
 
 }  // namespace marlaas
