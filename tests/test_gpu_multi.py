@@ -87,6 +87,15 @@ def test_decode_shaped_two_projections(oracle, layout):
     _check(oracle, ws, "gate/up", gemm_launches=1, out_dtype=torch.bfloat16, pad=8)
 
 
+def test_full_size_decode_qkv(oracle):
+    """The shape bench.py times for this call: 256 decode tokens (Zipf segment sizes over 32
+    adapters of rank 16), d_in 4096, q / k / v of 4096, 1024 and 1024 columns, bf16 outputs, the
+    layout bench.py uses; every output element against the oracle."""
+    sh, ranks, scales, ids = wl.config_ids(1, 0)
+    ws = _projections(101, sh["T"], sh["d_in"], (4096, 1024, 1024), [list(ranks)] * 3, list(scales), ids, wl.TORCH)
+    _check(oracle, ws, "decode qkv", gemm_launches=1, out_dtype=torch.bfloat16)
+
+
 def test_no_adapters_and_single_projection(oracle):
     rng = np.random.default_rng(4)
     T, K = 96, 264
