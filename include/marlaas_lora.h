@@ -72,7 +72,7 @@ typedef struct {
   int32_t layout;        /* marlaas_layout */
   const void* x;         /* [T, d_in], leading dimension ldx */
   int64_t ldx;
-  const void* W;         /* math: [d_in, d_out]; torch: [d_out, d_in]; leading dimension ldw */
+  const void* W;         /* math: [d_in, d_out]; torch: [d_out, d_in]; leading dimension ldw <= 4194304 */
   int64_t ldw;
   const void* const* A;  /* HOST array of n_adapters device pointers, each dense (no padding) */
   const void* const* B;  /* HOST array of n_adapters device pointers, each dense */

@@ -373,6 +373,7 @@ static int check_tensors(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   if (d->ldx < d->d_in || (d->ldx * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldx=%lld", (long long)d->ldx);
   const int64_t wcols = d->layout == MARLAAS_LAYOUT_MATH ? d->d_out : d->d_in;
   if (d->ldw < wcols || (d->ldw * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldw=%lld", (long long)d->ldw);
+  if (d->ldw > (1 << 22)) return fail(ctx, MARLAAS_EINVAL, "ldw=%lld is above 4194304", (long long)d->ldw);
   if (d->n_adapters > 0) {
     if (!d->A || !d->B) return fail(ctx, MARLAAS_EINVAL, "A / B pointer arrays are null");
     for (int t = 0; t < d->n_adapters; ++t) {

@@ -197,9 +197,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   // unit (l & 7) of row (l >> 3) and so fetches the global unit (l & 7) ^ swizzle(row); every
   // row segment is one whole 128-byte cache line.  k-n tiles ([64][256], 512 B per row): 2
   // k-rows per instruction.  Each wave issues DPW = 8 instructions per operand per k-tile.
+  // The weight operand's addresses are one wave-uniform base, advanced per k-tile with scalar
+  // arithmetic, plus a constant 32-bit byte offset per lane and instruction (a tile of the weight
+  // spans less than 4 GB: the launcher rejects leading dimensions above 2^22 elements); gathered
+  // rows of the first operand need full 64-bit addresses.
   const bf16_t* a_src[DPW];
-  const bf16_t* b_src[DPW];
-  int64_t b_step;          // elements to advance b_src per k-tile
+  const char* b_base;      // wave-uniform
+  uint32_t b_off[DPW];     // bytes
+  int64_t b_step;          // bytes to advance b_base per k-tile
 #pragma unroll
   for (int j = 0; j < DPW; ++j) {
     const int row = (wave * DPW + j) * 8 + (lane >> 3);
@@ -214,9 +219,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int unit = (lane & 7) ^ ((row >> 1) & 7);
       int64_t n = n0 + row;
       if (n >= a.Nout) n = a.Nout - 1;           // clamped columns are never stored
-      b_src[j] = a.Bop + n * a.ldb + kbeg + unit * 8;
+      b_off[j] = (uint32_t)(((n - n0) * a.ldb + unit * 8) * 2);
     }
-    b_step = BK;
+    b_base = (const char*)(a.Bop + n0 * a.ldb + kbeg);
+    b_step = BK * 2;
   } else {
 #pragma unroll
     for (int j = 0; j < DPW; ++j) {
@@ -224,9 +230,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
       const int unit = (lane & 31) ^ kn_swz(k);
       int64_t n = n0 + unit * 8;
       if (n >= a.Nout) n = a.Nout - 8;
-      b_src[j] = a.Bop + (kbeg + k) * a.ldb + n;
+      b_off[j] = (uint32_t)((k * a.ldb + (n - n0)) * 2);
     }
-    b_step = (int64_t)BK * a.ldb;
+    b_base = (const char*)(a.Bop + kbeg * a.ldb + n0);
+    b_step = (int64_t)BK * a.ldb * 2;
   }
   const int dma_off = wave * DPW * 1024;   // this wave's first KB inside an operand part of a slot
 
@@ -273,8 +280,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   do {                                                                                                    \
     char* _sb = smem + (slot_) * SLOT_BYTES + dma_off + (j_) * 1024;                                      \
     if (isb_) {                                                                                           \
-      __builtin_amdgcn_global_load_lds((gptr_t)b_src[j_], (lptr_t)(_sb + SLOT_B_OFF), 16, 0, 0); \
-      b_src[j_] += b_step;                                                                \
+      /* scalar base + 32-bit lane offset: the builtin only emits the 64-bit-address form, which */       \
+      /* costs a 64-bit vector add per request (m0 = LDS byte address of lane 0's 16 bytes)       */       \
+      const uint32_t _lds = (uint32_t)(uintptr_t)(lptr_t)(_sb + SLOT_B_OFF);                               \
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"                        \
+                   :: "v"(b_off[j_]), "s"(b_base), "s"(_lds) : "memory", "m0");                            \
+      if ((j_) == DPW - 1) b_base += b_step;                                                              \
     } else {                                                                                              \
       __builtin_amdgcn_global_load_lds((gptr_t)a_src[j_], (lptr_t)(_sb), 16, 0, 0);       \
       a_src[j_] += BK;                                                                    \
@@ -305,7 +316,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   } while (0)
 
 // One phase: the 32 MFMAs of row blocks 4 h_ .. 4 h_ + 3 (x fragments ux_) against all eight
-// column blocks (weight fragments uw_).  In their shadow, at every other MFMA: up to 4 x fragment
+// column blocks (weight fragments uw_).  In their shadow, after every other MFMA (after every
+// MFMA when there are twelve, so that they are back before the next phase starts): up to 4 x fragment
 // reads (row blocks 4 lxh_ .., k-step lxks_ of slot lxslot_, into lx_) and nw_ weight fragment
 // reads (column blocks lwn0_ .., k-step lwks_ of slot lwslot_, into lw_), and the 8 DMA
 // instructions of one operand part at every fourth MFMA.  sched_barrier pins the order (one wave
@@ -316,8 +328,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     _Pragma("unroll") for (int _i = 0; _i < 32; ++_i) {                                                   \
       acc[4 * (h_) + (_i >> 3)][_i & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                        \
           uw_[_i & 7], ux_[_i >> 3], acc[4 * (h_) + (_i >> 3)][_i & 7], 0, 0, 0);                         \
-      if ((_i & 1) == 0) {                                                                                \
-        const int _r = _i >> 1;                                                                           \
+      __builtin_amdgcn_sched_barrier(0);   /* the MFMA first: a read hoisted above it would be waited for at once */ \
+      if ((nx_) + (nw_) > 8 || (_i & 1) == 0) {     /* 12 reads: one per MFMA, else every other */          \
+        const int _r = (nx_) + (nw_) > 8 ? _i : _i >> 1;                                                  \
         if (_r < (nx_)) RING_READ_X(lxslot_, lxks_, 4 * (lxh_) + _r, lx_[_r]);                            \
         else if (_r - (nx_) < (nw_)) RING_READ_W(lwslot_, lwks_, (lwn0_) + _r - (nx_), lw_[(lwn0_) + _r - (nx_)]); \
       }                                                                                                   \
@@ -1412,6 +1425,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
                             hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
+  if (ldb > (1 << 22)) return hipErrorInvalidValue;      // 32-bit byte offsets inside a weight tile
   GemmArgs a;
   a.Aop = Aop; a.lda = lda; a.Bop = Bop; a.ldb = ldb; a.T = T; a.Kc = Kc; a.Nout = Nout;
   a.perm = perm; a.seg_off = seg_off; a.n_adapters = n_adapters; a.table = table; a.which = which;
