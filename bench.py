@@ -8,8 +8,17 @@ mixed configurations.  The headline line is the decode configuration
 bf16 configurations are reported in the same JSON line under "others".
 
 Inputs are seeded synthetic tensors already resident in HBM before the timed
-region.  The token->adapter map is built once, outside the timed region (a
-serving engine builds it once per batch and reuses it for every layer).
+region; adapters are registered in an adapter table and the token->adapter map
+is built once, both outside the timed region (a serving engine does both once
+per batch / per adapter version and reuses them for every layer).  Every weight
+set the timed steps rotate over is prepared before anything is captured or timed.
+
+Timing: W untimed warm-up steps, then exactly K steps between two
+synchronisations (ms_per_step, value); after that at least 50 further
+iterations, each bracketed by a pair of HIP events on the launch stream, give
+the median and the minimum.  The decode configuration runs as one HIP graph of K
+steps (one replay = K steps over rotating weight sets, so that every step streams
+its weight from HBM); the large configurations launch eagerly.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--configs 1,2,3,4]
                   [--layout torch|math] [--launch graph|eager] [--no-cpu-baseline] [--no-multi-projection]
@@ -17,6 +26,8 @@ serving engine builds it once per batch and reuses it for every layer).
 import argparse
 import json
 import os
+import statistics
+import subprocess
 import sys
 import time
 
@@ -27,13 +38,19 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2516.6   # 256 CUs x 4096 flop/clk x 2.4 GHz, dense bf16
+# Second denominator for the matrix-core bound: what a loop of nothing but bf16 MFMAs (the GEMM's
+# own instruction shape, 256 workgroups, N(0,1) operands) sustained on this machine under its power
+# limit; the all-zero-operand figure is 2460.
+MFMA_MEASURED_CEILING_TFLOPS = 1750.0
+METRIC = "mixed-LoRA layer TFLOP/s + tokens/s at 32 adapters; % of MFMA / HBM peak"
+MIN_EVENT_ITERS = 50
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--configs", default="1,2,3,4")
     ap.add_argument("--layout", default="torch", choices=["torch", "math"])
     ap.add_argument("--launch", default=None, choices=["graph", "eager"])
@@ -44,10 +61,12 @@ def parse_args():
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     ap.add_argument("--rotate", type=int, default=20, help="distinct weight sets cycled in the decode config")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-clocks", action="store_true", help="do not sample rocm-smi while the headline runs")
     ap.add_argument("--multi-projection-only", action="store_true",
                     help="time only the q/k/v multi-projection decode workload and print its line (for profiles)")
     ap.add_argument("--no-multi-projection", action="store_true",
                     help="skip the q/k/v multi-projection measurement of the decode configuration")
+    ap.add_argument("--no-event-stats", action="store_true", help="skip the extra event-timed iterations (for profiles)")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -75,9 +94,9 @@ def algorithmic_work(T, K, N, ranks, counts, bwd, out_bytes=2):
 
 def measured_traffic(cfg, kernel_names):
     """HBM bytes per launch (fetch + write) of the named kernels, from the committed summary of the
-    rocprofv3 --pmc runs (profiles/hbm_traffic.md); None when the summary has no such row.  Kernels
-    that run once each per launch of the timed span (GEMM + finish) add up; variants of one kernel
-    (forward / backward instantiations) are averaged over their launches."""
+    rocprofv3 --pmc runs (profiles/hbm_traffic.md); None when the summary has no such row.  Not
+    measured by this run.  Kernels that run once each per launch of the timed span add up; variants
+    of one kernel (forward / backward instantiations) are averaged over their launches."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.md")
     if not os.path.exists(path):
         return None
@@ -86,10 +105,13 @@ def measured_traffic(cfg, kernel_names):
         num = den = 0.0
         for line in open(path):
             cells = [c.strip() for c in line.split("|")]
-            if len(cells) >= 8 and cells[1] == str(cfg) and name in cells[2]:
-                launches = float(cells[3])
-                num += launches * (float(cells[5]) + float(cells[6]))
-                den += launches
+            try:
+                if len(cells) >= 8 and cells[1] == str(cfg) and name in cells[2]:
+                    launches = float(cells[3])
+                    num += launches * (float(cells[5]) + float(cells[6]))
+                    den += launches
+            except ValueError:
+                continue
         if den:
             total += num / den
             found = True
@@ -103,7 +125,8 @@ def device_normal(shape, std, gen, torch):
 
 
 def build_case(cfg, args, torch, api, wl):
-    """Device tensors, descriptors and buffers of one configuration."""
+    """Device tensors, adapter tables, descriptors and buffers of one configuration: everything a
+    timed step touches exists before the first step."""
     layout = api.MARLAAS_LAYOUT_TORCH if args.layout == "torch" else api.MARLAAS_LAYOUT_MATH
     sh, ranks, scales, ids = wl.config_ids(cfg, args.seed)
     T, K, N, n = sh["T"], sh["d_in"], sh["d_out"], sh["n"]
@@ -113,16 +136,26 @@ def build_case(cfg, args, torch, api, wl):
     ids_dev = torch.from_numpy(ids).cuda()
     segmap = api.marlaas_segmap_build(ctx, ids_dev, n)
     n_sets = args.rotate if cfg == 1 else 1
+    case = dict(cfg=cfg, ctx=ctx, segmap=segmap, T=T, K=K, N=N, n=n, ranks=ranks, ids=ids,
+                bwd=sh["bwd"], layout=layout, counts=np.bincount(ids, minlength=n))
+    if sh["bwd"]:
+        shapeA = [((int(r), K) if layout else (K, int(r))) for r in ranks]
+        shapeB = [((N, int(r)) if layout else (int(r), N)) for r in ranks]
+        case["dA"] = [torch.empty(s, dtype=torch.float32, device="cuda") for s in shapeA]
+        case["dB"] = [torch.empty(s, dtype=torch.float32, device="cuda") for s in shapeB]
     sets = []
     for _ in range(n_sets):
         x = device_normal((T, K), 1.0, gen, torch)
         W = device_normal((N, K) if layout else (K, N), K ** -0.5, gen, torch)
         A = [device_normal((int(r), K) if layout else (K, int(r)), K ** -0.5, gen, torch) for r in ranks]
         B = [device_normal((N, int(r)) if layout else (int(r), N), float(r) ** -0.5, gen, torch) for r in ranks]
-        desc = api.LoraDesc(x, W, A, B, ranks, scales, segmap, layout=layout, out_dtype=torch.bfloat16)
-        sets.append(dict(x=x, W=W, A=A, B=B, desc=desc))
-    case = dict(cfg=cfg, ctx=ctx, segmap=segmap, sets=sets, T=T, K=K, N=N, n=n, ranks=ranks, ids=ids,
-                bwd=sh["bwd"], layout=layout, counts=np.bincount(ids, minlength=n))
+        table = api.marlaas_adapter_table_create(ctx, n, 1, int(max(ranks)))
+        for t in range(n):
+            api.marlaas_adapter_table_update(ctx, table, 0, t, A[t], B[t], int(ranks[t]), float(scales[t]),
+                                             case["dA"][t] if sh["bwd"] else None, case["dB"][t] if sh["bwd"] else None)
+        desc = api.LoraDesc(x, W, None, None, None, None, segmap, layout=layout, out_dtype=torch.bfloat16, table=table)
+        sets.append(dict(x=x, W=W, A=A, B=B, table=table, desc=desc))
+    case["sets"] = sets
     case["y"] = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
     ws_bytes = api.marlaas_workspace_bytes(sets[0]["desc"], sh["bwd"])
     case["ws"] = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
@@ -131,8 +164,7 @@ def build_case(cfg, args, torch, api, wl):
         case["dY"] = device_normal((T, N), 1.0, gen, torch)
         case["dX"] = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
         case["u"] = torch.empty((T, api.marlaas_u_stride(sets[0]["desc"])), dtype=torch.float32, device="cuda")
-        case["dA"] = [torch.empty(tuple(a.shape), dtype=torch.float32, device="cuda") for a in sets[0]["A"]]
-        case["dB"] = [torch.empty(tuple(b.shape), dtype=torch.float32, device="cuda") for b in sets[0]["B"]]
+    torch.cuda.synchronize()
     return case
 
 
@@ -140,23 +172,25 @@ def one_step(case, i, api):
     s = case["sets"][i % len(case["sets"])]
     if case["bwd"]:
         api.marlaas_lora_fwd(case["ctx"], s["desc"], case["y"], u_save=case["u"])
-        api.marlaas_lora_bwd(case["ctx"], s["desc"], case["dY"], dX=case["dX"], dA=case["dA"], dB=case["dB"],
-                             u_saved=case["u"])
+        api.marlaas_lora_bwd(case["ctx"], s["desc"], case["dY"], dX=case["dX"], dA=api.MARLAAS_GRADS_IN_TABLE,
+                             dB=api.MARLAAS_GRADS_IN_TABLE, u_saved=case["u"])
     else:
         api.marlaas_lora_fwd(case["ctx"], s["desc"], case["y"])
 
 
-def time_case(case, steps, warmup, launch, torch, api, profile=True):
+def time_steps(step, steps, warmup, launch, torch, event_stats=True, during=None):
+    """The timing protocol: `warmup` untimed steps, exactly `steps` steps between two
+    synchronisations, then >= 50 further event-timed iterations (graph: one iteration = one replay
+    of the `steps` captured steps; eager: one step).  Returns a dict in ms per step."""
     for i in range(warmup):
-        one_step(case, i, api)
+        step(i)
     torch.cuda.synchronize()
     graph = None
     if launch == "graph":
-        # one HIP graph holding `steps` consecutive steps (each on its own weight set)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for i in range(steps):
-                one_step(case, i, api)
+                step(i)
         graph.replay()          # untimed replay: uploads the graph
         torch.cuda.synchronize()
     torch.cuda.synchronize()
@@ -165,12 +199,71 @@ def time_case(case, steps, warmup, launch, torch, api, profile=True):
         graph.replay()
     else:
         for i in range(steps):
-            one_step(case, i, api)
+            step(i)
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    if not profile:
-        return wall_ms / steps, None
-    # per-kernel durations: a second pass of the same steps with every launch bracketed by events
+    out = dict(ms_per_step=(time.perf_counter() - t0) * 1e3 / steps)
+    if not event_stats:
+        return out
+    iters = MIN_EVENT_ITERS if graph is not None else max(MIN_EVENT_ITERS, steps)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    side = during() if during is not None else None      # e.g. a clock sampler running beside the loop
+    for it, (b, e) in enumerate(pairs):
+        b.record()
+        if graph is not None:
+            graph.replay()
+        else:
+            step(it)
+        e.record()
+    torch.cuda.synchronize()
+    per = [b.elapsed_time(e) / (steps if graph is not None else 1) for b, e in pairs]
+    out.update(event_iterations=iters, event_median_ms=statistics.median(per), event_min_ms=min(per),
+               event_unit="one replay of the captured steps / steps" if graph is not None else "one step")
+    if side is not None:
+        # keep the same work running until the sampler has returned, then collect what it saw
+        t_end = time.perf_counter() + 20.0
+        while side.poll() is None and time.perf_counter() < t_end:
+            if graph is not None:
+                graph.replay()
+            else:
+                step(0)
+            torch.cuda.synchronize()
+        out["clocks"] = side.result()
+    return out
+
+
+class ClockSampler:
+    """rocm-smi in a child process while the timed loop runs: the engine and memory clocks under this load."""
+
+    def __init__(self):
+        self.proc = None
+        try:
+            self.proc = subprocess.Popen(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE,
+                                         stderr=subprocess.DEVNULL)
+        except OSError:
+            pass
+
+    def poll(self):
+        return 0 if self.proc is None else self.proc.poll()
+
+    def result(self):
+        if self.proc is None:
+            return None
+        try:
+            out, _ = self.proc.communicate(timeout=30)
+            card = next(iter(json.loads(out.decode()).values()))
+            keep = {}
+            for k, v in card.items():
+                kl = k.lower()
+                if "sclk" in kl or "mclk" in kl or "fclk" in kl:
+                    keep[k] = v
+            return keep or None
+        except Exception:
+            return None
+
+
+def kernel_spans(case, steps, torch, api):
+    """Per-kernel durations: a pass of the same steps, eager, with every launch of the library
+    bracketed by HIP events on the launch stream."""
     api.marlaas_profile_enable(case["ctx"], True)
     for i in range(steps):
         one_step(case, i, api)
@@ -181,7 +274,7 @@ def time_case(case, steps, warmup, launch, torch, api, profile=True):
         ms, cnt = api.marlaas_profile_read(case["ctx"], kid)
         kern[name] = dict(total_ms=ms, launches=cnt, avg_ms=(ms / cnt if cnt else None))
     api.marlaas_profile_enable(case["ctx"], False)
-    return wall_ms / steps, kern
+    return kern
 
 
 def vendor_reference(case, steps, warmup, launch, torch):
@@ -197,54 +290,40 @@ def vendor_reference(case, steps, warmup, launch, torch):
         torch.mm(s["x"], s["W"].t() if tl else s["W"], out=y)
         if case["bwd"]:
             torch.mm(case["dY"], s["W"] if tl else s["W"].t(), out=case["dX"])
-    for i in range(warmup):
-        step(i)
-    torch.cuda.synchronize()
-    graph = None
-    if launch == "graph":
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for i in range(steps):
-                step(i)
-        graph.replay()
-        torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(steps):
-            step(i)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) * 1e3 / steps
+    # (the vendor library may set itself up on the first call of a shape: at least one eager call before a capture)
+    return time_steps(step, steps, max(warmup, 1), launch, torch, event_stats=False)["ms_per_step"]
 
 
 def multi_projection_decode(case, args, steps, warmup, torch, api):
     """The decode batch against a block's q / k / v projections (d_out 4096, 1024, 1024: grouped-query
-    attention of an 8B-class model), each with its own adapters of rank 16: one
-    marlaas_lora_fwd_multi call per step against three marlaas_lora_fwd calls, HIP-graph replay over
-    rotating weight sets like the headline.  Roofline as for the headline: algorithmic bytes of the
-    step over the duration of the one GEMM + finish span."""
+    attention of an 8B-class model), each with its own adapters of rank 16 registered in one table of
+    three projections: one marlaas_lora_fwd_multi call per step against three marlaas_lora_fwd calls,
+    HIP-graph replay over rotating weight sets like the headline.  Roofline as for the headline:
+    algorithmic bytes of the step over the event-timed duration of a step of the replayed graph."""
     gen = torch.Generator(device="cuda")
     gen.manual_seed(77 + args.seed)
     T, K, n, ranks, layout = case["T"], case["K"], case["n"], case["ranks"], case["layout"]
     Ns = (4096, 1024, 1024)
     ctx, segmap = case["ctx"], case["segmap"]
-    scales = [2.0] * n
     sets = []
     for s in case["sets"][:max(2, len(case["sets"]) // 2)]:
+        table = api.marlaas_adapter_table_create(ctx, n, len(Ns), int(max(ranks)))
         projs = []
-        for N in Ns:
+        for p, N in enumerate(Ns):
             W = device_normal((N, K) if layout else (K, N), K ** -0.5, gen, torch)
             A = [device_normal((int(r), K) if layout else (K, int(r)), K ** -0.5, gen, torch) for r in ranks]
             B = [device_normal((N, int(r)) if layout else (int(r), N), float(r) ** -0.5, gen, torch) for r in ranks]
-            projs.append(dict(W=W, A=A, B=B, desc=api.LoraDesc(s["x"], W, A, B, ranks, scales, segmap, layout=layout,
-                                                              out_dtype=torch.bfloat16)))
+            for t in range(n):
+                api.marlaas_adapter_table_update(ctx, table, p, t, A[t], B[t], int(ranks[t]), 2.0)
+            projs.append(dict(W=W, A=A, B=B, desc=api.LoraDesc(s["x"], W, None, None, None, None, segmap, layout=layout,
+                                                              out_dtype=torch.bfloat16, table=table, proj=p)))
         sets.append(projs)
     ys = [torch.empty((T, N), dtype=torch.bfloat16, device="cuda") for N in Ns]
     descs0 = [pr["desc"] for pr in sets[0]]
     ws = torch.empty(max(api.marlaas_workspace_bytes_multi(descs0), 256), dtype=torch.uint8, device="cuda")
     old_ws = case["ws"]
     api.marlaas_set_workspace(ctx, ws)
+    torch.cuda.synchronize()
 
     def fused_step(i):
         api.marlaas_lora_fwd_multi(ctx, [pr["desc"] for pr in sets[i % len(sets)]], ys)
@@ -254,21 +333,10 @@ def multi_projection_decode(case, args, steps, warmup, torch, api):
             api.marlaas_lora_fwd(ctx, pr["desc"], y)
 
     out = {}
-    for name, step in (("fused", fused_step), ("separate", separate_step)):
-        for i in range(warmup):
-            step(i)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            for i in range(steps):
-                step(i)
-        graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        graph.replay()
-        torch.cuda.synchronize()
-        out[name + "_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / steps
-        del graph
+    fused = time_steps(fused_step, steps, warmup, "graph", torch, event_stats=not args.no_event_stats)
+    out["fused_ms_per_step"] = fused["ms_per_step"]
+    out["fused_event_median_ms"] = fused.get("event_median_ms")
+    out["separate_ms_per_step"] = time_steps(separate_step, steps, warmup, "graph", torch, event_stats=False)["ms_per_step"]
     api.marlaas_profile_enable(ctx, True)
     for i in range(steps):
         fused_step(i)
@@ -278,29 +346,59 @@ def multi_projection_decode(case, args, steps, warmup, torch, api):
     api.marlaas_set_workspace(ctx, old_ws)
     present = case["counts"] > 0
     nbytes = sum(2.0 * (K * N + 0.0) + 2.0 * T * N + 2.0 * float(np.sum(ranks[present])) * (K + N) for N in Ns) + 2.0 * T * K
-    span_ms = ms / cnt if cnt else None
+    span_ms = fused.get("event_median_ms") or fused["ms_per_step"]
     out.update(workload="decode q/k/v: T=%d, %d -> %s, %d adapters r=16 per projection" % (T, K, list(Ns), n),
                gemm_launches_per_step=cnt / steps, tokens_per_s=T / (out["fused_ms_per_step"] * 1e-3),
-               roofline=dict(bound="hbm", achieved=nbytes / (span_ms * 1e-3) / 1e9 if span_ms else None, peak=HBM_PEAK_GBS,
-                             unit="GB/s", frac=nbytes / (span_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if span_ms else None,
-                             traffic=None, kernel="gemm_skinny_kernel + splitk_finish_kernel (three projections, shrink fused)",
-                             avg_kernel_ms=span_ms))
+               roofline=dict(bound="hbm", achieved=nbytes / (span_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
+                             unit="GB/s", frac=nbytes / (span_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             traffic=None, kernel="small-batch GEMM kernels of one fused three-projection call",
+                             avg_kernel_ms=span_ms, eager_event_span_ms=(ms / cnt if cnt else None)))
     return out
 
 
-def cpu_baseline_decode(args, wl):
-    """The fp64 oracle, as it stands, on the full decode configuration."""
+def cpu_info():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, args, wl):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of configuration
+    `cfg`: the whole decode batch for configuration 1; for the large ones a seeded subset of token
+    rows against the full-size weights and adapters (rows are independent, so tokens/s carries over;
+    each call also widens W to fp64 once, which is counted)."""
     from oracle import lora_oracle
-    w = wl.make_config(1, seed=args.seed, layout=wl.TORCH if args.layout == "torch" else wl.MATH)
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        lora_oracle.fwd(w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"], layout=w["layout"])
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt >= 10.0 or reps >= 200:
-            break
-    return dict(value=reps * w["T"] / dt, unit="tokens/s", cores=lora_oracle.num_threads(), kind="oracle",
-                sample="all 256 tokens of the decode configuration, %d forward passes in %.1f s" % (reps, dt))
+    layout = wl.TORCH if args.layout == "torch" else wl.MATH
+    if cfg == 1:
+        w = wl.make_config(1, seed=args.seed, layout=layout)
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            lora_oracle.fwd(w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"], layout=w["layout"])
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= 10.0 or reps >= 200:
+                break
+        return dict(value=reps * w["T"] / dt, unit="tokens/s", cores=lora_oracle.num_threads(), kind="oracle", cpu=cpu_info(),
+                    sample="all 256 tokens of the decode configuration, %d forward passes in %.1f s" % (reps, dt))
+    sh, ranks, scales, ids = wl.config_ids(cfg, args.seed)
+    rows = {2: 2048, 3: 1024, 4: 2048}[cfg]
+    rng = np.random.default_rng(args.seed + 10 * cfg)
+    sub = ids[np.sort(rng.choice(sh["T"], size=rows, replace=False))]
+    w = wl.make_layer(args.seed, rows, sh["d_in"], sh["d_out"], ranks, scales, sub, dtype="bf16", layout=layout,
+                      want_dY=sh["bwd"])
+    a = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    t0 = time.perf_counter()
+    lora_oracle.fwd(*a, layout=layout)
+    if sh["bwd"]:
+        lora_oracle.bwd(*a, w["dY"], layout=layout)
+    dt = time.perf_counter() - t0
+    return dict(value=rows / dt, unit="tokens/s", cores=lora_oracle.num_threads(), kind="oracle", cpu=cpu_info(),
+                sample="%d token rows with the adapter labels of a seeded subset of the batch, full-size weights: "
+                       "forward%s in %.1f s" % (rows, " + backward (dX, dA, dB)" if sh["bwd"] else "", dt))
 
 
 def main():
@@ -311,19 +409,18 @@ def main():
         sys.exit(2)
     import torch
     from paper_2605_08527_amd import api
-    from paper_2605_08527_amd import workloads as wl
+    from harness import workloads as wl
     api.load()
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     cfgs = [int(c) for c in args.configs.split(",") if c]
+    steps, warmup = max(1, args.steps), max(0, args.warmup)
     if args.multi_projection_only:
-        steps = args.steps if args.steps is not None else 200
-        warmup = args.warmup if args.warmup is not None else 40
         case = build_case(1, args, torch, api, wl)
         m = multi_projection_decode(case, args, steps, warmup, torch, api)
         print(json.dumps({
-            "metric": "mixed-LoRA layer tokens/s at 32 adapters (with TFLOP/s and % of MFMA / HBM peak)",
+            "metric": METRIC,
             "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
             "ms_per_step": m["fused_ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16", "data": "synthetic",
@@ -335,49 +432,66 @@ def main():
     for cfg in cfgs:
         if cfg not in (1, 2, 3, 4):
             raise SystemExit("--configs takes 1..4 (config 0 is a parity-only case)")
-        steps = args.steps if args.steps is not None else {1: 200, 2: 20, 3: 5, 4: 30}[cfg]
-        warmup = args.warmup if args.warmup is not None else {1: 40, 2: 5, 3: 2, 4: 5}[cfg]
         launch = args.launch or ("graph" if cfg == 1 else "eager")
         case = build_case(cfg, args, torch, api, wl)
-        ms, kern = time_case(case, steps, warmup, launch, torch, api)
-        extra = {}
-        if not args.no_vendor_reference:
-            extra["vendor_base_gemm_only_ms_per_step"] = vendor_reference(case, steps, warmup, launch, torch)
-        if cfg == 1 and len(case["sets"]) > 1:
-            # the same steps on one weight set only: everything stays in the memory-side cache
-            hot = dict(case, sets=case["sets"][:1])
-            extra["hot_cache_ms_per_step"] = time_case(hot, steps, warmup, launch, torch, api, profile=False)[0]
-        if cfg == 1 and not args.no_multi_projection:
-            extra["multi_projection"] = multi_projection_decode(case, args, steps, warmup, torch, api)
-        if cfg == 4:
-            # the timed steps reuse a prebuilt segment map; building it (three small kernels and a
-            # read-back of the offsets) costs this much per batch
-            ids_dev = torch.from_numpy(case["ids"]).cuda()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(10):
-                m = api.marlaas_segmap_build(case["ctx"], ids_dev, case["n"])
-                del m
-            torch.cuda.synchronize()
-            extra["segmap_build_ms"] = (time.perf_counter() - t0) * 1e3 / 10
-            extra["ms_per_step_with_segmap_build"] = ms + extra["segmap_build_ms"]
+        sampler = (lambda: ClockSampler()) if (cfg == cfgs[0] and not args.no_clocks) else None
+        tm = time_steps(lambda i: one_step(case, i, api), steps, warmup, launch, torch,
+                        event_stats=not args.no_event_stats, during=sampler)
+        ms = tm["ms_per_step"]
+        kern = kernel_spans(case, steps, torch, api)
+        extra = {k: v for k, v in tm.items() if k != "ms_per_step"}
+        try:
+            if not args.no_vendor_reference:
+                extra["vendor_base_gemm_only_ms_per_step"] = vendor_reference(case, steps, warmup, launch, torch)
+            if cfg == 1 and len(case["sets"]) > 1:
+                # the same steps on one weight set only: everything stays in the memory-side cache
+                hot = dict(case, sets=case["sets"][:1])
+                extra["hot_cache_ms_per_step"] = time_steps(lambda i: one_step(hot, i, api), steps, warmup, launch, torch,
+                                                            event_stats=False)["ms_per_step"]
+            if cfg == 1 and not args.no_multi_projection:
+                extra["multi_projection"] = multi_projection_decode(case, args, steps, warmup, torch, api)
+            if cfg == 4:
+                # the timed steps reuse a prebuilt segment map; regrouping a batch into an existing map
+                # object (five small kernels, a read-back of the offsets and one wait) costs this much
+                ids_dev = torch.from_numpy(case["ids"]).cuda()
+                m = api.marlaas_segmap_create(case["ctx"], case["T"], case["n"])
+                api.marlaas_segmap_update(case["ctx"], m, ids_dev, case["n"])
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(10):
+                    api.marlaas_segmap_update(case["ctx"], m, ids_dev, case["n"])
+                torch.cuda.synchronize()
+                extra["segmap_update_ms"] = (time.perf_counter() - t0) * 1e3 / 10
+                extra["ms_per_step_with_segmap_update"] = ms + extra["segmap_update_ms"]
+            if not args.no_cpu_baseline:
+                extra["cpu_baseline"] = cpu_baseline(cfg, args, wl)
+        except Exception as e:       # an extra must never cost the line its timed numbers
+            extra["extras_error"] = "%s: %s" % (type(e).__name__, e)
         work = algorithmic_work(case["T"], case["K"], case["N"], case["ranks"], case["counts"], case["bwd"])
         g = kern["gemm"]
+        src = "profiles/hbm_traffic.md (rocprofv3 --pmc runs of this command; not measured by this run)"
         if cfg == 1:
-            # small batches: the split-K GEMM (which also computes the shrink) and its finish kernel are
-            # timed as one span; without a separate shrink launch that span is the whole step
+            # small batches: the step is the small-batch GEMM launches (which also compute the shrink) and
+            # nothing else, so the kernel span of a step is the step itself, in the mode it is timed in:
+            # the event-bracketed replay of the captured steps
             fused = kern["shrink"]["launches"] == 0
-            ach = (work["bytes"] if fused else work["gemm"]["bytes"]) / (g["avg_ms"] * 1e-3) / 1e9
+            span_ms = tm.get("event_median_ms", ms) if fused else g["avg_ms"]
+            ach = (work["bytes"] if fused else work["gemm"]["bytes"]) / (span_ms * 1e-3) / 1e9
             roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                        traffic=measured_traffic(1, ["gemm_skinny_kernel", "splitk_finish_kernel"]),
-                        kernel="gemm_skinny_kernel + splitk_finish_kernel" + (" (shrink fused)" if fused else ""),
-                        avg_kernel_ms=g["avg_ms"])
+                        traffic=measured_traffic(1, ["gemm_skinny_kernel", "splitk_finish_kernel", "gemm_decode_kernel"]),
+                        traffic_source=src,
+                        kernel="small-batch GEMM launches of the step" + (" (shrink fused)" if fused else ""),
+                        avg_kernel_ms=span_ms,
+                        span=("event-timed median of one step inside the replayed graph" if "event_median_ms" in tm and launch == "graph"
+                              else "event-timed per step"),
+                        eager_event_span_ms=g["avg_ms"])
         else:
             ach = work["gemm"]["flops"] / (g["avg_ms"] * 1e-3) / 1e12
             roof = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                         frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=measured_traffic(cfg, ["gemm_bf16_kernel"]),
-                        kernel="gemm_bf16_kernel",
-                        avg_kernel_ms=g["avg_ms"])
+                        traffic_source=src, kernel="gemm_bf16_kernel", avg_kernel_ms=g["avg_ms"],
+                        measured_mfma_ceiling=MFMA_MEASURED_CEILING_TFLOPS,
+                        frac_of_measured_ceiling=ach / MFMA_MEASURED_CEILING_TFLOPS)
         results[cfg] = dict(
             workload="config %d" % cfg, steps=steps, warmup=warmup, launch=launch, ms_per_step=ms,
             tokens_per_s=case["T"] / (ms * 1e-3), tflops=work["flops"] / (ms * 1e-3) / 1e12,
@@ -402,18 +516,18 @@ def main():
              3: "train fwd+bwd: T=262144, 14336->4096, 16 adapters r=32",
              4: "mixed fwd+bwd: T=16896 interleaved, 5120x5120, 64 adapters r in {8,16,32,64}"}
     line = {
-        "metric": "mixed-LoRA layer tokens/s at 32 adapters (with TFLOP/s and % of MFMA / HBM peak)",
+        "metric": METRIC,
         "value": h["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": h["steps"], "warmup": h["warmup"],
         "ms_per_step": h["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": names[head_cfg], "layout": args.layout, "launch": h["launch"],
                    "out_dtype": "bf16", "weight_sets_rotated": args.rotate if head_cfg == 1 else 1,
+                   "adapters": "registered in an adapter table, outside the timed region",
                    "segmap": "prebuilt, outside the timed region"},
         "tflops": h["tflops"], "roofline": h["roofline"],
     }
-    if not args.no_cpu_baseline and head_cfg == 1:
-        line["cpu_baseline"] = cpu_baseline_decode(args, wl)
-    for k in ("vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection"):
+    for k in ("cpu_baseline", "event_iterations", "event_median_ms", "event_min_ms", "event_unit", "clocks",
+              "vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection", "extras_error"):
         if k in h:
             line[k] = h[k]
     line["others"] = [dict(results[c], workload=names[c]) for c in cfgs if c != head_cfg]

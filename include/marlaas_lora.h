@@ -21,8 +21,12 @@
  *    leading dimensions are in elements and must keep rows 16-byte aligned;
  *    d_in and d_out must be multiples of 8.  Otherwise MARLAAS_EALIGN.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    marlaas_lora_fwd / marlaas_lora_bwd only enqueue work on it and return;
- *    marlaas_segmap_build enqueues, then waits for its own kernels.
+ *    The passes (marlaas_lora_fwd, marlaas_lora_bwd, marlaas_lora_fwd_multi,
+ *    marlaas_adapter_table_update) only enqueue kernels on it and return: they
+ *    allocate nothing, copy nothing from host memory, wait for nothing, and may
+ *    be recorded into a HIP graph by stream capture, first call included.
+ *    Device memory is only ever allocated by the *_create / *_build calls.
+ *    marlaas_segmap_update enqueues, then waits for its own kernels.
  *  - Argument errors are reported synchronously as negative status codes with a
  *    message retrievable by marlaas_last_error(); HIP failures map to
  *    MARLAAS_EHIP.  No C++ exception crosses this boundary.
@@ -40,6 +44,7 @@ extern "C" {
 
 typedef struct marlaas_ctx marlaas_ctx;       /* device id, workspace, last error text */
 typedef struct marlaas_segmap marlaas_segmap; /* token grouping by adapter (device + host copies) */
+typedef struct marlaas_adapter_table marlaas_adapter_table; /* registered adapters, versioned (device + host mirror) */
 
 typedef enum {
   MARLAAS_OK = 0,
@@ -79,6 +84,12 @@ typedef struct {
   const int32_t* ranks;  /* HOST int32[n_adapters], 1 .. MARLAAS_MAX_RANK */
   const float* scales;   /* HOST float[n_adapters], s_t (= alpha / r_t) */
   const marlaas_segmap* map; /* grouping of the T tokens by adapter, see marlaas_segmap_build */
+  /* Optional: the adapters come from a table object instead of the four host arrays above (which
+   * are then ignored and may be NULL); n_adapters must equal the table's.  `proj` selects the
+   * projection inside the table (0 for a table of one projection). */
+  const marlaas_adapter_table* table;
+  int32_t proj;
+  int32_t reserved;      /* set to 0 */
 } marlaas_lora_desc;
 
 /* Create a context bound to HIP device `device`.  *out is NULL on failure. */
@@ -103,19 +114,71 @@ const char* marlaas_last_error(const marlaas_ctx* ctx);
 int marlaas_segmap_build(marlaas_ctx* ctx, const int32_t* token_adapter, int64_t T,
                          int32_t n_adapters, void* stream, marlaas_segmap** out);
 void marlaas_segmap_destroy(marlaas_segmap* map);
+/*
+ * The same in two steps, for a serving or training loop that regroups a new
+ * batch every step: marlaas_segmap_create allocates a map object able to hold
+ * any batch of up to T_max tokens over up to n_adapters_max adapters (device
+ * buffers and one pinned host buffer, holding no map yet); marlaas_segmap_update
+ * regroups a batch into it without allocating: five small kernels, one
+ * device-to-host copy of the n_adapters + 2 offsets and one wait on `stream` (the
+ * host plans launch grids from the segment sizes).  Sizes beyond the capacity
+ * give MARLAAS_ESHAPE, ids outside [-1, n_adapters) MARLAAS_EINVAL (the object
+ * then holds no map until the next successful update), a capturing stream
+ * MARLAAS_EUNSUPPORTED.  marlaas_segmap_build = create(T, n_adapters) + update.
+ */
+int marlaas_segmap_create(marlaas_ctx* ctx, int64_t T_max, int32_t n_adapters_max, marlaas_segmap** out);
+int marlaas_segmap_update(marlaas_ctx* ctx, marlaas_segmap* map, const int32_t* token_adapter, int64_t T,
+                          int32_t n_adapters, void* stream);
 /* Copy the map to HOST buffers (either may be NULL): perm int32[T],
  * seg_off int32[n_adapters + 2].  Waits for the copy. */
 int marlaas_segmap_export(const marlaas_segmap* map, int32_t* perm, int32_t* seg_off);
 
 /*
+ * Adapter table: the per-task LoRA parameters as the manager holds them, one
+ * entry per task, replaced by a new version after every policy update of that
+ * task (paper Sec. 4.2 "theta_t^(v)", Alg. 1 commit step) while rollouts of the
+ * other tasks keep running.  The table lives in device memory; an entry is
+ * (A_t, B_t, rank, scale, and optionally the fp32 gradient buffers dA_t, dB_t
+ * shaped like A_t, B_t).  A table of n_proj > 1 projections holds the adapters
+ * of the projections of one block that share their input (q / k / v, gate / up);
+ * entry (proj, t) belongs to projection proj.  max_rank bounds the ranks the
+ * table will accept.
+ *
+ * marlaas_adapter_table_update registers or replaces entry (proj, t) by
+ * enqueueing tiny kernels on `stream` (the values travel in the kernel
+ * arguments): it allocates nothing, waits for nothing and may be captured.
+ * Passes enqueued later on the same stream see the new entry, passes enqueued
+ * earlier the old one; a HIP graph that was captured with a descriptor referring
+ * to this table reads the table when it is replayed, so a new adapter version
+ * needs no new capture as long as no rank changed.  An update that changes a
+ * rank also changes how the host plans launches (scratch layout, whether the
+ * shrink is fused): it bumps marlaas_adapter_table_plan_version, and graphs
+ * captured under an older plan version must be captured again.  Caller keeps
+ * the pointed-to tensors alive while passes that may read them are in flight.
+ * marlaas_adapter_table_version(table, proj, t) = number of updates of that
+ * entry (0: never registered), with t < 0 the number of updates of the table;
+ * -1 on bad arguments.  An adapter that no token of a batch uses may stay
+ * unregistered.  One host thread at a time per table.
+ */
+int marlaas_adapter_table_create(marlaas_ctx* ctx, int32_t n_adapters, int32_t n_proj, int32_t max_rank,
+                                 marlaas_adapter_table** out);
+void marlaas_adapter_table_destroy(marlaas_adapter_table* table);
+int marlaas_adapter_table_update(marlaas_ctx* ctx, marlaas_adapter_table* table, int32_t proj, int32_t t,
+                                 const void* A, const void* B, int32_t rank, float scale,
+                                 void* dA, void* dB, void* stream);
+int64_t marlaas_adapter_table_version(const marlaas_adapter_table* table, int32_t proj, int32_t t);
+int64_t marlaas_adapter_table_plan_version(const marlaas_adapter_table* table);
+
+/*
  * Scratch memory.  The caller hands over one device buffer (e.g. a torch
  * tensor) that must stay alive and unused by others while calls on this ctx
- * are in flight.  Apart from it the passes only keep small per-adapter tables
- * (pointers, ranks, scales) on the device: uploaded (hipMalloc + copy) the
- * first time a table's content is seen, then reused from a cache.  marlaas_workspace_bytes returns the
- * size needed by marlaas_lora_fwd (want_bwd = 0) or by fwd and bwd
- * (want_bwd = 1) for this descriptor (only sizes, ranks, dtypes and map are
- * read), or 0 if the descriptor is invalid.
+ * are in flight.  It holds the intermediates u, v, partial sums, a transposed
+ * weight copy for some large batches and, for descriptors without an adapter
+ * table, a per-call copy of their pointer tables (written by a small kernel at
+ * the start of the pass).  marlaas_workspace_bytes returns the size needed by
+ * marlaas_lora_fwd (want_bwd = 0) or by fwd and bwd (want_bwd = 1) for this
+ * descriptor (only sizes, ranks, dtypes, table and map are read), or 0 if the
+ * descriptor is invalid.
  */
 size_t marlaas_workspace_bytes(const marlaas_lora_desc* desc, int want_bwd);
 int marlaas_set_workspace(marlaas_ctx* ctx, void* dev_ptr, size_t bytes);
@@ -164,9 +227,12 @@ int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc* descs, int
  * dA, dB: HOST arrays of n_adapters device fp32 pointers, each shaped like
  * A_t / B_t (dense).  accumulate = 0 overwrites them (an adapter without tokens
  * gets zeros), accumulate = 1 adds to their contents.  dX may be NULL (skip),
- * and dA and dB may both be NULL (skip).  u_saved: what marlaas_lora_fwd wrote
+ * and dA and dB may both be NULL (skip).  With a descriptor that refers to an
+ * adapter table the gradient buffers are the ones registered in the table: pass
+ * MARLAAS_GRADS_IN_TABLE for both dA and dB.  u_saved: what marlaas_lora_fwd wrote
  * to u_save for the same descriptor, or NULL to recompute it.
  */
+#define MARLAAS_GRADS_IN_TABLE ((void* const*)(uintptr_t)1)
 int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, const void* dY, int64_t lddy,
                      const void* u_saved, void* dX, int64_t lddx, void* const* dA,
                      void* const* dB, int accumulate, void* stream);

@@ -20,6 +20,9 @@ MARLAAS_OK = 0
 EXPORTS = [
     "marlaas_create", "marlaas_destroy", "marlaas_strerror", "marlaas_last_error",
     "marlaas_segmap_build", "marlaas_segmap_destroy", "marlaas_segmap_export",
+    "marlaas_segmap_create", "marlaas_segmap_update",
+    "marlaas_adapter_table_create", "marlaas_adapter_table_destroy", "marlaas_adapter_table_update",
+    "marlaas_adapter_table_version", "marlaas_adapter_table_plan_version",
     "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd",
     "marlaas_workspace_bytes_multi", "marlaas_lora_fwd_multi",
     "marlaas_u_stride", "marlaas_profile_enable", "marlaas_profile_read",
@@ -37,6 +40,7 @@ class marlaas_lora_desc(ctypes.Structure):
         ("A", ctypes.POINTER(ctypes.c_void_p)), ("B", ctypes.POINTER(ctypes.c_void_p)),
         ("ranks", ctypes.POINTER(ctypes.c_int32)), ("scales", ctypes.POINTER(ctypes.c_float)),
         ("map", ctypes.c_void_p),
+        ("table", ctypes.c_void_p), ("proj", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -66,6 +70,20 @@ def load():
     lib.marlaas_segmap_destroy.restype = None
     lib.marlaas_segmap_export.argtypes = [vp, vp, vp]
     lib.marlaas_segmap_export.restype = ctypes.c_int
+    lib.marlaas_segmap_create.argtypes = [vp, i64, i32, ctypes.POINTER(vp)]
+    lib.marlaas_segmap_create.restype = ctypes.c_int
+    lib.marlaas_segmap_update.argtypes = [vp, vp, vp, i64, i32, vp]
+    lib.marlaas_segmap_update.restype = ctypes.c_int
+    lib.marlaas_adapter_table_create.argtypes = [vp, i32, i32, i32, ctypes.POINTER(vp)]
+    lib.marlaas_adapter_table_create.restype = ctypes.c_int
+    lib.marlaas_adapter_table_destroy.argtypes = [vp]
+    lib.marlaas_adapter_table_destroy.restype = None
+    lib.marlaas_adapter_table_update.argtypes = [vp, vp, i32, i32, vp, vp, i32, ctypes.c_float, vp, vp, vp]
+    lib.marlaas_adapter_table_update.restype = ctypes.c_int
+    lib.marlaas_adapter_table_version.argtypes = [vp, i32, i32]
+    lib.marlaas_adapter_table_version.restype = i64
+    lib.marlaas_adapter_table_plan_version.argtypes = [vp]
+    lib.marlaas_adapter_table_plan_version.restype = i64
     lib.marlaas_workspace_bytes.argtypes = [ctypes.POINTER(marlaas_lora_desc), ctypes.c_int]
     lib.marlaas_workspace_bytes.restype = ctypes.c_size_t
     lib.marlaas_set_workspace.argtypes = [vp, vp, ctypes.c_size_t]
@@ -73,7 +91,7 @@ def load():
     lib.marlaas_lora_fwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp]
     lib.marlaas_lora_fwd.restype = ctypes.c_int
     lib.marlaas_lora_bwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
-                                     ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int, vp]
+                                     vp, vp, ctypes.c_int, vp]
     lib.marlaas_lora_bwd.restype = ctypes.c_int
     lib.marlaas_workspace_bytes_multi.argtypes = [ctypes.POINTER(marlaas_lora_desc), i32]
     lib.marlaas_workspace_bytes_multi.restype = ctypes.c_size_t
@@ -179,6 +197,67 @@ def marlaas_segmap_destroy(segmap):
     segmap.close()
 
 
+def marlaas_segmap_create(ctx, T_max, n_adapters_max):
+    """A map object with room for T_max tokens / n_adapters_max adapters (holds no map yet)."""
+    h = ctypes.c_void_p()
+    _check(ctx, load().marlaas_segmap_create(ctx.handle, int(T_max), int(n_adapters_max), ctypes.byref(h)))
+    return Segmap(h, 0, 0)
+
+
+def marlaas_segmap_update(ctx, segmap, token_adapter, n_adapters, stream=None):
+    """Regroup a new batch into an existing map object (no allocation)."""
+    assert token_adapter.dtype == torch.int32 and token_adapter.is_cuda and token_adapter.is_contiguous()
+    _check(ctx, load().marlaas_segmap_update(ctx.handle, segmap.handle, _ptr(token_adapter), token_adapter.numel(),
+                                             int(n_adapters), _stream_ptr(stream)))
+    segmap.T, segmap.n_adapters = token_adapter.numel(), int(n_adapters)
+
+
+MARLAAS_GRADS_IN_TABLE = ctypes.c_void_p(1)
+
+
+class AdapterTable:
+    """Owns a marlaas_adapter_table and keeps the registered tensors alive."""
+
+    def __init__(self, handle, n_adapters, n_proj):
+        self.handle, self.n_adapters, self.n_proj = handle, n_adapters, n_proj
+        self.tensors = {}
+
+    def close(self):
+        if self.handle:
+            load().marlaas_adapter_table_destroy(self.handle)
+            self.handle = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def marlaas_adapter_table_create(ctx, n_adapters, n_proj=1, max_rank=128):
+    h = ctypes.c_void_p()
+    _check(ctx, load().marlaas_adapter_table_create(ctx.handle, int(n_adapters), int(n_proj), int(max_rank), ctypes.byref(h)))
+    return AdapterTable(h, int(n_adapters), int(n_proj))
+
+
+def marlaas_adapter_table_destroy(table):
+    table.close()
+
+
+def marlaas_adapter_table_update(ctx, table, proj, t, A, B, rank, scale, dA=None, dB=None, stream=None):
+    _check(ctx, load().marlaas_adapter_table_update(ctx.handle, table.handle, int(proj), int(t), _ptr(A), _ptr(B), int(rank),
+                                                    float(scale), _ptr(dA), _ptr(dB), _stream_ptr(stream)))
+    table.tensors[(int(proj), int(t))] = (A, B, dA, dB)
+
+
+def marlaas_adapter_table_version(table, proj=0, t=-1):
+    return int(load().marlaas_adapter_table_version(table.handle, int(proj), int(t)))
+
+
+def marlaas_adapter_table_plan_version(table):
+    return int(load().marlaas_adapter_table_plan_version(table.handle))
+
+
 def marlaas_segmap_export(segmap):
     """(perm, seg_off) as numpy int32 arrays."""
     import numpy as np
@@ -194,9 +273,14 @@ def marlaas_segmap_export(segmap):
 class LoraDesc:
     """Owns a marlaas_lora_desc and keeps the host arrays it points to alive."""
 
-    def __init__(self, x, W, A, B, ranks, scales, segmap, layout=MARLAAS_LAYOUT_MATH, out_dtype=None):
-        n = len(A)
-        self.tensors = (x, W, list(A), list(B), segmap)
+    def __init__(self, x, W, A, B, ranks, scales, segmap, layout=MARLAAS_LAYOUT_MATH, out_dtype=None,
+                 table=None, proj=0):
+        """With `table` (an AdapterTable) the adapters come from the table's projection `proj` and
+        A, B, ranks, scales are ignored (pass None)."""
+        if table is not None:
+            A, B, ranks, scales = [], [], [], []
+        n = len(A) if table is None else table.n_adapters
+        self.tensors = (x, W, list(A), list(B), segmap, table)
         self.c = marlaas_lora_desc()
         T, d_in = x.shape
         d_out = W.shape[1] if layout == MARLAAS_LAYOUT_MATH else W.shape[0]
@@ -206,6 +290,8 @@ class LoraDesc:
         self.c.layout = layout
         self.c.x, self.c.ldx = x.data_ptr(), x.stride(0) if T > 0 else d_in
         self.c.W, self.c.ldw = W.data_ptr(), W.stride(0)
+        self.c.table = table.handle if table is not None else None
+        self.c.proj, self.c.reserved = int(proj), 0
         self._A = (ctypes.c_void_p * max(n, 1))(*[a.data_ptr() for a in A])
         self._B = (ctypes.c_void_p * max(n, 1))(*[b.data_ptr() for b in B])
         self._ranks = (ctypes.c_int32 * max(n, 1))(*[int(r) for r in ranks])
@@ -264,7 +350,9 @@ def marlaas_lora_fwd_multi(ctx, descs, ys, stream=None):
 def marlaas_lora_bwd(ctx, desc, dY, dX=None, dA=None, dB=None, u_saved=None, accumulate=False, stream=None):
     n = desc.shape[3]
     pa = pb = None
-    if dA is not None:
+    if dA is MARLAAS_GRADS_IN_TABLE:
+        pa = pb = MARLAAS_GRADS_IN_TABLE
+    elif dA is not None:
         pa = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in dA])
         pb = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in dB])
     lddy = dY.stride(0) if dY.shape[0] > 0 else dY.shape[1]

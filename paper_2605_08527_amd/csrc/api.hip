@@ -1,31 +1,26 @@
 // Host side of the C ABI: contexts, argument checks, the token grouping
-// object, cached device copies of the per-adapter pointer tables, workspace
-// carving and the order in which the kernels of a forward / backward pass are
-// enqueued.  Nothing here computes on tensors.
+// object, the adapter table object, workspace carving and the order in which
+// the kernels of a forward / backward pass are enqueued.  Nothing here computes
+// on tensors, and the passes (forward, backward, multi-projection forward,
+// adapter update) neither allocate nor wait: everything they need on the device
+// is either in an object the caller created beforehand or in the workspace.
 #include "../../include/marlaas_lora.h"
 #include "common.h"
 
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
-#include <list>
 #include <new>
 #include <string>
 #include <vector>
 
 using namespace marlaas;
 
-struct TableSlot {
-  std::string key;       // raw bytes of the host-side table
-  void* dev = nullptr;
-};
-
 struct marlaas_ctx {
   int device = 0;
   void* ws = nullptr;
   size_t ws_bytes = 0;
   std::string err;
-  std::list<TableSlot> tables;   // most recently used first
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
   std::vector<Span> spans;       // event pairs recorded while profiling is on
@@ -33,10 +28,16 @@ struct marlaas_ctx {
 
 struct marlaas_segmap {
   int device = 0;
-  int64_t T = 0;
+  int64_t T_cap = 0;                // capacity: the device buffers below hold a map of this size
+  int32_t n_cap = 0;
+  int64_t T = 0;                    // current map (after marlaas_segmap_update)
   int32_t n = 0;
-  int32_t* perm_dev = nullptr;      // [T] grouped order (always built)
-  int32_t* seg_off_dev = nullptr;   // [n + 2]
+  bool built = false;
+  int32_t* perm_dev = nullptr;      // [T_cap] grouped order (always built)
+  int32_t* seg_off_dev = nullptr;   // [n_cap + 2]
+  int32_t* block_hist = nullptr;    // counting-sort scratch
+  int32_t* flags_dev = nullptr;     // [2]
+  int32_t* readback = nullptr;      // pinned host: seg_off[n_cap + 2], flags[2]
   std::vector<int32_t> seg_off;     // host copy
   bool identity = false;            // ids were already grouped: kernels skip the gather
   int max_seg = 0;                  // largest adapter segment
@@ -45,8 +46,24 @@ struct marlaas_segmap {
   int n_chunks = 0;
 };
 
-static const size_t TABLE_CACHE_SLOTS = 512;
+// Registered adapters of one layer (or of the projections of one block that share an input):
+// the device tables the kernels read plus a host mirror used for checks and launch planning.
+struct marlaas_adapter_table {
+  int device = 0;
+  int32_t n = 0, n_proj = 0, max_rank = 0;
+  void* dev_block = nullptr;
+  DevTables dev;
+  std::vector<AdapterEntry> host;        // [n_proj * n]; rank 0 = not registered
+  std::vector<GradEntry> hgrads;
+  std::vector<int32_t> hranks;           // same ranks, contiguous (what the planners read)
+  std::vector<float> hscales;
+  std::vector<int64_t> versions;         // per entry: number of updates
+  int64_t updates = 0;                   // of the whole table
+  int64_t plan_version = 0;              // bumped when an update changes a rank
+};
+
 static const size_t WS_ALIGN = 256;
+static const int64_t EXT_CAP_MAX = 1 << 16;   // extended columns a table can describe
 
 static int fail(marlaas_ctx* ctx, int status, const char* fmt, ...) {
   if (ctx) {
@@ -73,6 +90,8 @@ struct ProfSpan {
   marlaas_ctx* ctx; hipStream_t st; hipEvent_t end = nullptr;
   ProfSpan(marlaas_ctx* c, int kernel, hipStream_t s) : ctx(c), st(s) {
     if (!c->profile) return;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) return;   // no timing inside a capture
     hipEvent_t b = nullptr;
     if (hipEventCreate(&b) != hipSuccess) return;
     if (hipEventCreate(&end) != hipSuccess) { (void)hipEventDestroy(b); end = nullptr; return; }
@@ -150,102 +169,87 @@ extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
   if (!ctx) return;
   (void)hipSetDevice(ctx->device);
   drop_spans(ctx);
-  for (auto& s : ctx->tables) (void)hipFree(s.dev);
   delete ctx;
 }
 
-// Device copy of a small host table, cached by content so that the steady
-// state (the same layers called every step) uploads nothing.
-static int cached_table(marlaas_ctx* ctx, const void* host, size_t bytes, const void** dev) {
-  std::string key((const char*)host, bytes);
-  for (auto it = ctx->tables.begin(); it != ctx->tables.end(); ++it) {
-    if (it->key == key) {
-      ctx->tables.splice(ctx->tables.begin(), ctx->tables, it);
-      *dev = ctx->tables.front().dev;
-      return MARLAAS_OK;
-    }
-  }
-  if (ctx->tables.size() >= TABLE_CACHE_SLOTS) {
-    HIP_TRY(ctx, hipDeviceSynchronize());   // a kernel in flight may still read the victim
-    (void)hipFree(ctx->tables.back().dev);
-    ctx->tables.pop_back();
-  }
-  TableSlot s;
-  s.key.swap(key);
-  HIP_TRY(ctx, hipMalloc(&s.dev, bytes));
-  hipError_t e = hipMemcpy(s.dev, host, bytes, hipMemcpyHostToDevice);
+// ------------------------------------------------------------------ segmap
+extern "C" int marlaas_segmap_create(marlaas_ctx* ctx, int64_t T_max, int32_t n_adapters_max, marlaas_segmap** out) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!out) return fail(ctx, MARLAAS_EINVAL, "segmap_create: out is null");
+  *out = nullptr;
+  if (T_max < 0 || T_max > 0x7fffffff - 4096) return fail(ctx, MARLAAS_EINVAL, "segmap_create: T_max=%lld out of range", (long long)T_max);
+  if (n_adapters_max < 0 || n_adapters_max > MARLAAS_MAX_ADAPTERS)
+    return fail(ctx, MARLAAS_EINVAL, "segmap_create: n_adapters_max=%d out of range", n_adapters_max);
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  marlaas_segmap* m = new (std::nothrow) marlaas_segmap();
+  if (!m) return fail(ctx, MARLAAS_ENOMEM, "segmap_create: host allocation failed");
+  m->device = ctx->device; m->T_cap = T_max; m->n_cap = n_adapters_max;
+  const size_t nb = (size_t)(segmap_blocks(T_max) > 0 ? segmap_blocks(T_max) : 1);
+  const size_t nn = (size_t)n_adapters_max + 2;
+  hipError_t e = hipSuccess;
+  do {
+    if ((e = hipMalloc((void**)&m->perm_dev, sizeof(int32_t) * (size_t)(T_max > 0 ? T_max : 1))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->seg_off_dev, sizeof(int32_t) * nn)) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->block_hist, sizeof(int32_t) * nb * nn)) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->flags_dev, 2 * sizeof(int32_t))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->chunks_dev, sizeof(RowChunk) * (size_t)segmap_chunk_bound(T_max, n_adapters_max))) != hipSuccess) break;
+    e = hipHostMalloc((void**)&m->readback, sizeof(int32_t) * (nn + 2), hipHostMallocDefault);
+  } while (0);
   if (e != hipSuccess) {
-    (void)hipFree(s.dev);
-    return fail(ctx, MARLAAS_EHIP, "table upload failed: %s", hipGetErrorString(e));
+    marlaas_segmap_destroy(m);
+    return fail(ctx, MARLAAS_ENOMEM, "segmap_create: %s", hipGetErrorString(e));
   }
-  ctx->tables.push_front(std::move(s));
-  *dev = ctx->tables.front().dev;
+  *out = m;
   return MARLAAS_OK;
 }
 
-// ------------------------------------------------------------------ segmap
-extern "C" int marlaas_segmap_build(marlaas_ctx* ctx, const int32_t* token_adapter, int64_t T,
-                                    int32_t n_adapters, void* stream, marlaas_segmap** out) {
+extern "C" int marlaas_segmap_update(marlaas_ctx* ctx, marlaas_segmap* m, const int32_t* token_adapter, int64_t T,
+                                     int32_t n_adapters, void* stream) {
   if (!ctx) return MARLAAS_EINVAL;
-  if (!out) return fail(ctx, MARLAAS_EINVAL, "segmap_build: out is null");
-  *out = nullptr;
-  if (T < 0 || T > 0x7fffffff - 4096) return fail(ctx, MARLAAS_EINVAL, "segmap_build: T=%lld out of range", (long long)T);
-  if (n_adapters < 0 || n_adapters > MARLAAS_MAX_ADAPTERS)
-    return fail(ctx, MARLAAS_EINVAL, "segmap_build: n_adapters=%d out of range", n_adapters);
-  if (T > 0 && !token_adapter) return fail(ctx, MARLAAS_EINVAL, "segmap_build: token_adapter is null");
+  if (!m) return fail(ctx, MARLAAS_EINVAL, "segmap_update: map is null");
+  if (T < 0 || T > m->T_cap) return fail(ctx, MARLAAS_ESHAPE, "segmap_update: T=%lld exceeds the map's capacity %lld", (long long)T, (long long)m->T_cap);
+  if (n_adapters < 0 || n_adapters > m->n_cap)
+    return fail(ctx, MARLAAS_ESHAPE, "segmap_update: n_adapters=%d exceeds the map's capacity %d", n_adapters, m->n_cap);
+  if (T > 0 && !token_adapter) return fail(ctx, MARLAAS_EINVAL, "segmap_update: token_adapter is null");
+  if (m->device != ctx->device) return fail(ctx, MARLAAS_EINVAL, "segmap_update: map belongs to device %d", m->device);
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   hipStream_t st = (hipStream_t)stream;
-  marlaas_segmap* m = new (std::nothrow) marlaas_segmap();
-  if (!m) return fail(ctx, MARLAAS_ENOMEM, "segmap_build: host allocation failed");
-  m->device = ctx->device; m->T = T; m->n = n_adapters;
-  const int nblk = segmap_blocks(T);
-  int32_t* block_hist = nullptr;
-  int32_t* flags = nullptr;
-  int status = MARLAAS_OK;
-  int32_t hflags[2] = {0, 0};
-  m->seg_off.assign((size_t)n_adapters + 2, 0);
-  hipError_t e = hipSuccess;
-  do {
-    if ((e = hipMalloc((void**)&m->perm_dev, sizeof(int32_t) * (size_t)(T > 0 ? T : 1))) != hipSuccess) break;
-    if ((e = hipMalloc((void**)&m->seg_off_dev, sizeof(int32_t) * ((size_t)n_adapters + 2))) != hipSuccess) break;
-    if ((e = hipMalloc((void**)&block_hist, sizeof(int32_t) * (size_t)(nblk > 0 ? nblk : 1) * ((size_t)n_adapters + 1))) != hipSuccess) break;
-    if ((e = hipMalloc((void**)&flags, 2 * sizeof(int32_t))) != hipSuccess) break;
-    if ((e = launch_segmap(token_adapter, T, n_adapters, m->perm_dev, m->seg_off_dev, block_hist, flags, st)) != hipSuccess) break;
-    if ((e = hipMemcpyAsync(hflags, flags, sizeof hflags, hipMemcpyDeviceToHost, st)) != hipSuccess) break;
-    if ((e = hipMemcpyAsync(m->seg_off.data(), m->seg_off_dev, sizeof(int32_t) * m->seg_off.size(), hipMemcpyDeviceToHost, st)) != hipSuccess) break;
-    e = hipStreamSynchronize(st);
-  } while (0);
-  (void)hipFree(block_hist);
-  (void)hipFree(flags);
-  if (e != hipSuccess) status = fail(ctx, MARLAAS_EHIP, "segmap_build: %s", hipGetErrorString(e));
-  else if (hflags[0]) status = fail(ctx, MARLAAS_EINVAL, "segmap_build: token id outside [-1, %d)", n_adapters);
-  if (status != MARLAAS_OK) { marlaas_segmap_destroy(m); return status; }
-  m->identity = hflags[1] == 0;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone)
+    return fail(ctx, MARLAAS_EUNSUPPORTED, "segmap_update reads the segment sizes back and cannot run inside a stream capture");
+  m->built = false;
+  const size_t nn = (size_t)n_adapters + 2;
+  HIP_TRY(ctx, launch_segmap(token_adapter, T, n_adapters, m->perm_dev, m->seg_off_dev, m->block_hist, m->flags_dev,
+                             m->chunks_dev, st));
+  HIP_TRY(ctx, hipMemcpyAsync(m->readback, m->seg_off_dev, sizeof(int32_t) * nn, hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipMemcpyAsync(m->readback + nn, m->flags_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(ctx, hipStreamSynchronize(st));
+  if (m->readback[nn]) return fail(ctx, MARLAAS_EINVAL, "segmap: token id outside [-1, %d)", n_adapters);
+  m->T = T; m->n = n_adapters;
+  m->seg_off.assign(m->readback, m->readback + nn);
+  m->identity = m->readback[nn + 1] == 0;
+  m->max_seg = 0;
   for (int t = 0; t < n_adapters; ++t) {
     int len = m->seg_off[t + 1] - m->seg_off[t];
     if (len > m->max_seg) m->max_seg = len;
   }
   m->T_lora = m->seg_off[n_adapters];
-  // row chunks: segment t split into pieces of ROW_CHUNK rows; the rows without an adapter last
-  std::vector<RowChunk> chunks;
-  for (int t = 0; t <= n_adapters; ++t) {
-    const int32_t end = t < n_adapters ? m->seg_off[t + 1] : (int32_t)T;
-    for (int32_t row0 = m->seg_off[t]; row0 < end; row0 += ROW_CHUNK) {
-      RowChunk c;
-      c.row0 = row0; c.nrows = end - row0 < ROW_CHUNK ? end - row0 : ROW_CHUNK; c.t = t < n_adapters ? t : -1; c.pad = 0;
-      chunks.push_back(c);
-    }
-  }
-  m->n_chunks = (int)chunks.size();
-  if (m->n_chunks > 0) {
-    e = hipMalloc((void**)&m->chunks_dev, sizeof(RowChunk) * chunks.size());
-    if (e == hipSuccess) e = hipMemcpy(m->chunks_dev, chunks.data(), sizeof(RowChunk) * chunks.size(), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-      status = fail(ctx, MARLAAS_EHIP, "segmap_build: %s", hipGetErrorString(e));
-      marlaas_segmap_destroy(m);
-      return status;
-    }
-  }
+  m->n_chunks = (int)segmap_chunk_count(m->seg_off.data(), n_adapters);
+  m->built = true;
+  return MARLAAS_OK;
+}
+
+extern "C" int marlaas_segmap_build(marlaas_ctx* ctx, const int32_t* token_adapter, int64_t T,
+                                    int32_t n_adapters, void* stream, marlaas_segmap** out) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!out) return fail(ctx, MARLAAS_EINVAL, "segmap_build: out is null");
+  *out = nullptr;
+  if (T > 0 && !token_adapter) return fail(ctx, MARLAAS_EINVAL, "segmap_build: token_adapter is null");
+  marlaas_segmap* m = nullptr;
+  int rc = marlaas_segmap_create(ctx, T, n_adapters, &m);
+  if (rc != MARLAAS_OK) return rc;
+  rc = marlaas_segmap_update(ctx, m, token_adapter, T, n_adapters, stream);
+  if (rc != MARLAAS_OK) { marlaas_segmap_destroy(m); return rc; }
   *out = m;
   return MARLAAS_OK;
 }
@@ -255,12 +259,15 @@ extern "C" void marlaas_segmap_destroy(marlaas_segmap* map) {
   (void)hipSetDevice(map->device);
   (void)hipFree(map->perm_dev);
   (void)hipFree(map->seg_off_dev);
+  (void)hipFree(map->block_hist);
+  (void)hipFree(map->flags_dev);
   (void)hipFree(map->chunks_dev);
+  if (map->readback) (void)hipHostFree(map->readback);
   delete map;
 }
 
 extern "C" int marlaas_segmap_export(const marlaas_segmap* map, int32_t* perm, int32_t* seg_off) {
-  if (!map) return MARLAAS_EINVAL;
+  if (!map || !map->built) return MARLAAS_EINVAL;
   if (seg_off) memcpy(seg_off, map->seg_off.data(), sizeof(int32_t) * map->seg_off.size());
   if (perm && map->T > 0) {
     if (hipSetDevice(map->device) != hipSuccess) return MARLAAS_EHIP;
@@ -270,17 +277,112 @@ extern "C" int marlaas_segmap_export(const marlaas_segmap* map, int32_t* perm, i
   return MARLAAS_OK;
 }
 
+// ------------------------------------------------------------------ adapter table
+extern "C" int marlaas_adapter_table_create(marlaas_ctx* ctx, int32_t n_adapters, int32_t n_proj, int32_t max_rank,
+                                            marlaas_adapter_table** out) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!out) return fail(ctx, MARLAAS_EINVAL, "adapter_table_create: out is null");
+  *out = nullptr;
+  if (n_adapters < 1 || n_adapters > MARLAAS_MAX_ADAPTERS) return fail(ctx, MARLAAS_EINVAL, "adapter_table_create: n_adapters=%d out of range", n_adapters);
+  if (n_proj < 1 || n_proj > MARLAAS_MAX_PROJ) return fail(ctx, MARLAAS_EINVAL, "adapter_table_create: n_proj must be 1..%d", MARLAAS_MAX_PROJ);
+  if (max_rank < 1 || max_rank > MARLAAS_MAX_RANK) return fail(ctx, MARLAAS_EINVAL, "adapter_table_create: max_rank must be 1..%d", MARLAAS_MAX_RANK);
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  marlaas_adapter_table* tb = new (std::nothrow) marlaas_adapter_table();
+  if (!tb) return fail(ctx, MARLAAS_ENOMEM, "adapter_table_create: host allocation failed");
+  tb->device = ctx->device; tb->n = n_adapters; tb->n_proj = n_proj; tb->max_rank = max_rank;
+  const int64_t P = (int64_t)n_adapters * n_proj;
+  int64_t cap = P * max_rank;
+  if (cap > EXT_CAP_MAX) cap = EXT_CAP_MAX;
+  const size_t bytes = dev_tables_bytes(P, cap);
+  hipError_t e = hipMalloc(&tb->dev_block, bytes);
+  if (e == hipSuccess) e = hipMemset(tb->dev_block, 0, bytes);     // creation is not a pass: a plain blocking fill
+  if (e != hipSuccess) {
+    marlaas_adapter_table_destroy(tb);
+    return fail(ctx, MARLAAS_ENOMEM, "adapter_table_create: %s", hipGetErrorString(e));
+  }
+  tb->dev = dev_tables_carve(tb->dev_block, P, cap);
+  AdapterEntry z; z.A = nullptr; z.B = nullptr; z.rank = 0; z.scale = 0.f;
+  GradEntry zg; zg.dA = nullptr; zg.dB = nullptr;
+  tb->host.assign((size_t)P, z);
+  tb->hgrads.assign((size_t)P, zg);
+  tb->hranks.assign((size_t)P, 0);
+  tb->hscales.assign((size_t)P, 0.f);
+  tb->versions.assign((size_t)P, 0);
+  *out = tb;
+  return MARLAAS_OK;
+}
+
+extern "C" void marlaas_adapter_table_destroy(marlaas_adapter_table* tb) {
+  if (!tb) return;
+  (void)hipSetDevice(tb->device);
+  (void)hipFree(tb->dev_block);
+  delete tb;
+}
+
+extern "C" int marlaas_adapter_table_update(marlaas_ctx* ctx, marlaas_adapter_table* tb, int32_t proj, int32_t t,
+                                            const void* A, const void* B, int32_t rank, float scale,
+                                            void* dA, void* dB, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!tb) return fail(ctx, MARLAAS_EINVAL, "adapter_table_update: table is null");
+  if (tb->device != ctx->device) return fail(ctx, MARLAAS_EINVAL, "adapter_table_update: table belongs to device %d", tb->device);
+  if (proj < 0 || proj >= tb->n_proj || t < 0 || t >= tb->n)
+    return fail(ctx, MARLAAS_EINVAL, "adapter_table_update: (projection %d, adapter %d) outside the table (%d x %d)", proj, t, tb->n_proj, tb->n);
+  if (!A || !B) return fail(ctx, MARLAAS_EINVAL, "adapter_table_update: null factor");
+  if (!aligned16(A) || !aligned16(B)) return fail(ctx, MARLAAS_EALIGN, "adapter_table_update: factors must be 16-byte aligned");
+  if (rank < 1 || rank > tb->max_rank) return fail(ctx, MARLAAS_EINVAL, "adapter_table_update: rank %d, table holds 1..%d", rank, tb->max_rank);
+  if ((dA == nullptr) != (dB == nullptr)) return fail(ctx, MARLAAS_EINVAL, "adapter_table_update: dA and dB must both be given or both be null");
+  if (dA && (!aligned16(dA) || !aligned16(dB))) return fail(ctx, MARLAAS_EALIGN, "adapter_table_update: gradient buffers must be 16-byte aligned");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t i = (int64_t)proj * tb->n + t;
+  AdapterEntry e; e.A = A; e.B = B; e.rank = rank; e.scale = scale;
+  GradEntry g; g.dA = (float*)dA; g.dB = (float*)dB;
+  const bool rank_changed = tb->hranks[i] != rank;
+  HIP_TRY(ctx, enqueue_write_entries(tb->dev, i, 1, &e, st));
+  HIP_TRY(ctx, enqueue_write_grads(tb->dev, i, 1, &g, st));
+  if (rank_changed) HIP_TRY(ctx, enqueue_derive(tb->dev, (int64_t)tb->n * tb->n_proj, st));
+  tb->host[i] = e; tb->hgrads[i] = g; tb->hranks[i] = rank; tb->hscales[i] = scale;
+  ++tb->versions[i];
+  ++tb->updates;
+  if (rank_changed) ++tb->plan_version;
+  return MARLAAS_OK;
+}
+
+extern "C" int64_t marlaas_adapter_table_version(const marlaas_adapter_table* tb, int32_t proj, int32_t t) {
+  if (!tb) return -1;
+  if (t < 0) return tb->updates;
+  if (proj < 0 || proj >= tb->n_proj || t >= tb->n) return -1;
+  return tb->versions[(size_t)proj * tb->n + t];
+}
+
+extern "C" int64_t marlaas_adapter_table_plan_version(const marlaas_adapter_table* tb) {
+  return tb ? tb->plan_version : -1;
+}
+
 // ------------------------------------------------------------------ descriptor checks
+// Ranks and scales of a descriptor's adapters (host memory): from its table when it has one.
+static const int32_t* ranks_of(const marlaas_lora_desc* d) {
+  return d->table ? d->table->hranks.data() + (size_t)d->proj * d->table->n : d->ranks;
+}
+
 static int max_rank_of(const marlaas_lora_desc* d) {
+  const int32_t* ranks = ranks_of(d);
   int mr = 0;
-  for (int t = 0; t < d->n_adapters; ++t) if (d->ranks[t] > mr) mr = d->ranks[t];
+  for (int t = 0; t < d->n_adapters; ++t) if (ranks[t] > mr) mr = ranks[t];
   return mr;
 }
 
 static int sum_ranks_of(const marlaas_lora_desc* d) {
+  const int32_t* ranks = ranks_of(d);
   int64_t sum = 0;
-  for (int t = 0; t < d->n_adapters; ++t) sum += d->ranks[t];
+  for (int t = 0; t < d->n_adapters; ++t) sum += ranks[t];
   return sum > 0x7fffffff ? 0x7fffffff : (int)sum;
+}
+
+static bool ranks_mult8_of(const marlaas_lora_desc* d) {
+  const int32_t* ranks = ranks_of(d);
+  for (int t = 0; t < d->n_adapters; ++t) if (ranks[t] & 7) return false;
+  return true;
 }
 
 static int check_sizes(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
@@ -293,30 +395,49 @@ static int check_sizes(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   if (d->out_dtype != MARLAAS_BF16 && d->out_dtype != MARLAAS_F32) return fail(ctx, MARLAAS_EINVAL, "bad out_dtype");
   if (d->layout != MARLAAS_LAYOUT_MATH && d->layout != MARLAAS_LAYOUT_TORCH) return fail(ctx, MARLAAS_EINVAL, "bad layout");
   if ((d->d_in & 7) || (d->d_out & 7)) return fail(ctx, MARLAAS_EALIGN, "d_in and d_out must be multiples of 8");
-  if (d->n_adapters > 0) {
+  if (!d->map) return fail(ctx, MARLAAS_EINVAL, "segment map is null");
+  if (!d->map->built) return fail(ctx, MARLAAS_EINVAL, "segment map holds no map (marlaas_segmap_update failed or was never called)");
+  if (d->map->T != d->T || d->map->n != d->n_adapters)
+    return fail(ctx, MARLAAS_ESHAPE, "segment map was built for T=%lld, n=%d", (long long)d->map->T, d->map->n);
+  if (d->table) {
+    const marlaas_adapter_table* tb = d->table;
+    if (tb->n != d->n_adapters) return fail(ctx, MARLAAS_ESHAPE, "adapter table holds %d adapters, descriptor says %d", tb->n, d->n_adapters);
+    if (d->proj < 0 || d->proj >= tb->n_proj) return fail(ctx, MARLAAS_EINVAL, "projection %d outside the adapter table (%d)", d->proj, tb->n_proj);
+    // an adapter that no token uses may be unregistered (rank 0: the kernels skip it)
+    const int32_t* ranks = ranks_of(d);
+    for (int t = 0; t < d->n_adapters; ++t)
+      if (ranks[t] == 0 && d->map->seg_off[t + 1] > d->map->seg_off[t])
+        return fail(ctx, MARLAAS_EINVAL, "adapter %d has tokens but is not registered in the adapter table", t);
+  } else if (d->n_adapters > 0) {
     if (!d->ranks || !d->scales) return fail(ctx, MARLAAS_EINVAL, "ranks / scales are null");
     for (int t = 0; t < d->n_adapters; ++t)
       if (d->ranks[t] < 1 || d->ranks[t] > MARLAAS_MAX_RANK)
         return fail(ctx, MARLAAS_EINVAL, "rank of adapter %d is %d, must be 1..%d", t, d->ranks[t], MARLAAS_MAX_RANK);
   }
-  if (!d->map) return fail(ctx, MARLAAS_EINVAL, "segment map is null");
-  if (d->map->T != d->T || d->map->n != d->n_adapters)
-    return fail(ctx, MARLAAS_ESHAPE, "segment map was built for T=%lld, n=%d", (long long)d->map->T, d->map->n);
   return MARLAAS_OK;
 }
 
 extern "C" int64_t marlaas_u_stride(const marlaas_lora_desc* d) {
   if (!d || d->n_adapters < 0 || d->n_adapters > MARLAAS_MAX_ADAPTERS) return 0;
   if (d->n_adapters == 0) return 16;
-  if (!d->ranks) return 0;
+  if (d->table) {
+    if (d->table->n != d->n_adapters || d->proj < 0 || d->proj >= d->table->n_proj) return 0;
+  } else if (!d->ranks) {
+    return 0;
+  }
   int mr = max_rank_of(d);
-  if (mr < 1 || mr > MARLAAS_MAX_RANK) return 0;
+  if (mr < 0 || mr > MARLAAS_MAX_RANK) return 0;
+  if (mr == 0) return d->table ? 16 : 0;
   return (mr + 15) & ~15;
 }
+
+// Extended columns the workspace copy of a descriptor's tables can describe.
+static int64_t ws_ext_cap(int64_t n_ext) { return n_ext < EXT_CAP_MAX ? n_ext : EXT_CAP_MAX; }
 
 struct WsPlan {
   size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;   // part: reused by every kernel with partial sums
   size_t wt_off = 0, wt_bytes = 0;   // transposed copy of the weight (large batches, output-contiguous storage)
+  size_t tab_off = 0, tab_bytes = 0; // per-call copy of the adapter tables (descriptors without a table object)
 };
 
 static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
@@ -347,6 +468,10 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
     p.wt_bytes = align_up(wt, WS_ALIGN);
     p.wt_off = off; off += p.wt_bytes;
   }
+  if (!d->table && d->n_adapters > 0) {
+    p.tab_bytes = dev_tables_bytes(d->n_adapters, ws_ext_cap(n_ext));
+    p.tab_off = off; off += p.tab_bytes;
+  }
   p.total = off;
   return p;
 }
@@ -374,7 +499,9 @@ static int check_tensors(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   const int64_t wcols = d->layout == MARLAAS_LAYOUT_MATH ? d->d_out : d->d_in;
   if (d->ldw < wcols || (d->ldw * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldw=%lld", (long long)d->ldw);
   if (d->ldw > (1 << 22)) return fail(ctx, MARLAAS_EINVAL, "ldw=%lld is above 4194304", (long long)d->ldw);
-  if (d->n_adapters > 0) {
+  if (d->table) {
+    if (d->table->device != ctx->device) return fail(ctx, MARLAAS_EINVAL, "adapter table belongs to device %d", d->table->device);
+  } else if (d->n_adapters > 0) {
     if (!d->A || !d->B) return fail(ctx, MARLAAS_EINVAL, "A / B pointer arrays are null");
     for (int t = 0; t < d->n_adapters; ++t) {
       if (!d->A[t] || !d->B[t]) return fail(ctx, MARLAAS_EINVAL, "adapter %d has a null factor", t);
@@ -384,46 +511,73 @@ static int check_tensors(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   return MARLAAS_OK;
 }
 
-static int adapter_table(marlaas_ctx* ctx, const marlaas_lora_desc* d, const AdapterEntry** dev) {
-  *dev = nullptr;
+// Where the kernels of one call find its adapters.
+struct Bank {
+  const AdapterEntry* entries = nullptr;   // device: this call's adapters, [n_adapters]
+  const GradEntry* grads = nullptr;
+  DevTables all;                           // the whole bank (a table object's, or the workspace copy)
+  int t0 = 0;                              // index of entries[0] in the bank
+  int ext_base = 0;                        // first extended column of this call in the bank's column space
+  int n_ext = 0;                           // this call's extended columns (sum of its ranks)
+  bool mult8 = true;
+  bool in_ws = false;                      // tables are a per-call copy in the workspace
+};
+
+// Resolve a descriptor's tables.  Without a table object the entries are written into the
+// workspace slice `ws_tab` by a small kernel launch on the caller's stream (payload in the kernel
+// arguments); with one, nothing is enqueued.
+static int resolve_bank(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* ws_tab, size_t ws_tab_bytes,
+                        hipStream_t st, Bank* b) {
+  *b = Bank();
   if (d->n_adapters == 0) return MARLAAS_OK;
+  b->n_ext = sum_ranks_of(d);
+  b->mult8 = ranks_mult8_of(d);
+  if (d->table) {
+    const marlaas_adapter_table* tb = d->table;
+    b->all = tb->dev;
+    b->t0 = d->proj * tb->n;
+    b->entries = tb->dev.entries + b->t0;
+    b->grads = tb->dev.grads + b->t0;
+    int64_t base = 0;
+    for (int i = 0; i < b->t0; ++i) base += tb->hranks[i];
+    b->ext_base = (int)base;
+    return MARLAAS_OK;
+  }
+  const size_t need = dev_tables_bytes(d->n_adapters, ws_ext_cap(b->n_ext));
+  if (!ws_tab || ws_tab_bytes < need)
+    return fail(ctx, MARLAAS_ENOMEM, "a descriptor without an adapter table needs workspace for its tables (%zu bytes)", need);
+  b->all = dev_tables_carve(ws_tab, d->n_adapters, ws_ext_cap(b->n_ext));
+  b->entries = b->all.entries;
+  b->grads = b->all.grads;
+  b->in_ws = true;
   std::vector<AdapterEntry> host((size_t)d->n_adapters);
-  memset(host.data(), 0, host.size() * sizeof(AdapterEntry));
   for (int t = 0; t < d->n_adapters; ++t) {
     host[t].A = d->A[t]; host[t].B = d->B[t]; host[t].rank = d->ranks[t]; host[t].scale = d->scales[t];
   }
-  return cached_table(ctx, host.data(), host.size() * sizeof(AdapterEntry), (const void**)dev);
-}
-
-// Tables of the fused shrink: rank offsets and the (adapter, rank index) of every extended column.
-static int fuse_tables(marlaas_ctx* ctx, const marlaas_lora_desc* d, GemmFuse* f) {
-  const int n = d->n_adapters;
-  std::vector<int32_t> host((size_t)n + 1);
-  bool mult8 = true;
-  int32_t off = 0;
-  for (int t = 0; t < n; ++t) { host[t] = off; off += d->ranks[t]; if (d->ranks[t] & 7) mult8 = false; }
-  host[n] = off;
-  // offsets padded to an even count, so that the column pairs that follow stay 8-byte aligned
-  if (host.size() & 1) host.push_back(0);
-  const size_t cols_at = host.size();
-  host.resize(cols_at + 2 * (size_t)off);
-  for (int t = 0, e = 0; t < n; ++t)
-    for (int q = 0; q < d->ranks[t]; ++q, ++e) { host[cols_at + 2 * e] = t; host[cols_at + 2 * e + 1] = q; }
-  const void* dev = nullptr;
-  int rc = cached_table(ctx, host.data(), host.size() * sizeof(int32_t), &dev);
-  if (rc != MARLAAS_OK) return rc;
-  f->roff = (const int32_t*)dev;
-  f->cols = (const ExtCol*)((const int32_t*)dev + cols_at);
-  f->n_ext = off;
-  f->ranks_mult8 = mult8;
-  f->u_out = nullptr;
+  HIP_TRY(ctx, enqueue_write_entries(b->all, 0, d->n_adapters, host.data(), st));
   return MARLAAS_OK;
 }
 
+// The fused shrink reads rank offsets and extended columns; a workspace copy derives them now.
+static int bank_fuse(marlaas_ctx* ctx, const Bank& b, int n_adapters, hipStream_t st, GemmFuse* f) {
+  if (b.in_ws) HIP_TRY(ctx, enqueue_derive(b.all, n_adapters, st));
+  f->roff = b.all.roff + b.t0;
+  f->cols = b.all.cols + b.ext_base;
+  f->n_ext = b.n_ext;
+  f->ranks_mult8 = b.mult8;
+  f->u_out = nullptr;
+  f->t0 = b.t0;
+  f->ext_base = b.ext_base;
+  return MARLAAS_OK;
+}
+
+static bool bank_can_fuse(const Bank& b) {
+  return b.n_ext > 0 && (int64_t)b.ext_base + b.n_ext <= b.all.ext_cap;
+}
+
 // ------------------------------------------------------------------ forward
-extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy,
-                                void* u_save, void* stream) {
-  if (!ctx) return MARLAAS_EINVAL;
+static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy, void* u_save, void* stream,
+                    void* ws, size_t ws_bytes) {
   int rc = check_sizes(ctx, d);
   if (rc != MARLAAS_OK) return rc;
   if (d->T == 0) return MARLAAS_OK;
@@ -439,15 +593,16 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
   float* u = (float*)u_save;
   const bool lora = d->n_adapters > 0 && map->T_lora > 0;
   WsPlan p = plan_workspace(d, 0);
-  const bool have_ws = ctx->ws && ctx->ws_bytes >= p.total;
+  const bool have_ws = ws && ws_bytes >= p.total;
   if (lora && !u) {
     if (!have_ws)
-      return fail(ctx, MARLAAS_ENOMEM, "forward needs %zu workspace bytes, have %zu", p.total, ctx->ws_bytes);
-    u = (float*)((char*)ctx->ws + p.u_off);
+      return fail(ctx, MARLAAS_ENOMEM, "forward needs %zu workspace bytes, have %zu", p.total, ws_bytes);
+    u = (float*)((char*)ws + p.u_off);
   }
-  float* part = (have_ws && p.part_bytes) ? (float*)((char*)ctx->ws + p.part_off) : nullptr;
-  const AdapterEntry* table = nullptr;
-  if ((rc = adapter_table(ctx, d, &table)) != MARLAAS_OK) return rc;
+  float* part = (have_ws && p.part_bytes) ? (float*)((char*)ws + p.part_off) : nullptr;
+  Bank bank;
+  if (lora && (rc = resolve_bank(ctx, d, have_ws ? (char*)ws + p.tab_off : nullptr, p.tab_bytes, st, &bank)) != MARLAAS_OK) return rc;
+  const AdapterEntry* table = bank.entries;
   const int32_t* perm = map->identity ? nullptr : map->perm_dev;
   // forward contracts over d_in: math W[d_in,d_out] is [contraction, output] (NN), torch is NT;
   // A_t follows W for the shrink, B_t follows W for the expand.
@@ -457,13 +612,10 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
     // small batches: the GEMM computes the shrink itself and no shrink kernel runs
     GemmFuse fuse;
     bool fused = false;
-    if (lora && part) {
-      const int n_ext = sum_ranks_of(d);
-      bool mult8 = true;
-      for (int t = 0; t < d->n_adapters; ++t) if (d->ranks[t] & 7) mult8 = false;
-      fused = gemm_can_fuse_shrink(form, d->T, d->d_in, d->d_out, n_ext, mult8, p.part_bytes);
+    if (lora && part && bank_can_fuse(bank)) {
+      fused = gemm_can_fuse_shrink(form, d->T, d->d_in, d->d_out, bank.n_ext, bank.mult8, p.part_bytes);
       if (fused) {
-        if ((rc = fuse_tables(ctx, d, &fuse)) != MARLAAS_OK) return rc;
+        if ((rc = bank_fuse(ctx, bank, d->n_adapters, st, &fuse)) != MARLAAS_OK) return rc;
         fuse.u_out = u;
       }
     }
@@ -473,7 +625,7 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
-                                  fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
+                                  fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ws + p.wt_off) : nullptr,
                                   p.wt_bytes, st));
   } else {
     if (lora)
@@ -484,6 +636,12 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
                                  rs, y, ldy, out_f32, st));
   }
   return MARLAAS_OK;
+}
+
+extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy,
+                                void* u_save, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  return fwd_impl(ctx, d, y, ldy, u_save, stream, ctx->ws, ctx->ws_bytes);
 }
 
 // ------------------------------------------------------------------ forward, several projections
@@ -498,8 +656,18 @@ static int check_multi(marlaas_ctx* ctx, const marlaas_lora_desc* descs, int32_t
     if (b.T != a.T || b.d_in != a.d_in || b.x != a.x || b.ldx != a.ldx || b.in_dtype != a.in_dtype ||
         b.out_dtype != a.out_dtype || b.layout != a.layout || b.n_adapters != a.n_adapters || b.map != a.map)
       return fail(ctx, MARLAAS_ESHAPE, "projection %d differs from projection 0 in T, d_in, x, dtypes, layout, n_adapters or map", p);
+    if ((b.table == nullptr) != (a.table == nullptr))
+      return fail(ctx, MARLAAS_EINVAL, "either every projection or none refers to an adapter table");
   }
   return MARLAAS_OK;
+}
+
+// One table object whose projections 0 .. n_proj - 1 are the call's, in order: its combined tables serve the fused pass.
+static bool multi_shares_table(const marlaas_lora_desc* descs, int32_t n_proj) {
+  if (!descs[0].table || descs[0].table->n_proj != n_proj) return false;
+  for (int p = 0; p < n_proj; ++p)
+    if (descs[p].table != descs[0].table || descs[p].proj != p) return false;
+  return true;
 }
 
 static void multi_proj_host(const marlaas_lora_desc* descs, int32_t n_proj, void* const* y, const int64_t* ldy,
@@ -516,9 +684,23 @@ static void multi_proj_host(const marlaas_lora_desc* descs, int32_t n_proj, void
     e.tile0 = tile0; e.fin0 = fin0; e.tab0 = p * descs[p].n_adapters;
     tile0 += (int32_t)((descs[p].d_out + 127) / 128);
     fin0 += (int32_t)((descs[p].d_out + 511) / 512);
-    for (int t = 0; t < descs[p].n_adapters; ++t) { ext += descs[p].ranks[t]; if (descs[p].ranks[t] & 7) *mult8 = false; }
+    const int32_t* ranks = ranks_of(&descs[p]);
+    for (int t = 0; t < descs[p].n_adapters; ++t) { ext += ranks[t]; if (ranks[t] & 7) *mult8 = false; }
   }
   *n_ext = ext > 0x7fffffff ? 0x7fffffff : (int)ext;
+}
+
+// Workspace of the fused multi-projection pass: partial sums, then (descriptors without a shared
+// table object) the combined tables.
+struct MultiPlan { size_t part_bytes = 0, tab_off = 0, tab_bytes = 0, total = 0; };
+static MultiPlan plan_multi(const marlaas_lora_desc* descs, int32_t n_proj, const ProjEntry* proj, int n_ext, bool lora) {
+  MultiPlan m;
+  m.part_bytes = align_up(gemm_multi_bytes(descs[0].T, descs[0].d_in, proj, n_proj, lora ? n_ext : 0), WS_ALIGN);
+  m.tab_off = m.part_bytes;
+  if (lora && !multi_shares_table(descs, n_proj))
+    m.tab_bytes = dev_tables_bytes((int64_t)n_proj * descs[0].n_adapters, ws_ext_cap(n_ext));
+  m.total = m.tab_off + m.tab_bytes;
+  return m;
 }
 
 extern "C" size_t marlaas_workspace_bytes_multi(const marlaas_lora_desc* descs, int32_t n_proj) {
@@ -533,8 +715,8 @@ extern "C" size_t marlaas_workspace_bytes_multi(const marlaas_lora_desc* descs, 
     int n_ext = 0; bool mult8 = true;
     multi_proj_host(descs, n_proj, nullptr, nullptr, &proj, &n_ext, &mult8);
     const bool lora = descs[0].n_adapters > 0 && descs[0].map->T_lora > 0;
-    const size_t fused = align_up(gemm_multi_bytes(descs[0].T, descs[0].d_in, proj.data(), n_proj, lora ? n_ext : 0), WS_ALIGN);
-    if (fused > need) need = fused;
+    const MultiPlan m = plan_multi(descs, n_proj, proj.data(), n_ext, lora);
+    if (m.part_bytes > 0 && m.total > need) need = m.total;
   }
   return need;
 }
@@ -560,8 +742,15 @@ extern "C" int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc*
   int n_ext = 0; bool mult8 = true;
   multi_proj_host(descs, n_proj, y, ldy, &proj, &n_ext, &mult8);
   if (!lora) n_ext = 0;
-  bool fused = n_proj > 1 && d0->in_dtype == MARLAAS_BF16 && ctx->ws != nullptr;
-  if (fused) fused = gemm_multi_ok(form, d0->T, d0->d_in, proj.data(), n_proj, n_ext, mult8, ctx->ws_bytes);
+  const bool shared = multi_shares_table(descs, n_proj);
+  // descriptors that refer to tables, but not to one table in projection order, have no combined tables
+  bool fused = n_proj > 1 && d0->in_dtype == MARLAAS_BF16 && ctx->ws != nullptr && (!lora || shared || !d0->table);
+  MultiPlan mp;
+  if (fused) {
+    mp = plan_multi(descs, n_proj, proj.data(), n_ext, lora);
+    fused = ctx->ws_bytes >= mp.total && gemm_multi_ok(form, d0->T, d0->d_in, proj.data(), n_proj, n_ext, mult8, mp.part_bytes);
+    if (fused && lora && n_ext > (shared ? d0->table->dev.ext_cap : EXT_CAP_MAX)) fused = false;
+  }
   if (!fused) {
     // sizes outside the fused path: one projection after the other (same stream, same scratch)
     for (int p = 0; p < n_proj; ++p)
@@ -575,38 +764,28 @@ extern "C" int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc*
   const AdapterEntry* table = nullptr;
   GemmFuse fuse;
   if (lora) {
-    std::vector<AdapterEntry> host((size_t)n_proj * n);
-    memset(host.data(), 0, host.size() * sizeof(AdapterEntry));
-    for (int p = 0; p < n_proj; ++p)
-      for (int t = 0; t < n; ++t) {
-        AdapterEntry& e = host[(size_t)p * n + t];
-        e.A = descs[p].A[t]; e.B = descs[p].B[t]; e.rank = descs[p].ranks[t]; e.scale = descs[p].scales[t];
-      }
-    if ((rc = cached_table(ctx, host.data(), host.size() * sizeof(AdapterEntry), (const void**)&table)) != MARLAAS_OK) return rc;
-    std::vector<int32_t> ft((size_t)n_proj * n + 1);
-    int32_t off = 0;
-    for (int p = 0; p < n_proj; ++p)
-      for (int t = 0; t < n; ++t) { ft[(size_t)p * n + t] = off; off += descs[p].ranks[t]; }
-    ft[(size_t)n_proj * n] = off;
-    if (ft.size() & 1) ft.push_back(0);
-    const size_t cols_at = ft.size();
-    ft.resize(cols_at + 2 * (size_t)off);
-    size_t e = 0;
-    for (int p = 0; p < n_proj; ++p)
-      for (int t = 0; t < n; ++t)
-        for (int q = 0; q < descs[p].ranks[t]; ++q, ++e) { ft[cols_at + 2 * e] = p * n + t; ft[cols_at + 2 * e + 1] = q; }
-    const void* dev = nullptr;
-    if ((rc = cached_table(ctx, ft.data(), ft.size() * sizeof(int32_t), &dev)) != MARLAAS_OK) return rc;
-    fuse.roff = (const int32_t*)dev;
-    fuse.cols = (const ExtCol*)((const int32_t*)dev + cols_at);
-    fuse.n_ext = off; fuse.ranks_mult8 = mult8; fuse.u_out = nullptr;
+    DevTables all;
+    if (shared) {
+      all = d0->table->dev;
+    } else {
+      all = dev_tables_carve((char*)ctx->ws + mp.tab_off, (int64_t)n_proj * n, ws_ext_cap(n_ext));
+      std::vector<AdapterEntry> host((size_t)n_proj * n);
+      for (int p = 0; p < n_proj; ++p)
+        for (int t = 0; t < n; ++t) {
+          AdapterEntry& e = host[(size_t)p * n + t];
+          e.A = descs[p].A[t]; e.B = descs[p].B[t]; e.rank = descs[p].ranks[t]; e.scale = descs[p].scales[t];
+        }
+      HIP_TRY(ctx, enqueue_write_entries(all, 0, (int64_t)n_proj * n, host.data(), st));
+      HIP_TRY(ctx, enqueue_derive(all, (int64_t)n_proj * n, st));
+    }
+    table = all.entries;
+    fuse.roff = all.roff; fuse.cols = all.cols;
+    fuse.n_ext = n_ext; fuse.ranks_mult8 = mult8; fuse.u_out = nullptr; fuse.t0 = 0; fuse.ext_base = 0;
   }
-  const ProjEntry* proj_dev = nullptr;
-  if ((rc = cached_table(ctx, proj.data(), proj.size() * sizeof(ProjEntry), (const void**)&proj_dev)) != MARLAAS_OK) return rc;
   const int32_t* perm = map->identity ? nullptr : map->perm_dev;
   PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16_multi((const bf16_t*)d0->x, d0->ldx, form, d0->T, d0->d_in, perm,
-                                      map->seg_off_dev, n, table, proj.data(), proj_dev, n_proj,
-                                      d0->out_dtype == MARLAAS_F32, (float*)ctx->ws, ctx->ws_bytes, map->chunks_dev,
+                                      map->seg_off_dev, n, table, proj.data(), n_proj,
+                                      d0->out_dtype == MARLAAS_F32, (float*)ctx->ws, mp.part_bytes, map->chunks_dev,
                                       map->n_chunks, lora ? &fuse : nullptr, st));
   return MARLAAS_OK;
 }
@@ -618,6 +797,9 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
   if (!ctx) return MARLAAS_EINVAL;
   int rc = check_sizes(ctx, d);
   if (rc != MARLAAS_OK) return rc;
+  const bool grads_in_table = dA == MARLAAS_GRADS_IN_TABLE || dB == MARLAAS_GRADS_IN_TABLE;
+  if (grads_in_table && (dA != dB || !d->table))
+    return fail(ctx, MARLAAS_EINVAL, "MARLAAS_GRADS_IN_TABLE must be passed for both dA and dB, with a descriptor that has an adapter table");
   const bool want_grads = dA != nullptr || dB != nullptr;
   if (want_grads && (!dA || !dB)) return fail(ctx, MARLAAS_EINVAL, "dA and dB must both be given or both be null");
   if (accumulate != 0 && accumulate != 1) return fail(ctx, MARLAAS_EINVAL, "accumulate must be 0 or 1");
@@ -630,10 +812,18 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     if (dX && (!aligned16(dX) || lddx < d->d_in || (lddx * osz) % 16)) return fail(ctx, MARLAAS_EALIGN, "dX / lddx");
     if (u_saved && !aligned16(u_saved)) return fail(ctx, MARLAAS_EALIGN, "u_saved must be 16-byte aligned");
   }
-  if (want_grads)
+  if (grads_in_table) {
+    const marlaas_adapter_table* tb = d->table;
+    for (int t = 0; t < d->n_adapters; ++t) {
+      const size_t i = (size_t)d->proj * tb->n + t;
+      if (tb->hranks[i] > 0 && !tb->hgrads[i].dA)
+        return fail(ctx, MARLAAS_EINVAL, "adapter %d was registered without gradient buffers", t);
+    }
+  } else if (want_grads) {
     for (int t = 0; t < d->n_adapters; ++t)
       if (!dA[t] || !dB[t] || !aligned16(dA[t]) || !aligned16(dB[t]))
         return fail(ctx, MARLAAS_EINVAL, "gradient buffers of adapter %d are null or misaligned", t);
+  }
   if (d->T == 0 && !(want_grads && !accumulate && d->n_adapters > 0)) return MARLAAS_OK;
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   hipStream_t st = (hipStream_t)stream;
@@ -647,13 +837,18 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
   float* v = d->n_adapters > 0 ? (float*)((char*)ctx->ws + p.v_off) : nullptr;
   const bool need_u = lora && want_grads && !u;
   if (need_u) u = (float*)((char*)ctx->ws + p.u_off);
-  const AdapterEntry* table = nullptr;
-  if ((rc = adapter_table(ctx, d, &table)) != MARLAAS_OK) return rc;
-  const GradEntry* grads = nullptr;
-  if (want_grads && d->n_adapters > 0) {
+  Bank bank;
+  if (d->n_adapters > 0 && (rc = resolve_bank(ctx, d, (char*)ctx->ws + p.tab_off, p.tab_bytes, st, &bank)) != MARLAAS_OK) return rc;
+  const AdapterEntry* table = bank.entries;
+  const GradEntry* grads = bank.grads;
+  if (want_grads && !grads_in_table && d->n_adapters > 0) {
+    // explicit gradient pointer lists belong to descriptors that carry their own A / B lists; the
+    // per-call copy of the tables in the workspace receives them
+    if (!bank.in_ws)
+      return fail(ctx, MARLAAS_EINVAL, "with an adapter table, register the gradient buffers in the table and pass MARLAAS_GRADS_IN_TABLE");
     std::vector<GradEntry> host((size_t)d->n_adapters);
     for (int t = 0; t < d->n_adapters; ++t) { host[t].dA = (float*)dA[t]; host[t].dB = (float*)dB[t]; }
-    if ((rc = cached_table(ctx, host.data(), host.size() * sizeof(GradEntry), (const void**)&grads)) != MARLAAS_OK) return rc;
+    HIP_TRY(ctx, enqueue_write_grads(bank.all, 0, d->n_adapters, host.data(), st));
   }
   const int32_t* perm = map->identity ? nullptr : map->perm_dev;
   // forward-side forms (contraction over d_in) and backward-side forms (contraction over d_out)
@@ -675,13 +870,10 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     // small batches: the dX GEMM computes v itself (and leaves it in `v` for the dA reduction)
     GemmFuse fuse;
     bool fused = false;
-    if (lora && dX && part) {
-      const int n_ext = sum_ranks_of(d);
-      bool mult8 = true;
-      for (int t = 0; t < d->n_adapters; ++t) if (d->ranks[t] & 7) mult8 = false;
-      fused = gemm_can_fuse_shrink(bform, d->T, d->d_out, d->d_in, n_ext, mult8, p.part_bytes);
+    if (lora && dX && part && bank_can_fuse(bank)) {
+      fused = gemm_can_fuse_shrink(bform, d->T, d->d_out, d->d_in, bank.n_ext, bank.mult8, p.part_bytes);
       if (fused) {
-        if ((rc = fuse_tables(ctx, d, &fuse)) != MARLAAS_OK) return rc;
+        if ((rc = bank_fuse(ctx, bank, d->n_adapters, st, &fuse)) != MARLAAS_OK) return rc;
         fuse.u_out = v;
       }
     }

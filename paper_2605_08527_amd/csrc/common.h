@@ -42,6 +42,7 @@ struct ExtCol {
 
 // One projection of a fused multi-projection forward (small batches): its weight, its output and
 // where it sits in the concatenated column space (each projection padded to whole column tiles).
+// The entries of a call travel inside the kernel arguments (no device copy).
 struct ProjEntry {
   const void* W; int64_t ldw;     // weight operand, stored in the call's form
   int64_t Nout;                   // output columns of this projection
@@ -51,6 +52,31 @@ struct ProjEntry {
   int32_t tab0;                   // index of this projection's first adapter in the combined table
   int32_t pad;
 };
+static constexpr int MAX_PROJ = 8;
+
+// The per-adapter tables of one call as the kernels read them, all in device memory.  They live
+// either in an adapter table object (written when an adapter is registered or swapped) or in a
+// slice of the caller's workspace (written at the start of the call); the passes only read them.
+//   entries[i], grads[i] : i = projection * n_adapters + adapter
+//   roff[i]              : sum of the ranks of entries 0 .. i - 1 (P + 1 values, P = entries)
+//   cols[e]              : (entry, rank index) of extended column e, for e < min(roff[P], ext_cap)
+struct DevTables {
+  AdapterEntry* entries = nullptr;
+  GradEntry* grads = nullptr;
+  int32_t* roff = nullptr;
+  ExtCol* cols = nullptr;
+  int32_t ext_cap = 0;
+};
+// Bytes of one DevTables block for P entries and ext_cap extended columns, and its carving.
+size_t dev_tables_bytes(int64_t P, int64_t ext_cap);
+DevTables dev_tables_carve(void* base, int64_t P, int64_t ext_cap);
+// Enqueue: entries[first .. first + count) = host values (by-value kernel arguments, no copy node).
+hipError_t enqueue_write_entries(const DevTables& d, int64_t first, int64_t count, const AdapterEntry* host,
+                                 hipStream_t stream);
+hipError_t enqueue_write_grads(const DevTables& d, int64_t first, int64_t count, const GradEntry* host,
+                               hipStream_t stream);
+// Enqueue: roff and cols recomputed from the ranks in entries[0 .. P).
+hipError_t enqueue_derive(const DevTables& d, int64_t P, hipStream_t stream);
 
 // How a [contraction, output] operand is stored.
 //   FORM_NT: element (k, n) at ptr[n * ld + k]   (contraction index contiguous)
@@ -85,8 +111,12 @@ struct SegmapDev {
 };
 
 hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* seg_off,
-                         int32_t* block_hist, int32_t* flags, hipStream_t stream);
+                         int32_t* block_hist, int32_t* flags, RowChunk* chunks, hipStream_t stream);
 int segmap_blocks(int64_t T);
+// Row chunks of a grouped order with these segment offsets (n + 2 entries): how many there are.
+int64_t segmap_chunk_count(const int32_t* seg_off, int n);
+// Upper bound of that count for any map of T tokens and n adapters.
+int64_t segmap_chunk_bound(int64_t T, int n);
 
 // u[m, 0..r_stride) = scale_t * sum_c X[perm[m], c] * L_t(c, q), grouped order m.
 // which = 0 uses AdapterEntry::A as L_t, 1 uses ::B.  lora_form: FORM_NN when
@@ -102,6 +132,10 @@ struct GemmFuse {
   int n_ext;               // sum of the ranks
   bool ranks_mult8;        // every rank is a multiple of 8
   float* u_out;            // [T][r_stride] device: receives scale_t * (X L_t) per grouped row
+  // `cols` and `roff` may point into the tables of a larger adapter bank: ExtCol::t then counts
+  // the bank's entries and t0 is the entry index of the call's table[0]; roff values are offsets
+  // in the bank's extended-column space and ext_base is the call's first one (roff of table[0]).
+  int t0 = 0, ext_base = 0;
 };
 
 // out[perm[m], :] = Aop[perm[m], :] * Bop + (m in segment t) U[m, :] * L_t
@@ -113,9 +147,10 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
                             hipStream_t stream);
 // Several projections of the same input in one pass (small batches only: 128 x 128 tiles with
-// the shrink carried as extended columns, or no adapters at all).  `proj_host` / `proj_dev` hold the
-// same n_proj entries; `table` is the combined adapter table ([projection][adapter]), `fuse` (null:
-// no adapters) the combined extended-column tables, ExtCol::t indexing the combined table.
+// the shrink carried as extended columns, or no adapters at all).  `proj_host` holds the n_proj
+// entries (host memory); `table` is the combined adapter table ([projection][adapter]), `fuse` (null:
+// no adapters) the combined extended-column tables, ExtCol::t indexing the combined table.  The
+// projection entries travel in the kernel arguments.
 // gemm_multi_ok tells whether the sizes qualify; otherwise the caller runs the projections one by one.
 bool gemm_multi_ok(int form, int64_t T, int64_t Kc, const ProjEntry* proj_host, int n_proj, int n_ext,
                    bool ranks_mult8, size_t partial_bytes);
@@ -123,7 +158,7 @@ size_t gemm_multi_bytes(int64_t T, int64_t Kc, const ProjEntry* proj_host, int n
 hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int64_t T, int64_t Kc,
                                   const int32_t* perm, const int32_t* seg_off, int n_adapters,
                                   const AdapterEntry* table, const ProjEntry* proj_host,
-                                  const ProjEntry* proj_dev, int n_proj, int out_is_f32, float* partials,
+                                  int n_proj, int out_is_f32, float* partials,
                                   size_t partial_bytes, const RowChunk* chunks, int n_chunks,
                                   const GemmFuse* fuse, hipStream_t stream);
 // Scratch for a transposed copy of the weight: a large batch whose weight is stored

@@ -30,6 +30,7 @@
 #include "common.h"
 
 #include <atomic>
+#include <cstring>
 
 namespace marlaas {
 
@@ -72,13 +73,17 @@ struct GemmArgs {
   // X * [all adapters' shrink factors] (extended column e = rank offset of adapter t + q); the
   // finish kernel picks each row's own adapter, scales and writes u_out.
   const ExtCol* ext_cols; const int32_t* ext_roff; int n_ext;   // n_ext = sum of the ranks; 0: not fused
+  // ExtCol::t counts entries of the whole adapter bank, `table` may start inside it: entry index
+  // of table[0]; ext_roff[] are offsets in the bank's column space, ext_base the call's first one
+  int ext_t0, ext_base;
   float* u_part; int64_t ldu;   // [ks][pm][ldu] fp32 partial sums of the extended columns
   float* u_out;                 // [T][r_stride] (may be null)
   // Several projections in one pass (small-batch kernels only; n_proj <= 1: the fields above
   // describe the only projection).  Column tile tn belongs to the last projection whose tile0 <=
   // tn; `table`, `ext_roff` and ExtCol::t then index [projection][adapter].
-  const ProjEntry* proj; int n_proj;
+  int n_proj;
   int fin_cols;                 // column chunks of the finish kernel's grid, all projections
+  ProjEntry proj[MAX_PROJ];     // by value: read with wave-uniform loads from the kernel arguments
 };
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
@@ -648,7 +653,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       int e = tn * SK_BX + row;
       if (e >= a.n_ext) e = a.n_ext - 1;
       const ExtCol c = a.ext_cols[e];
-      const AdapterEntry en = a.table[c.t];
+      const AdapterEntry en = a.table[c.t - a.ext_t0];
       x_src = (const bf16_t*)(a.which ? en.A : en.B) + (int64_t)c.q * a.Kc + kbeg + unit * 8;
       x_step = BK;
     } else {                         // tile [64 k][32 e], 64-byte rows: factor stored [Kc][r], r % 8 == 0
@@ -656,7 +661,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       int e = tn * SK_BX + (lane & 3) * 8;
       if (e >= a.n_ext) e = a.n_ext - 8;
       const ExtCol c = a.ext_cols[e];
-      const AdapterEntry en = a.table[c.t];
+      const AdapterEntry en = a.table[c.t - a.ext_t0];
       x_src = (const bf16_t*)(a.which ? en.A : en.B) + (kbeg + k) * en.rank + c.q;
       x_step = (int64_t)BK * en.rank;
     }
@@ -1035,7 +1040,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         int e = tn * SK_BX + row;
         if (e >= a.n_ext) e = a.n_ext - 1;
         const ExtCol c = a.ext_cols[e];
-        const AdapterEntry en = a.table[c.t];
+        const AdapterEntry en = a.table[c.t - a.ext_t0];
         uint4 w = zero4;
         if ((k0 + lc * 8) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? en.A : en.B) + (int64_t)c.q * a.Kc + k0 + lc * 8);
         *(uint4*)(xs + swz_rowk(row, lc)) = w;
@@ -1044,7 +1049,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         int e = tn * SK_BX + lc * 8;
         if (e >= a.n_ext) e = a.n_ext - 8;
         const ExtCol c = a.ext_cols[e];
-        const AdapterEntry en = a.table[c.t];
+        const AdapterEntry en = a.table[c.t - a.ext_t0];
         uint4 w = zero4;
         if ((k0 + k) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? en.A : en.B) + (k0 + k) * en.rank + c.q);
         *(uint4*)(xs + k * 64 + lc * 16) = w;
@@ -1121,7 +1126,7 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
     const int r = e.rank;
     if (a.n_ext > 0) {
       // fused shrink: u = scale * (sum over the splits of this adapter's extended columns)
-      const int roff = a.ext_roff[tab0 + ch.t];
+      const int roff = a.ext_roff[tab0 + ch.t] - a.ext_base;
       const int64_t ustride = a.pm * a.ldu;
 #pragma unroll
       for (int i = 0; i < UPT; ++i) {
@@ -1137,8 +1142,9 @@ __global__ __launch_bounds__(FIN_THREADS) void splitk_finish_kernel(GemmArgs a) 
             for (int ii = 0; ii < 4; ++ii) if (ks0 + ii < a.ksplit) sum += pu[ii];
           }
           sum *= e.scale;
-          if (col == 0 && a.u_out) a.u_out[(int64_t)(ch.row0 + j) * a.r_stride + q] = sum;
         }
+        // (ranks r .. r_stride - 1 are padding of the row: zeros, as the shrink kernels write them)
+        if (col == 0 && a.u_out && j < ch.nrows && q < a.r_stride) a.u_out[(int64_t)(ch.row0 + j) * a.r_stride + q] = sum;
         ureg[i] = sum;
       }
     } else {
@@ -1432,12 +1438,15 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   a.U = U; a.r_stride = r_stride; a.out = out; a.ldo = ldo;
   GemmPlan p = gemm_plan(T, Kc, Nout, fuse ? fuse->n_ext : 0);
   a.ext_cols = nullptr; a.ext_roff = nullptr; a.n_ext = 0; a.u_part = nullptr; a.ldu = 0; a.u_out = nullptr;
-  a.proj = nullptr; a.n_proj = 1; a.fin_cols = (int)((Nout + FIN_COLS - 1) / FIN_COLS);
+  a.ext_t0 = 0; a.ext_base = 0;
+  memset(a.proj, 0, sizeof a.proj);
+  a.n_proj = 1; a.fin_cols = (int)((Nout + FIN_COLS - 1) / FIN_COLS);
   if (fuse) {
     // the caller skipped the shrink: the conditions of gemm_can_fuse_shrink() must hold
     if (!gemm_can_fuse_shrink(form, T, Kc, Nout, fuse->n_ext, fuse->ranks_mult8, partials ? partial_bytes : 0) || chunks == nullptr)
       return hipErrorInvalidValue;
     a.ext_cols = fuse->cols; a.ext_roff = fuse->roff; a.n_ext = fuse->n_ext;
+    a.ext_t0 = fuse->t0; a.ext_base = fuse->ext_base;
     a.u_part = partials + p.bytes / sizeof(float); a.ldu = p.ldu; a.u_out = fuse->u_out;
     a.U = nullptr;
   }
@@ -1491,12 +1500,12 @@ bool gemm_multi_ok(int form, int64_t T, int64_t Kc, const ProjEntry* proj_host, 
 hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int64_t T, int64_t Kc,
                                   const int32_t* perm, const int32_t* seg_off, int n_adapters,
                                   const AdapterEntry* table, const ProjEntry* proj_host,
-                                  const ProjEntry* proj_dev, int n_proj, int out_is_f32, float* partials,
+                                  int n_proj, int out_is_f32, float* partials,
                                   size_t partial_bytes, const RowChunk* chunks, int n_chunks,
                                   const GemmFuse* fuse, hipStream_t stream) {
   const int n_ext = fuse ? fuse->n_ext : 0;
   if (!gemm_multi_ok(form, T, Kc, proj_host, n_proj, n_ext, fuse ? fuse->ranks_mult8 : true,
-                     partials ? partial_bytes : 0) || chunks == nullptr || proj_dev == nullptr)
+                     partials ? partial_bytes : 0) || chunks == nullptr || n_proj > MAX_PROJ)
     return hipErrorInvalidValue;
   const int64_t tiles = multi_tiles(proj_host, n_proj);
   const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext);
@@ -1508,11 +1517,15 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
   a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.ksplit = p.ksplit; a.kchunk = p.kchunk;
   a.partials = partials; a.ldp = p.ldp; a.pm = p.pm; a.chunks = chunks; a.n_chunks = n_chunks;
   a.ext_cols = nullptr; a.ext_roff = nullptr; a.n_ext = 0; a.u_part = nullptr; a.ldu = 0; a.u_out = nullptr;
+  a.ext_t0 = 0; a.ext_base = 0;
   if (fuse) {
     a.ext_cols = fuse->cols; a.ext_roff = fuse->roff; a.n_ext = n_ext;
+    a.ext_t0 = fuse->t0; a.ext_base = fuse->ext_base;
     a.u_part = partials + p.bytes / sizeof(float); a.ldu = p.ldu;
   }
-  a.proj = proj_dev; a.n_proj = n_proj;
+  memset(a.proj, 0, sizeof a.proj);
+  for (int q = 0; q < n_proj; ++q) a.proj[q] = proj_host[q];
+  a.n_proj = n_proj;
   int fin_cols = 0;
   for (int q = 0; q < n_proj; ++q) fin_cols += (int)((proj_host[q].Nout + FIN_COLS - 1) / FIN_COLS);
   a.fin_cols = fin_cols;

@@ -6,7 +6,23 @@
 // and are bound by HBM; the small operand stays in LDS.
 #include "common.h"
 
+#include <atomic>
+
 namespace marlaas {
+
+// Raise a kernel's dynamic LDS limit to the hardware maximum, once per (kernel, device): `slot`
+// names the kernel instantiation, bit i of its word = device i has it.
+static hipError_t allow_big_lds(const void* kernel, int slot) {
+  static std::atomic<uint64_t> done[16];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done[slot].load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess) done[slot].fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // ============================================================== shrink
 static constexpr int SH_THREADS = 256;
@@ -265,7 +281,7 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
     kern = nq <= 1 ? shrink_bf16_kernel<FORM_NN, 1> : nq <= 2 ? shrink_bf16_kernel<FORM_NN, 2>
          : nq <= 4 ? shrink_bf16_kernel<FORM_NN, 4> : shrink_bf16_kernel<FORM_NN, 8>;
   if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_big_lds((const void*)kern, (lora_form == FORM_NT ? 0 : 4) + (nq <= 1 ? 0 : nq <= 2 ? 1 : nq <= 4 ? 2 : 3));
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, dim3(rb_max * ksplit, n_adapters), dim3(SH_THREADS), lds, stream, a);
@@ -522,7 +538,7 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
     kern = nq <= 1 ? reduce_bf16_kernel<FORM_NT, 1> : nq <= 2 ? reduce_bf16_kernel<FORM_NT, 2>
          : nq <= 4 ? reduce_bf16_kernel<FORM_NT, 4> : reduce_bf16_kernel<FORM_NT, 8>;
   if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_big_lds((const void*)kern, 8 + (out_form == FORM_NT ? 0 : 4) + (nq <= 1 ? 0 : nq <= 2 ? 1 : nq <= 4 ? 2 : 3));
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, dim3(a.slabs * a.chunks_max, n_adapters), dim3(RD_THREADS), lds, stream, a);

@@ -108,11 +108,46 @@ __global__ __launch_bounds__(SEG_THREADS) void segmap_scatter(const int32_t* __r
   }
 }
 
+// Row chunks of the grouped order: segment t cut into pieces of ROW_CHUNK rows, the rows without
+// an adapter (bucket n) last.  One block; thread b handles bucket b, the first chunk index of a
+// bucket is the prefix sum of the buckets' chunk counts (serial over at most n + 1 values).
+__global__ __launch_bounds__(1024) void segmap_chunks(const int32_t* __restrict__ seg_off, int n,
+                                                      RowChunk* __restrict__ chunks) {
+  extern __shared__ int32_t first[];   // [n + 2]
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int b = 0; b <= n; ++b) {
+      first[b] = run;
+      run += (seg_off[b + 1] - seg_off[b] + ROW_CHUNK - 1) / ROW_CHUNK;
+    }
+  }
+  __syncthreads();
+  for (int b = threadIdx.x; b <= n; b += blockDim.x) {
+    const int32_t end = seg_off[b + 1];
+    int c = first[b];
+    for (int32_t row0 = seg_off[b]; row0 < end; row0 += ROW_CHUNK, ++c) {
+      RowChunk ch;
+      ch.row0 = row0; ch.nrows = end - row0 < ROW_CHUNK ? end - row0 : ROW_CHUNK; ch.t = b < n ? b : -1; ch.pad = 0;
+      chunks[c] = ch;
+    }
+  }
+}
+
+int64_t segmap_chunk_count(const int32_t* seg_off, int n) {
+  int64_t c = 0;
+  for (int b = 0; b <= n; ++b) c += (seg_off[b + 1] - seg_off[b] + ROW_CHUNK - 1) / ROW_CHUNK;
+  return c;
+}
+
+int64_t segmap_chunk_bound(int64_t T, int n) { return T / ROW_CHUNK + n + 2; }
+
+// plain fill (a kernel, not a memset node)
+__global__ void segmap_clear_flags(int32_t* flags) { flags[threadIdx.x] = 0; }
+
 hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* seg_off,
-                         int32_t* block_hist, int32_t* flags, hipStream_t stream) {
+                         int32_t* block_hist, int32_t* flags, RowChunk* chunks, hipStream_t stream) {
   int nblk = segmap_blocks(T);
-  hipError_t e = hipMemsetAsync(flags, 0, 2 * sizeof(int32_t), stream);
-  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(segmap_clear_flags, dim3(1), dim3(2), 0, stream, flags);
   if (nblk > 0) {
     hipLaunchKernelGGL(segmap_hist, dim3(nblk), dim3(SEG_THREADS), (n + 1) * sizeof(int32_t),
                        stream, ids, T, n, block_hist, flags);
@@ -123,6 +158,7 @@ hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, in
     hipLaunchKernelGGL(segmap_scatter, dim3(nblk), dim3(SEG_THREADS),
                        (n + 1 + SEG_THREADS) * sizeof(int32_t), stream, ids, T, n, block_hist, perm);
   }
+  hipLaunchKernelGGL(segmap_chunks, dim3(1), dim3(1024), (n + 2) * sizeof(int32_t), stream, seg_off, n, chunks);
   return hipGetLastError();
 }
 

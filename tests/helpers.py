@@ -4,7 +4,7 @@ import numpy as np
 import torch
 
 from paper_2605_08527_amd import api
-from paper_2605_08527_amd import workloads as wl
+from harness import workloads as wl
 
 TOL_MAX, TOL_MEAN = 1e-2, 1e-3   # floored relative error vs the fp64 oracle (bf16 in, fp32 accumulate)
 
@@ -22,9 +22,11 @@ def to_host(t):
 
 
 class HipLayer:
-    """One workload resident on the GPU with its context, map and descriptor."""
+    """One workload resident on the GPU with its context, map and descriptor.  With table=True the
+    adapters (and their gradient buffers) are registered in an adapter table object and the
+    descriptor refers to it; otherwise the descriptor carries the host pointer lists."""
 
-    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None):
+    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None, table=False):
         self.w = w
         self.ctx = ctx or api.marlaas_create(0)
         self.x, self.W = to_dev(w["x"]), to_dev(w["W"])
@@ -34,8 +36,22 @@ class HipLayer:
         self.dY = to_dev(w["dY"]) if w.get("dY") is not None else None
         self.n = len(self.A)
         self.map = api.marlaas_segmap_build(self.ctx, self.ids, self.n)
-        self.desc = api.LoraDesc(self.x, self.W, self.A, self.B, w["ranks"], w["scales"], self.map,
-                                 layout=w["layout"], out_dtype=out_dtype)
+        self.table = None
+        self.gA = self.gB = None
+        if table and self.n > 0:
+            self.table = api.marlaas_adapter_table_create(self.ctx, self.n, 1, int(max(w["ranks"])))
+            if want_bwd:
+                self.gA = [torch.full(tuple(a.shape), float("nan"), dtype=torch.float32, device="cuda") for a in self.A]
+                self.gB = [torch.full(tuple(b.shape), float("nan"), dtype=torch.float32, device="cuda") for b in self.B]
+            for t in range(self.n):
+                api.marlaas_adapter_table_update(self.ctx, self.table, 0, t, self.A[t], self.B[t], int(w["ranks"][t]),
+                                                 float(w["scales"][t]), self.gA[t] if want_bwd else None,
+                                                 self.gB[t] if want_bwd else None)
+            self.desc = api.LoraDesc(self.x, self.W, None, None, None, None, self.map, layout=w["layout"],
+                                     out_dtype=out_dtype, table=self.table)
+        else:
+            self.desc = api.LoraDesc(self.x, self.W, self.A, self.B, w["ranks"], w["scales"], self.map,
+                                     layout=w["layout"], out_dtype=out_dtype)
         self.out_dtype = out_dtype
         nbytes = api.marlaas_workspace_bytes(self.desc, want_bwd)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
@@ -54,12 +70,19 @@ class HipLayer:
     def bwd(self, u_saved=None, accumulate=False, init=None, want_dX=True, want_grads=True):
         dX = torch.full((self.T, self.K), float("nan"), dtype=self.out_dtype, device="cuda") if want_dX else None
         dA = dB = None
-        if want_grads:
-            fill = float("nan") if init is None else init
-            dA = [torch.full(tuple(a.shape), fill, dtype=torch.float32, device="cuda") for a in self.A]
-            dB = [torch.full(tuple(b.shape), fill, dtype=torch.float32, device="cuda") for b in self.B]
-        api.marlaas_lora_bwd(self.ctx, self.desc, self.dY, dX=dX, dA=dA, dB=dB, u_saved=u_saved,
-                             accumulate=accumulate)
+        fill = float("nan") if init is None else init
+        if want_grads and self.table is not None:
+            dA, dB = self.gA, self.gB
+            for g in dA + dB:
+                g.fill_(fill)
+            api.marlaas_lora_bwd(self.ctx, self.desc, self.dY, dX=dX, dA=api.MARLAAS_GRADS_IN_TABLE,
+                                 dB=api.MARLAAS_GRADS_IN_TABLE, u_saved=u_saved, accumulate=accumulate)
+        else:
+            if want_grads:
+                dA = [torch.full(tuple(a.shape), fill, dtype=torch.float32, device="cuda") for a in self.A]
+                dB = [torch.full(tuple(b.shape), fill, dtype=torch.float32, device="cuda") for b in self.B]
+            api.marlaas_lora_bwd(self.ctx, self.desc, self.dY, dX=dX, dA=dA, dB=dB, u_saved=u_saved,
+                                 accumulate=accumulate)
         torch.cuda.synchronize()
         return dX, dA, dB
 

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2605_08527_amd import workloads as wl
+from harness import workloads as wl
 from helpers import HipLayer, assert_close, to_host
 
 pytestmark = pytest.mark.gpu

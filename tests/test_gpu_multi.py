@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2605_08527_amd import api
-from paper_2605_08527_amd import workloads as wl
+from harness import workloads as wl
 from helpers import assert_close, to_dev, to_host
 
 pytestmark = pytest.mark.gpu

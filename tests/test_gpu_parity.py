@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2605_08527_amd import api
-from paper_2605_08527_amd import workloads as wl
+from harness import workloads as wl
 from helpers import HipLayer, assert_close, oracle_grads_in_layout, to_host
 
 pytestmark = pytest.mark.gpu
@@ -23,12 +23,40 @@ def _oracle_all(oracle, w, bwd):
     return y, dX, dA, dB
 
 
-def _check_layer(oracle, w, bwd, out_dtype=torch.float32, tol=(1e-2, 1e-3), tag=""):
+@pytest.fixture(params=[False, True], ids=["lists", "table"])
+def use_table(request):
+    """Adapters given as host pointer lists in the descriptor, or registered in an adapter table object."""
+    return request.param
+
+
+def check_u_save(oracle, w, L, u, tag=""):
+    """u_save holds s_t (x A_t) per token in the grouped order of the map: compare with the
+    oracle's u, rows taken through the exported permutation; the padding ranks must be zero."""
+    if L.n == 0 or u is None:
+        return
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    _, u_ref = oracle.fwd(*args, layout=w["layout"], want_u=True)
+    perm, seg_off = api.marlaas_segmap_export(L.map)
+    T_lora = int(seg_off[L.n])
+    if T_lora == 0:
+        return
+    toks = perm[:T_lora]
+    ranks = np.asarray(w["ranks"])[w["ids"][toks]]
+    want = np.zeros((T_lora, u.shape[1]))
+    want[:, :u_ref.shape[1]] = u_ref[toks] * np.asarray(w["scales"], dtype=np.float64)[w["ids"][toks]][:, None]
+    got = to_host(u[:T_lora])
+    pad = np.arange(u.shape[1])[None, :] >= ranks[:, None]
+    assert np.all(got[pad] == 0.0), tag + " u_save: padding ranks are not zero"
+    assert_close(got, want, tag + " u_save")
+
+
+def _check_layer(oracle, w, bwd, out_dtype=torch.float32, tol=(1e-2, 1e-3), tag="", table=False):
     y_ref, dX_ref, dA_ref, dB_ref = _oracle_all(oracle, w, bwd)
-    L = HipLayer(w, out_dtype=out_dtype, want_bwd=bwd)
+    L = HipLayer(w, out_dtype=out_dtype, want_bwd=bwd, table=table)
     y, u = L.fwd(save_u=bwd)
     stats = {"y": assert_close(to_host(y), y_ref, tag + " y", *tol)}
     if bwd:
+        check_u_save(oracle, w, L, u, tag)
         for saved in (u, None):      # with the saved intermediate, then recomputing it
             dX, dA, dB = L.bwd(u_saved=saved)
             stats["dX"] = assert_close(to_host(dX), dX_ref, tag + " dX", *tol)
@@ -75,9 +103,9 @@ def test_config0_fp32(oracle, layout, seed):
 # ------------------------------------------------------------------ bf16 configs, reduced sizes
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("cfg,scale", [(1, 0.25), (2, 0.05), (3, 0.03), (4, 0.08)])
-def test_bf16_configs_scaled(oracle, cfg, scale, layout):
+def test_bf16_configs_scaled(oracle, cfg, scale, layout, use_table):
     w = wl.make_config(cfg, seed=cfg, scale=scale, layout=layout, want_dY=True)
-    _check_layer(oracle, w, bwd=True, tag="cfg%d@%g" % (cfg, scale))
+    _check_layer(oracle, w, bwd=True, tag="cfg%d@%g" % (cfg, scale), table=use_table)
 
 
 @pytest.mark.parametrize("layout", [0, 1])
@@ -90,14 +118,24 @@ def test_bf16_output_dtype(oracle, layout):
 
 # ------------------------------------------------------------------ config 1 at full size
 @pytest.mark.parametrize("layout", [0, 1])
-def test_config1_full(oracle, layout):
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_config1_full(oracle, layout, seed, use_table):
+    w = wl.make_config(1, seed=seed, layout=layout)
+    _check_layer(oracle, w, bwd=False, tag="cfg1", table=use_table)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_config1_full_saves_u(oracle, layout, use_table):
+    """The decode configuration with u_save requested: the fused shrink writes it from the finish kernel."""
     w = wl.make_config(1, seed=0, layout=layout)
-    _check_layer(oracle, w, bwd=False, tag="cfg1")
+    L = HipLayer(w, table=use_table)
+    y, u = L.fwd(save_u=True)
+    check_u_save(oracle, w, L, u, "cfg1")
 
 
 # ------------------------------------------------------------------ ragged shapes and odd ranks
 @pytest.mark.parametrize("layout", [0, 1])
-def test_ragged_shapes_and_ranks(oracle, layout):
+def test_ragged_shapes_and_ranks(oracle, layout, use_table):
     rng = np.random.default_rng(5)
     ranks = [1, 5, 12, 100, 128, 16, 7]
     T = 777
@@ -105,12 +143,12 @@ def test_ragged_shapes_and_ranks(oracle, layout):
     ids[ids == 5] = 2    # adapter 5 empty
     w = wl.make_layer(13, T, 520, 328, ranks, [2.0, 0.5, 1.0, 0.25, 0.125, 1.0, 3.0], ids,
                       dtype="bf16", layout=layout, want_dY=True)
-    _check_layer(oracle, w, bwd=True, tag="ragged")
+    _check_layer(oracle, w, bwd=True, tag="ragged", table=use_table)
 
 
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("ranks", [(8, 16, 24, 32), (1, 5, 12, 16, 7), (64, 64)])
-def test_small_batch_paths(oracle, layout, ranks):
+def test_small_batch_paths(oracle, layout, ranks, use_table):
     """Few rows: the GEMM splits the contraction and, when the summed ranks fit its extended
     columns (and, for operands stored output-contiguous, every rank is a multiple of 8),
     computes the shrink itself; otherwise the separate shrink kernel runs.  The three rank sets
@@ -121,7 +159,7 @@ def test_small_batch_paths(oracle, layout, ranks):
     ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
     w = wl.make_layer(17, T, 520, 384, list(ranks), [1.0 + 0.5 * i for i in range(len(ranks))], ids,
                       dtype="bf16", layout=layout, want_dY=True)
-    _check_layer(oracle, w, bwd=True, tag="small%s" % (ranks,))
+    _check_layer(oracle, w, bwd=True, tag="small%s" % (ranks,), table=use_table)
 
 
 def _padded(t, pad):
@@ -162,7 +200,7 @@ def test_padded_leading_dimensions(oracle, layout, T):
 
 
 @pytest.mark.parametrize("layout", [0, 1])
-def test_many_adapters_few_tokens_each(oracle, layout):
+def test_many_adapters_few_tokens_each(oracle, layout, use_table):
     """300 adapters (ranks 4, 8, 12, 16 in turn) over 700 tokens: most segments hold one to four
     tokens, some adapters none; exercises the per-adapter grids and the row-chunk list."""
     rng = np.random.default_rng(41)
@@ -170,12 +208,12 @@ def test_many_adapters_few_tokens_each(oracle, layout):
     ranks = [4 * (1 + t % 4) for t in range(n)]
     ids = rng.integers(-1, n, size=T).astype(np.int32)
     w = wl.make_layer(37, T, 256, 384, ranks, [1.0 + (t % 3) for t in range(n)], ids, dtype="bf16", layout=layout, want_dY=True)
-    _check_layer(oracle, w, bwd=True, tag="n300")
+    _check_layer(oracle, w, bwd=True, tag="n300", table=use_table)
 
 
 def test_hip_graph_replay_matches_eager():
-    """Forward + backward captured once into a HIP graph (after an eager call has filled the
-    pointer-table cache) and replayed three times, with eager work and synchronisations between
+    """Forward + backward captured once into a HIP graph (after an eager call)
+    and replayed three times, with eager work and synchronisations between
     the replays: every replay reproduces the eager results bit for bit (this small batch takes
     the paths without atomics), also after the inputs changed in place."""
     rng = np.random.default_rng(3)
@@ -222,7 +260,7 @@ def test_hip_graph_replay_matches_eager():
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
-def test_random_shapes(oracle, seed):
+def test_random_shapes(oracle, seed, use_table):
     """Three seeded random problems per seed: T from a list that straddles the tile heights, d_in
     and d_out any multiples of 8 up to 1272, 0-9 adapters with ranks from 1 to 128, either
     layout, token order shuffled or grouped; forward and backward (with and without the saved
@@ -239,7 +277,8 @@ def test_random_shapes(oracle, seed):
         if rng.random() < 0.3:
             ids = np.sort(ids)
         w = wl.make_layer(1000 * seed + case, T, K, N, ranks, scales, ids, dtype="bf16", layout=layout, want_dY=True)
-        _check_layer(oracle, w, bwd=True, tag="rand s%d c%d T=%d K=%d N=%d ranks=%s layout=%d" % (seed, case, T, K, N, ranks, layout))
+        _check_layer(oracle, w, bwd=True, tag="rand s%d c%d T=%d K=%d N=%d ranks=%s layout=%d" % (seed, case, T, K, N, ranks, layout),
+                     table=use_table)
 
 
 def test_no_adapters_and_all_base_tokens(oracle):
@@ -272,13 +311,21 @@ def test_zero_B_is_bitwise_base_only():
 
 
 def test_permutation_equivariance_on_gpu():
+    """Permuting the tokens together with their labels permutes y and dX and leaves dA_t, dB_t
+    unchanged (up to the summation order inside a segment)."""
     w = wl.make_config(4, seed=2, scale=0.04, want_dY=True)
     perm = np.random.default_rng(0).permutation(w["T"])
     wp = dict(w, x=np.ascontiguousarray(w["x"][perm]), dY=np.ascontiguousarray(w["dY"][perm]), ids=w["ids"][perm])
     L, Lp = HipLayer(w, want_bwd=True), HipLayer(wp, want_bwd=True)
-    y, _ = L.fwd()
-    yp, _ = Lp.fwd()
+    y, u = L.fwd(save_u=True)
+    yp, up = Lp.fwd(save_u=True)
     assert_close(to_host(yp), to_host(y)[perm], "perm y", 1e-5, 1e-6)
+    dX, dA, dB = L.bwd(u_saved=u)
+    dXp, dAp, dBp = Lp.bwd(u_saved=up)
+    assert_close(to_host(dXp), to_host(dX)[perm], "perm dX", 1e-5, 1e-6)
+    for t in range(L.n):
+        assert_close(to_host(dAp[t]), to_host(dA[t]), "perm dA[%d]" % t, 1e-4, 1e-5)
+        assert_close(to_host(dBp[t]), to_host(dB[t]), "perm dB[%d]" % t, 1e-4, 1e-5)
 
 
 def test_accumulate_and_empty_tokens(oracle):

@@ -1,0 +1,299 @@
+"""GPU tests of what lets the passes run without allocating: the adapter table object (registered,
+versioned adapters; hot-swap between graph replays), capture of a first-ever call, the reusable
+segment map.  Everything is compared with the fp64 oracle (floored relative error max <= 1e-2,
+mean <= 1e-3, fp32 outputs) or, for integer work, bit for bit with numpy."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_08527_amd import api
+from harness import workloads as wl
+from helpers import HipLayer, assert_close, oracle_grads_in_layout, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_args(w):
+    return (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+
+
+def _small_workload(seed, layout, T=192, K=512, N=640, ranks=(16, 8, 32, 16)):
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    return wl.make_layer(seed, T, K, N, list(ranks), [2.0, 1.0, 0.5, 2.0][:len(ranks)], ids, dtype="bf16", layout=layout,
+                         want_dY=True)
+
+
+@pytest.mark.parametrize("table", [False, True], ids=["lists", "table"])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_first_ever_call_is_captured(oracle, layout, table):
+    """Forward + backward of a descriptor that has never run, recorded straight into a HIP graph
+    (fresh context: nothing is cached anywhere), then replayed twice: both replays match the oracle."""
+    w = _small_workload(5 + layout, layout)
+    L = HipLayer(w, want_bwd=True, table=table)
+    y = torch.full((L.T, L.N), float("nan"), dtype=torch.float32, device="cuda")
+    u = torch.zeros((L.T, api.marlaas_u_stride(L.desc)), dtype=torch.float32, device="cuda")
+    dX = torch.full((L.T, L.K), float("nan"), dtype=torch.float32, device="cuda")
+    if table:
+        dA, dB = L.gA, L.gB
+        ga = gb = api.MARLAAS_GRADS_IN_TABLE
+    else:
+        dA = [torch.full(tuple(a.shape), float("nan"), dtype=torch.float32, device="cuda") for a in L.A]
+        dB = [torch.full(tuple(b.shape), float("nan"), dtype=torch.float32, device="cuda") for b in L.B]
+        ga, gb = dA, dB
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            api.marlaas_lora_fwd(L.ctx, L.desc, y, u_save=u)
+            api.marlaas_lora_bwd(L.ctx, L.desc, L.dY, dX=dX, dA=ga, dB=gb, u_saved=u)
+    y_ref = oracle.fwd(*_oracle_args(w), layout=layout)
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*_oracle_args(w), w["dY"], layout=layout)
+    dA_ref, dB_ref = oracle_grads_in_layout(dA_ref, dB_ref, layout)
+    for rep in range(2):
+        for t in [y, dX] + dA + dB:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_close(to_host(y), y_ref, "replay %d y" % rep)
+        assert_close(to_host(dX), dX_ref, "replay %d dX" % rep)
+        for t in range(L.n):
+            assert_close(to_host(dA[t]), dA_ref[t], "replay %d dA[%d]" % (rep, t))
+            assert_close(to_host(dB[t]), dB_ref[t], "replay %d dB[%d]" % (rep, t))
+        (L.x.float() @ L.W.float().t() if layout else L.x.float() @ L.W.float()).sum().item()   # eager work between replays
+
+
+def _multi_setup(ws, table, out_dtype=torch.float32):
+    ctx = api.marlaas_create(0)
+    x = to_dev(ws[0]["x"])
+    ids = torch.from_numpy(np.ascontiguousarray(ws[0]["ids"], dtype=np.int32)).cuda()
+    n = len(ws[0]["A"])
+    seg = api.marlaas_segmap_build(ctx, ids, n)
+    keep, descs, ys = [], [], []
+    tb = None
+    if table:
+        tb = api.marlaas_adapter_table_create(ctx, n, len(ws), max(int(max(w["ranks"])) for w in ws))
+    for p, w in enumerate(ws):
+        W, A, B = to_dev(w["W"]), [to_dev(a) for a in w["A"]], [to_dev(b) for b in w["B"]]
+        keep.append((W, A, B))
+        if table:
+            for t in range(n):
+                api.marlaas_adapter_table_update(ctx, tb, p, t, A[t], B[t], int(w["ranks"][t]), float(w["scales"][t]))
+            d = api.LoraDesc(x, W, None, None, None, None, seg, layout=w["layout"], out_dtype=out_dtype, table=tb, proj=p)
+        else:
+            d = api.LoraDesc(x, W, A, B, w["ranks"], w["scales"], seg, layout=w["layout"], out_dtype=out_dtype)
+        descs.append(d)
+        ys.append(torch.full((x.shape[0], d.shape[2]), float("nan"), dtype=out_dtype, device="cuda"))
+    wsbuf = torch.empty(max(api.marlaas_workspace_bytes_multi(descs), 256), dtype=torch.uint8, device="cuda")
+    api.marlaas_set_workspace(ctx, wsbuf)
+    return ctx, seg, keep, descs, ys, wsbuf, tb
+
+
+def _projections(seed, T, K, Ns, ranks_per_proj, scales, ids, layout):
+    ws = [wl.make_layer(seed + 7 * p, T, K, N, list(ranks_per_proj[p]), list(scales), ids, dtype="bf16", layout=layout)
+          for p, N in enumerate(Ns)]
+    for w in ws[1:]:
+        w["x"] = ws[0]["x"]
+    return ws
+
+
+@pytest.mark.parametrize("table", [False, True], ids=["lists", "table"])
+@pytest.mark.parametrize("layout", [0, 1])
+def test_first_ever_multi_projection_call_is_captured(oracle, layout, table):
+    """q / k / v of one input through marlaas_lora_fwd_multi, first call recorded into a graph; with
+    a shared adapter table (projections 0..2 of one table) and with per-descriptor pointer lists.
+    The replays match the oracle, and the call ran as one fused GEMM launch (profiled eagerly after)."""
+    rng = np.random.default_rng(3)
+    T, K, Ns = 200, 520, (384, 136, 200)
+    ranks = ((8, 16, 24, 32), (16, 16, 8, 8), (32, 8, 16, 24))
+    ids = rng.integers(-1, 4, size=T).astype(np.int32)
+    ws = _projections(51, T, K, Ns, ranks, [2.0, 0.5, 1.0, 0.25], ids, layout)
+    ctx, seg, keep, descs, ys, wsbuf, tb = _multi_setup(ws, table)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            api.marlaas_lora_fwd_multi(ctx, descs, ys)
+    refs = [oracle.fwd(*_oracle_args(w), layout=layout) for w in ws]
+    for rep in range(2):
+        for y in ys:
+            y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for p, (y, ref) in enumerate(zip(ys, refs)):
+            assert_close(to_host(y), ref, "replay %d projection %d" % (rep, p))
+    api.marlaas_profile_enable(ctx, True)
+    api.marlaas_lora_fwd_multi(ctx, descs, ys)
+    torch.cuda.synchronize()
+    assert api.marlaas_profile_read(ctx, api.MARLAAS_KERNEL_GEMM)[1] == 1
+    api.marlaas_profile_enable(ctx, False)
+    # a single projection of the shared table through the single-projection entry point
+    if table:
+        y1 = torch.full_like(ys[1], float("nan"))
+        api.marlaas_lora_fwd(ctx, descs[1], y1)
+        torch.cuda.synchronize()
+        assert_close(to_host(y1), refs[1], "projection 1 alone")
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_adapter_hot_swap_between_graph_replays(oracle, layout):
+    """The manager commits a new version of one task's adapter while a captured decode graph keeps
+    being replayed (paper Sec. 4.2, Alg. 1): the graph is captured once with adapter version 1,
+    replayed (oracle with version 1), adapter 2 is replaced through marlaas_adapter_table_update
+    (new A, B, new scale, same rank), and the same graph, replayed, matches the oracle with version 2."""
+    w = _small_workload(31 + layout, layout, T=256, K=1024, N=768, ranks=(16, 16, 16, 16))
+    L = HipLayer(w, table=True)
+    y = torch.full((L.T, L.N), float("nan"), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            api.marlaas_lora_fwd(L.ctx, L.desc, y)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert_close(to_host(y), oracle.fwd(*_oracle_args(w), layout=layout), "version 1")
+    assert api.marlaas_adapter_table_version(L.table, 0, 2) == 1
+    plan = api.marlaas_adapter_table_plan_version(L.table)
+    # version 2 of adapter 2: other values, other scale
+    w2 = _small_workload(977, layout, T=256, K=1024, N=768, ranks=(16, 16, 16, 16))
+    newA, newB = to_dev(w2["A"][2]), to_dev(w2["B"][2])
+    api.marlaas_adapter_table_update(L.ctx, L.table, 0, 2, newA, newB, 16, 0.75)
+    assert api.marlaas_adapter_table_version(L.table, 0, 2) == 2
+    assert api.marlaas_adapter_table_version(L.table, 0, 1) == 1
+    assert api.marlaas_adapter_table_version(L.table) == 5
+    assert api.marlaas_adapter_table_plan_version(L.table) == plan       # same rank: captured graphs stay valid
+    y.fill_(float("nan"))
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    A2, B2 = list(w["A"]), list(w["B"])
+    A2[2], B2[2] = w2["A"][2], w2["B"][2]
+    scales2 = np.array(w["scales"], dtype=np.float32)
+    scales2[2] = 0.75
+    ref2 = oracle.fwd(w["x"], w["W"], A2, B2, w["ranks"], scales2, w["ids"], layout=layout)
+    assert_close(to_host(y), ref2, "version 2")
+    # the update itself can be part of a captured sequence: swap back to version 1 inside a graph
+    with torch.cuda.stream(side):
+        g2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g2, stream=side):
+            api.marlaas_adapter_table_update(L.ctx, L.table, 0, 2, L.A[2], L.B[2], 16, float(w["scales"][2]))
+            api.marlaas_lora_fwd(L.ctx, L.desc, y)
+    y.fill_(float("nan"))
+    torch.cuda.synchronize()
+    g2.replay()
+    torch.cuda.synchronize()
+    assert_close(to_host(y), oracle.fwd(*_oracle_args(w), layout=layout), "back to version 1")
+
+
+def test_rank_change_bumps_the_plan_version(oracle):
+    """Replacing an adapter by one of another rank changes the launch plan: the plan version moves,
+    and the next (eager) passes, forward and backward, match the oracle with the new adapter."""
+    w = _small_workload(41, wl.TORCH, ranks=(16, 8, 32, 16))
+    L = HipLayer(w, want_bwd=True, table=True)
+    y, _ = L.fwd()
+    assert_close(to_host(y), oracle.fwd(*_oracle_args(w), layout=wl.TORCH), "before")
+    plan = api.marlaas_adapter_table_plan_version(L.table)
+    w2 = _small_workload(43, wl.TORCH, ranks=(16, 24, 32, 16))           # adapter 1: rank 8 -> 24
+    newA, newB = to_dev(w2["A"][1]), to_dev(w2["B"][1])
+    gA = torch.full(tuple(newA.shape), float("nan"), dtype=torch.float32, device="cuda")
+    gB = torch.full(tuple(newB.shape), float("nan"), dtype=torch.float32, device="cuda")
+    api.marlaas_adapter_table_update(L.ctx, L.table, 0, 1, newA, newB, 24, 1.5, gA, gB)
+    assert api.marlaas_adapter_table_plan_version(L.table) == plan + 1
+    L.A[1], L.B[1], L.gA[1], L.gB[1] = newA, newB, gA, gB
+    nbytes = api.marlaas_workspace_bytes(L.desc, True)
+    L.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    api.marlaas_set_workspace(L.ctx, L.ws)
+    A2, B2 = list(w["A"]), list(w["B"])
+    A2[1], B2[1] = w2["A"][1], w2["B"][1]
+    ranks2 = np.array([16, 24, 32, 16], np.int32)
+    scales2 = np.array(w["scales"], np.float32)
+    scales2[1] = 1.5
+    args2 = (w["x"], w["W"], A2, B2, ranks2, scales2, w["ids"])
+    y, u = L.fwd(save_u=True)
+    assert_close(to_host(y), oracle.fwd(*args2, layout=wl.TORCH), "after y")
+    dX, dA, dB = L.bwd(u_saved=u)
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*args2, w["dY"], layout=wl.TORCH)
+    dA_ref, dB_ref = oracle_grads_in_layout(dA_ref, dB_ref, wl.TORCH)
+    assert_close(to_host(dX), dX_ref, "after dX")
+    for t in range(L.n):
+        assert_close(to_host(dA[t]), dA_ref[t], "after dA[%d]" % t)
+        assert_close(to_host(dB[t]), dB_ref[t], "after dB[%d]" % t)
+
+
+def test_unregistered_adapter_without_tokens_and_table_errors(oracle):
+    rng = np.random.default_rng(9)
+    ranks = [16, 8, 16]
+    T = 150
+    ids = rng.integers(-1, 3, size=T).astype(np.int32)
+    ids[ids == 1] = 0                      # adapter 1 has no tokens and stays unregistered
+    w = wl.make_layer(19, T, 256, 384, ranks, [2.0, 1.0, 0.5], ids, dtype="bf16", layout=wl.TORCH, want_dY=True)
+    ctx = api.marlaas_create(0)
+    x, W = to_dev(w["x"]), to_dev(w["W"])
+    A, B = [to_dev(a) for a in w["A"]], [to_dev(b) for b in w["B"]]
+    seg = api.marlaas_segmap_build(ctx, torch.from_numpy(ids).cuda(), 3)
+    tb = api.marlaas_adapter_table_create(ctx, 3, 1, 16)
+    gA = [torch.full(tuple(a.shape), float("nan"), dtype=torch.float32, device="cuda") for a in A]
+    gB = [torch.full(tuple(b.shape), float("nan"), dtype=torch.float32, device="cuda") for b in B]
+    for t in (0, 2):
+        api.marlaas_adapter_table_update(ctx, tb, 0, t, A[t], B[t], ranks[t], float(w["scales"][t]), gA[t], gB[t])
+    d = api.LoraDesc(x, W, None, None, None, None, seg, layout=wl.TORCH, out_dtype=torch.float32, table=tb)
+    wsbuf = torch.empty(max(api.marlaas_workspace_bytes(d, True), 256), dtype=torch.uint8, device="cuda")
+    api.marlaas_set_workspace(ctx, wsbuf)
+    y = torch.full((T, 384), float("nan"), dtype=torch.float32, device="cuda")
+    dX = torch.full((T, 256), float("nan"), dtype=torch.float32, device="cuda")
+    api.marlaas_lora_fwd(ctx, d, y)
+    api.marlaas_lora_bwd(ctx, d, to_dev(w["dY"]), dX=dX, dA=api.MARLAAS_GRADS_IN_TABLE, dB=api.MARLAAS_GRADS_IN_TABLE)
+    torch.cuda.synchronize()
+    assert_close(to_host(y), oracle.fwd(*_oracle_args(w), layout=wl.TORCH), "y")
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*_oracle_args(w), w["dY"], layout=wl.TORCH)
+    assert_close(to_host(dX), dX_ref, "dX")
+    for t in (0, 2):
+        assert_close(to_host(gA[t]), dA_ref[t].T, "dA[%d]" % t)
+        assert_close(to_host(gB[t]), dB_ref[t].T, "dB[%d]" % t)
+    assert bool(torch.isnan(gA[1]).all())                      # never registered, never touched
+    # errors: a rank beyond the table's, a projection outside it, explicit gradient lists with a table,
+    # tokens on an unregistered adapter
+    for bad in (dict(rank=32), dict(proj=1), dict(t=3)):
+        kw = dict(proj=0, t=1, rank=8)
+        kw.update(bad)
+        with pytest.raises(api.MarlaasError):
+            api.marlaas_adapter_table_update(ctx, tb, kw["proj"], kw["t"], A[1], B[1], kw["rank"], 1.0)
+    with pytest.raises(api.MarlaasError):
+        api.marlaas_lora_bwd(ctx, d, to_dev(w["dY"]), dX=dX, dA=gA, dB=gB)
+    ids2 = ids.copy()
+    ids2[0] = 1
+    seg2 = api.marlaas_segmap_build(ctx, torch.from_numpy(ids2).cuda(), 3)
+    d2 = api.LoraDesc(x, W, None, None, None, None, seg2, layout=wl.TORCH, out_dtype=torch.float32, table=tb)
+    with pytest.raises(api.MarlaasError) as e:
+        api.marlaas_lora_fwd(ctx, d2, y)
+    assert "not registered" in str(e.value)
+    torch.cuda.synchronize()
+
+
+def test_segmap_object_is_reused_across_batches():
+    """One map object, created once with room for the largest batch, regrouped for three batches of
+    different sizes (the last with a bad id): each matches numpy's stable argsort bit for bit, and a
+    failed update leaves the object without a map until the next good one."""
+    ctx = api.marlaas_create(0)
+    m = api.marlaas_segmap_create(ctx, 5000, 40)
+    rng = np.random.default_rng(2)
+    for T, n in ((5000, 40), (300, 7), (1, 1), (0, 3), (4097, 33)):
+        ids = rng.integers(-1, n, size=T).astype(np.int32)
+        api.marlaas_segmap_update(ctx, m, torch.from_numpy(ids).cuda(), n)
+        perm, seg_off = api.marlaas_segmap_export(m)
+        key = np.where(ids < 0, n, ids)
+        assert np.array_equal(perm, np.argsort(key, kind="stable").astype(np.int32))
+        counts = np.bincount(key, minlength=n + 1)
+        assert np.array_equal(seg_off, np.concatenate([[0], np.cumsum(counts)]).astype(np.int32))
+    with pytest.raises(api.MarlaasError):
+        api.marlaas_segmap_update(ctx, m, torch.zeros(5001, dtype=torch.int32, device="cuda"), 4)      # beyond the capacity
+    with pytest.raises(api.MarlaasError):
+        api.marlaas_segmap_update(ctx, m, torch.tensor([0, 9, 1], dtype=torch.int32, device="cuda"), 4)  # bad id
+    with pytest.raises(api.MarlaasError):
+        api.marlaas_segmap_export(m)
+    api.marlaas_segmap_update(ctx, m, torch.tensor([1, 0, 1], dtype=torch.int32, device="cuda"), 2)
+    perm, seg_off = api.marlaas_segmap_export(m)
+    assert perm.tolist() == [1, 0, 2] and seg_off.tolist() == [0, 1, 3, 3]

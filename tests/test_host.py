@@ -7,7 +7,7 @@ import re
 import numpy as np
 
 from paper_2605_08527_amd import api
-from paper_2605_08527_amd import workloads as wl
+from harness import workloads as wl
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 

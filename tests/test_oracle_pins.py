@@ -9,7 +9,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from paper_2605_08527_amd import workloads as wl
+from harness import workloads as wl
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
