@@ -201,6 +201,25 @@ int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, void* y, i
                      void* u_save, void* stream);
 
 /*
+ * marlaas_lora_fwd for callers that cannot allocate device memory or hand over
+ * a workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and same
+ * results as marlaas_lora_fwd, but every intermediate (u, split-contraction
+ * partial sums, the per-call copy of pointer tables) lives in one static array
+ * of MARLAAS_STATIC_SCRATCH_BYTES in the library's device code: each GPU the
+ * library runs on holds its own copy until the process ends, and the call
+ * allocates nothing and ignores marlaas_set_workspace.  A descriptor whose
+ * forward needs more scratch than that (marlaas_workspace_bytes(desc, 0)) gives
+ * MARLAAS_ENOMEM with a message and enqueues nothing.  All calls on one GPU
+ * share the array: calls that may overlap in time (different streams, different
+ * contexts or threads) race on it; calls on one stream are ordered and safe.
+ * Nothing in the array has to be cleared between calls.
+ */
+#define MARLAAS_STATIC_SCRATCH_BYTES (32u << 20)
+int marlaas_lora_fwd_static(marlaas_ctx* ctx, const marlaas_lora_desc* desc, void* y, int64_t ldy,
+                            void* u_save, void* stream);
+
+/*
  * Forward of several projections of the same input in one call (a transformer
  * block's q / k / v, or gate / up: what a rollout engine with multi-LoRA
  * batching, paper Sec. 1, launches per layer for every decode step):

@@ -24,6 +24,7 @@ EXPORTS = [
     "marlaas_adapter_table_create", "marlaas_adapter_table_destroy", "marlaas_adapter_table_update",
     "marlaas_adapter_table_version", "marlaas_adapter_table_plan_version",
     "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd",
+    "marlaas_lora_fwd_static",
     "marlaas_workspace_bytes_multi", "marlaas_lora_fwd_multi",
     "marlaas_u_stride", "marlaas_profile_enable", "marlaas_profile_read",
 ]
@@ -90,6 +91,8 @@ def load():
     lib.marlaas_set_workspace.restype = ctypes.c_int
     lib.marlaas_lora_fwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp]
     lib.marlaas_lora_fwd.restype = ctypes.c_int
+    lib.marlaas_lora_fwd_static.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp]
+    lib.marlaas_lora_fwd_static.restype = ctypes.c_int
     lib.marlaas_lora_bwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
                                      vp, vp, ctypes.c_int, vp]
     lib.marlaas_lora_bwd.restype = ctypes.c_int
@@ -326,6 +329,14 @@ def marlaas_set_workspace(ctx, tensor):
 def marlaas_lora_fwd(ctx, desc, y, u_save=None, stream=None):
     ldy = y.stride(0) if y.shape[0] > 0 else y.shape[1]
     _check(ctx, load().marlaas_lora_fwd(ctx.handle, desc.ref, _ptr(y), ldy, _ptr(u_save), _stream_ptr(stream)))
+
+
+MARLAAS_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def marlaas_lora_fwd_static(ctx, desc, y, u_save=None, stream=None):
+    ldy = y.stride(0) if y.shape[0] > 0 else y.shape[1]
+    _check(ctx, load().marlaas_lora_fwd_static(ctx.handle, desc.ref, _ptr(y), ldy, _ptr(u_save), _stream_ptr(stream)))
 
 
 def _desc_array(descs):

@@ -10,6 +10,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -20,6 +21,7 @@ struct marlaas_ctx {
   int device = 0;
   void* ws = nullptr;
   size_t ws_bytes = 0;
+  void* static_ws = nullptr;     // device address of this GPU's static scratch array
   std::string err;
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
@@ -64,6 +66,26 @@ struct marlaas_adapter_table {
 
 static const size_t WS_ALIGN = 256;
 static const int64_t EXT_CAP_MAX = 1 << 16;   // extended columns a table can describe
+
+// Scratch of marlaas_lora_fwd_static: one array per GPU, part of the loaded code object, so no
+// call ever allocates it.  Host code must not use the array's name as an address: the device
+// address is looked up once per device (in marlaas_create, with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[MARLAAS_STATIC_SCRATCH_BYTES];
+static const int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static hipError_t static_scratch_of(int device, void** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // for the current device
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 static int fail(marlaas_ctx* ctx, int status, const char* fmt, ...) {
   if (ctx) {
@@ -126,10 +148,14 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   if (!out) return MARLAAS_EINVAL;
   *out = nullptr;
   int count = 0;
-  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return MARLAAS_EHIP;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count || device >= MAX_DEVICES) return MARLAAS_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return MARLAAS_EHIP;
+  void* sp = nullptr;
+  if (static_scratch_of(device, &sp) != hipSuccess || !sp) return MARLAAS_EHIP;
   marlaas_ctx* ctx = new (std::nothrow) marlaas_ctx();
   if (!ctx) return MARLAAS_ENOMEM;
   ctx->device = device;
+  ctx->static_ws = sp;
   *out = ctx;
   return MARLAAS_OK;
 }
@@ -642,6 +668,18 @@ extern "C" int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, vo
                                 void* u_save, void* stream) {
   if (!ctx) return MARLAAS_EINVAL;
   return fwd_impl(ctx, d, y, ldy, u_save, stream, ctx->ws, ctx->ws_bytes);
+}
+
+extern "C" int marlaas_lora_fwd_static(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy,
+                                       void* u_save, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  int rc = check_sizes(ctx, d);
+  if (rc != MARLAAS_OK) return rc;
+  const size_t need = plan_workspace(d, 0).total;
+  if (need > (size_t)MARLAAS_STATIC_SCRATCH_BYTES)
+    return fail(ctx, MARLAAS_ENOMEM, "this forward needs %zu scratch bytes, the static scratch holds %zu: use marlaas_lora_fwd with a workspace",
+                need, (size_t)MARLAAS_STATIC_SCRATCH_BYTES);
+  return fwd_impl(ctx, d, y, ldy, u_save, stream, ctx->static_ws, (size_t)MARLAAS_STATIC_SCRATCH_BYTES);
 }
 
 // ------------------------------------------------------------------ forward, several projections
