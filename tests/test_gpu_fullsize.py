@@ -1,51 +1,104 @@
 """GPU parity at the full benchmark sizes (configurations 2, 3, 4), in the launch
-configuration bench.py times (torch layout, bf16 outputs, prebuilt segment map):
-y and dX are compared with the oracle on a seeded sample of rows that includes
-both ends of every adapter segment, dA_t / dB_t in full for a sample of
-adapters.  Tolerance: the bf16-output bounds (max 1e-2, mean 2.5e-3: the final
-rounding alone costs about 1.4e-3 mean) for y / dX, 1e-2 / 1e-3 for the fp32
-gradients."""
+configuration bench.py times (torch layout, adapters in a table, prebuilt segment map), seeds 0-2.
+
+Gate: fp32 outputs (the fp32 accumulators as they are) against the fp64 oracle at floored relative
+error max <= 1e-2, mean <= 1e-3 per output tensor.  y, dX and u are compared on >= 1024 sampled
+rows: both ends of every adapter segment, the rows on either side of row-tile edges of the grouped
+order, and seeded random rows; dA_t / dB_t in full, for every adapter of configurations 3 and 4.
+
+Secondary: the same passes with bf16 outputs (what bench.py writes).  The final rounding alone
+puts a floor under their error (the oracle's own values rounded to bf16 score about 8.7e-4 mean),
+so they are held to that measured floor plus 5 %, and to one bf16 unit in the last place (2^-8) at
+the maximum."""
 import numpy as np
 import pytest
 import torch
 
+from paper_2605_08527_amd import api
 from harness import workloads as wl
 from helpers import HipLayer, assert_close, to_host
 
 pytestmark = pytest.mark.gpu
 
 
-def _sample_rows(ids, n_extra, seed):
+def _sample_rows(ids, n_extra, seed, tile=256):
     T = ids.shape[0]
     rng = np.random.default_rng(seed)
-    order = np.argsort(ids, kind="stable")
+    order = np.argsort(ids, kind="stable")          # grouped order (ids >= 0 here)
     key = ids[order]
-    first = order[np.r_[0, np.flatnonzero(np.diff(key)) + 1]]
-    last = order[np.r_[np.flatnonzero(np.diff(key)), T - 1]]
+    cuts = np.flatnonzero(np.diff(key))
+    first = order[np.r_[0, cuts + 1]]
+    last = order[np.r_[cuts, T - 1]]
+    edges = np.arange(tile, T, tile)
+    edges = edges[rng.permutation(edges.size)[:128]]
+    at_edges = order[np.concatenate([edges - 1, edges])] if edges.size else np.zeros(0, np.int64)
     extra = rng.integers(0, T, size=n_extra)
-    return np.unique(np.concatenate([first, last, extra, [0, T - 1]])).astype(np.int64)
+    return np.unique(np.concatenate([first, last, at_edges, extra, [0, T - 1]])).astype(np.int64)
 
 
-@pytest.mark.parametrize("cfg,n_extra,adapters", [(2, 96, None), (3, 48, [0, 15]), (4, 96, [0, 7, 21, 40, 63])])
-def test_full_size_sampled(oracle, cfg, n_extra, adapters):
-    w = wl.make_config(cfg, seed=0, layout=wl.TORCH)
+def _bf16_floor(ref):
+    """Error of the oracle's own values after rounding to bf16: (max, mean) of the metric."""
+    rounded = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
+    mx, mean, _ = wl.rel_err_stats(rounded, ref)
+    return mx, mean
+
+
+def _check_bf16(got, ref, what):
+    mx, mean, _ = wl.rel_err_stats(got, ref)
+    fmx, fmean = _bf16_floor(ref)
+    assert np.all(np.isfinite(got)), what
+    assert mean <= 1.05 * fmean + 2e-5 and mx <= 2.0 ** -8 * 1.01, \
+        "%s (bf16 out): max %.3e mean %.3e, rounding floor max %.3e mean %.3e" % (what, mx, mean, fmx, fmean)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("cfg,adapters", [(2, None), (3, list(range(16))), (4, list(range(64)))])
+def test_full_size(oracle, cfg, adapters, seed):
+    w = wl.make_config(cfg, seed=seed, layout=wl.TORCH)
     bwd = w["dY"] is not None
-    L = HipLayer(w, out_dtype=torch.bfloat16, want_bwd=bwd)
-    rows = _sample_rows(w["ids"], n_extra, 100 + cfg)
-    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
-    y, u = L.fwd(save_u=bwd)
-    y_ref = oracle.fwd(*args, layout=w["layout"], rows=rows)
+    rows = _sample_rows(w["ids"], 900, 100 * seed + cfg)
+    assert rows.size >= 1024
     rows_t = torch.from_numpy(rows).cuda()
-    assert_close(to_host(y[rows_t]), y_ref, "cfg%d y" % cfg, 1e-2, 2.5e-3)
-    assert bool(torch.isfinite(y.float()).all())
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    y_ref, u_ref = oracle.fwd(*args, layout=w["layout"], rows=rows, want_u=True)
+    if bwd:
+        dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=w["layout"], rows=rows, adapters=adapters)
+    # ---- gate: fp32 outputs
+    L = HipLayer(w, out_dtype=torch.float32, want_bwd=bwd, table=True)
+    y, u = L.fwd(save_u=True)
+    tag = "cfg%d seed%d" % (cfg, seed)
+    assert_close(to_host(y[rows_t]), y_ref, tag + " y")
+    assert bool(torch.isfinite(y).all())
+    # u_save: s_t (x A_t) in grouped order; grouped position of token i through the exported map
+    perm, seg_off = api.marlaas_segmap_export(L.map)
+    pos = np.empty(L.T, np.int64)
+    pos[perm] = np.arange(L.T)
+    sc = np.asarray(w["scales"], np.float64)[w["ids"][rows]]
+    want_u = np.zeros((rows.size, u.shape[1]))
+    want_u[:, :u_ref.shape[1]] = u_ref * sc[:, None]
+    assert_close(to_host(u[torch.from_numpy(pos[rows]).cuda()]), want_u, tag + " u_save")
+    del y
     if bwd:
         dX, dA, dB = L.bwd(u_saved=u)
-        dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=w["layout"], rows=rows, adapters=adapters)
-        assert_close(to_host(dX[rows_t]), dX_ref, "cfg%d dX" % cfg, 1e-2, 2.5e-3)
+        assert_close(to_host(dX[rows_t]), dX_ref, tag + " dX")
+        assert bool(torch.isfinite(dX).all())
+        del dX
         for s, t in enumerate(adapters):      # oracle gradients are in math orientation
-            assert_close(to_host(dA[t]), dA_ref[s].T, "cfg%d dA[%d]" % (cfg, t))
-            assert_close(to_host(dB[t]), dB_ref[s].T, "cfg%d dB[%d]" % (cfg, t))
+            assert_close(to_host(dA[t]), dA_ref[s].T, tag + " dA[%d]" % t)
+            assert_close(to_host(dB[t]), dB_ref[s].T, tag + " dB[%d]" % t)
         assert all(bool(torch.isfinite(g).all()) for g in dA + dB)
+    # ---- secondary: bf16 outputs, same inputs, same map and table
+    Lb = HipLayer(w, out_dtype=torch.bfloat16, want_bwd=bwd, table=True)
+    del L
+    torch.cuda.empty_cache()
+    yb, ub = Lb.fwd(save_u=bwd)
+    _check_bf16(to_host(yb[rows_t]), y_ref, tag + " y")
+    if bwd:
+        dXb, dAb, dBb = Lb.bwd(u_saved=ub)
+        _check_bf16(to_host(dXb[rows_t]), dX_ref, tag + " dX")
+        for s, t in enumerate(adapters[:4]):
+            assert_close(to_host(dAb[t]), dA_ref[s].T, tag + " dA[%d] (bf16-output pass)" % t)
+            assert_close(to_host(dBb[t]), dB_ref[s].T, tag + " dB[%d] (bf16-output pass)" % t)
 
 
 @pytest.mark.parametrize("layout", [wl.MATH, wl.TORCH])
