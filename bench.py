@@ -67,6 +67,8 @@ def parse_args():
     ap.add_argument("--no-multi-projection", action="store_true",
                     help="skip the q/k/v multi-projection measurement of the decode configuration")
     ap.add_argument("--no-event-stats", action="store_true", help="skip the extra event-timed iterations (for profiles)")
+    ap.add_argument("--no-packed-weight", action="store_true",
+                    help="decode configuration without the packed copy of the weight (the kernels then stage W through LDS)")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -153,8 +155,11 @@ def build_case(cfg, args, torch, api, wl):
         for t in range(n):
             api.marlaas_adapter_table_update(ctx, table, 0, t, A[t], B[t], int(ranks[t]), float(scales[t]),
                                              case["dA"][t] if sh["bwd"] else None, case["dB"][t] if sh["bwd"] else None)
-        desc = api.LoraDesc(x, W, None, None, None, None, segmap, layout=layout, out_dtype=torch.bfloat16, table=table)
-        sets.append(dict(x=x, W=W, A=A, B=B, table=table, desc=desc))
+        # small batches read a packed copy of the frozen weight, written once per weight (outside the timed region)
+        Wp = api.marlaas_pack_weight(ctx, W, layout, 0) if (cfg == 1 and not args.no_packed_weight) else None
+        desc = api.LoraDesc(x, W, None, None, None, None, segmap, layout=layout, out_dtype=torch.bfloat16, table=table,
+                            W_packed_fwd=Wp)
+        sets.append(dict(x=x, W=W, A=A, B=B, table=table, desc=desc, Wp=Wp))
     case["sets"] = sets
     case["y"] = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
     ws_bytes = api.marlaas_workspace_bytes(sets[0]["desc"], sh["bwd"])
@@ -315,8 +320,10 @@ def multi_projection_decode(case, args, steps, warmup, torch, api):
             B = [device_normal((N, int(r)) if layout else (int(r), N), float(r) ** -0.5, gen, torch) for r in ranks]
             for t in range(n):
                 api.marlaas_adapter_table_update(ctx, table, p, t, A[t], B[t], int(ranks[t]), 2.0)
-            projs.append(dict(W=W, A=A, B=B, desc=api.LoraDesc(s["x"], W, None, None, None, None, segmap, layout=layout,
-                                                              out_dtype=torch.bfloat16, table=table, proj=p)))
+            Wp = api.marlaas_pack_weight(ctx, W, layout, 0) if not args.no_packed_weight else None
+            projs.append(dict(W=W, A=A, B=B, Wp=Wp,
+                              desc=api.LoraDesc(s["x"], W, None, None, None, None, segmap, layout=layout,
+                                                out_dtype=torch.bfloat16, table=table, proj=p, W_packed_fwd=Wp)))
         sets.append(projs)
     ys = [torch.empty((T, N), dtype=torch.bfloat16, device="cuda") for N in Ns]
     descs0 = [pr["desc"] for pr in sets[0]]
@@ -523,6 +530,8 @@ def main():
         "config": {"workload": names[head_cfg], "layout": args.layout, "launch": h["launch"],
                    "out_dtype": "bf16", "weight_sets_rotated": args.rotate if head_cfg == 1 else 1,
                    "adapters": "registered in an adapter table, outside the timed region",
+                   "weight": ("row-major" if (args.no_packed_weight or head_cfg != 1) else
+                              "frozen W also held as a packed copy (marlaas_pack_weight, once, outside the timed region)"),
                    "segmap": "prebuilt, outside the timed region"},
         "tflops": h["tflops"], "roofline": h["roofline"],
     }

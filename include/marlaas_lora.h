@@ -90,6 +90,11 @@ typedef struct {
   const marlaas_adapter_table* table;
   int32_t proj;
   int32_t reserved;      /* set to 0 */
+  /* Optional (bf16 only): packed copies of W written once by marlaas_pack_weight, for the forward
+   * product (direction 0) and for the backward product dY W^T (direction 1).  Small batches
+   * (decode) then read the packed copy and not W.  NULL means not available. */
+  const void* W_packed_fwd;
+  const void* W_packed_bwd;
 } marlaas_lora_desc;
 
 /* Create a context bound to HIP device `device`.  *out is NULL on failure. */
@@ -168,6 +173,26 @@ int marlaas_adapter_table_update(marlaas_ctx* ctx, marlaas_adapter_table* table,
                                  void* dA, void* dB, void* stream);
 int64_t marlaas_adapter_table_version(const marlaas_adapter_table* table, int32_t proj, int32_t t);
 int64_t marlaas_adapter_table_plan_version(const marlaas_adapter_table* table);
+
+/*
+ * Packed weight.  The base weight is frozen and shared by every tenant (paper
+ * Sec. 1 principle (1)), so it can be laid out once for the kernel that streams
+ * it on every decode step: marlaas_pack_weight writes W (bf16, either layout)
+ * into `packed`, a caller-owned device buffer of marlaas_packed_weight_bytes
+ * bytes, in the order in which the small-batch kernel's matrix-core fragments
+ * consume it (blocks of 16 output columns x 32 contraction values, 1 KB each,
+ * zero beyond the matrix), for direction 0 = forward (x W) or 1 = backward
+ * (dY W^T).  Only enqueues one kernel on `stream`; allocates nothing.  Pass the
+ * buffer in marlaas_lora_desc::W_packed_fwd / W_packed_bwd together with W
+ * itself (large batches keep reading W); the results are those of the unpacked
+ * path up to summation order.  With adapters, the packed path is taken when the
+ * factors that multiply the layer input are stored contraction-contiguous
+ * (forward: torch layout; backward: math layout); otherwise the call runs as
+ * without a packed copy.
+ */
+size_t marlaas_packed_weight_bytes(int64_t d_in, int64_t d_out, int32_t direction);
+int marlaas_pack_weight(marlaas_ctx* ctx, const void* W, int64_t ldw, int64_t d_in, int64_t d_out,
+                        int32_t layout, int32_t direction, void* packed, void* stream);
 
 /*
  * Scratch memory.  The caller hands over one device buffer (e.g. a torch

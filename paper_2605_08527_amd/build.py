@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmarlaas_lora.so")
-SOURCES = ["api.hip", "segmap.hip", "tables.hip", "gemm_bf16.hip", "lora_small.hip", "lora_f32.hip"]
+SOURCES = ["api.hip", "segmap.hip", "tables.hip", "gemm_bf16.hip", "gemm_decode.hip", "lora_small.hip", "lora_f32.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

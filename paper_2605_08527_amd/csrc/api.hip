@@ -366,7 +366,8 @@ extern "C" int marlaas_adapter_table_update(marlaas_ctx* ctx, marlaas_adapter_ta
   const bool rank_changed = tb->hranks[i] != rank;
   HIP_TRY(ctx, enqueue_write_entries(tb->dev, i, 1, &e, st));
   HIP_TRY(ctx, enqueue_write_grads(tb->dev, i, 1, &g, st));
-  if (rank_changed) HIP_TRY(ctx, enqueue_derive(tb->dev, (int64_t)tb->n * tb->n_proj, st));
+  // (the extended-column list carries copies of the factor pointers: always rebuilt)
+  HIP_TRY(ctx, enqueue_derive(tb->dev, (int64_t)tb->n * tb->n_proj, st));
   tb->host[i] = e; tb->hgrads[i] = g; tb->hranks[i] = rank; tb->hscales[i] = scale;
   ++tb->versions[i];
   ++tb->updates;
@@ -521,6 +522,8 @@ static int check_tensors(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   if (d->T > 0 && !d->x) return fail(ctx, MARLAAS_EINVAL, "x is null");
   if (!d->W) return fail(ctx, MARLAAS_EINVAL, "W is null");
   if (!aligned16(d->x) || !aligned16(d->W)) return fail(ctx, MARLAAS_EALIGN, "x and W must be 16-byte aligned");
+  if (!aligned16(d->W_packed_fwd) || !aligned16(d->W_packed_bwd)) return fail(ctx, MARLAAS_EALIGN, "packed weights must be 16-byte aligned");
+  if ((d->W_packed_fwd || d->W_packed_bwd) && d->in_dtype != MARLAAS_BF16) return fail(ctx, MARLAAS_EINVAL, "packed weights exist for bf16 only");
   if (d->ldx < d->d_in || (d->ldx * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldx=%lld", (long long)d->ldx);
   const int64_t wcols = d->layout == MARLAAS_LAYOUT_MATH ? d->d_out : d->d_in;
   if (d->ldw < wcols || (d->ldw * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldw=%lld", (long long)d->ldw);
@@ -601,6 +604,33 @@ static bool bank_can_fuse(const Bank& b) {
   return b.n_ext > 0 && (int64_t)b.ext_base + b.n_ext <= b.all.ext_cap;
 }
 
+// ------------------------------------------------------------------ packed weight
+extern "C" size_t marlaas_packed_weight_bytes(int64_t d_in, int64_t d_out, int32_t direction) {
+  if (d_in <= 0 || d_out <= 0 || d_in > (1 << 24) || d_out > (1 << 24) || (direction != 0 && direction != 1)) return 0;
+  return direction == 0 ? packed_weight_bytes(d_in, d_out) : packed_weight_bytes(d_out, d_in);
+}
+
+extern "C" int marlaas_pack_weight(marlaas_ctx* ctx, const void* W, int64_t ldw, int64_t d_in, int64_t d_out,
+                                   int32_t layout, int32_t direction, void* packed, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!W || !packed) return fail(ctx, MARLAAS_EINVAL, "pack_weight: null pointer");
+  if (d_in <= 0 || d_out <= 0 || d_in > (1 << 24) || d_out > (1 << 24)) return fail(ctx, MARLAAS_EINVAL, "pack_weight: bad sizes");
+  if ((d_in & 7) || (d_out & 7)) return fail(ctx, MARLAAS_EALIGN, "d_in and d_out must be multiples of 8");
+  if (layout != MARLAAS_LAYOUT_MATH && layout != MARLAAS_LAYOUT_TORCH) return fail(ctx, MARLAAS_EINVAL, "pack_weight: bad layout");
+  if (direction != 0 && direction != 1) return fail(ctx, MARLAAS_EINVAL, "pack_weight: direction must be 0 (forward) or 1 (backward)");
+  const int64_t wcols = layout == MARLAAS_LAYOUT_MATH ? d_out : d_in;
+  if (ldw < wcols) return fail(ctx, MARLAAS_EALIGN, "pack_weight: ldw=%lld", (long long)ldw);
+  if (!aligned16(W) || !aligned16(packed)) return fail(ctx, MARLAAS_EALIGN, "pack_weight: pointers must be 16-byte aligned");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  // element (i, j) of W (i over d_in, j over d_out) is at W[i * si + j * sj]
+  const int64_t si = layout == MARLAAS_LAYOUT_MATH ? ldw : 1, sj = layout == MARLAAS_LAYOUT_MATH ? 1 : ldw;
+  if (direction == 0)   // forward: contraction over d_in, outputs over d_out
+    HIP_TRY(ctx, launch_pack_weight((const bf16_t*)W, si, sj, d_in, d_out, (bf16_t*)packed, (hipStream_t)stream));
+  else                  // backward (dX = dY W^T): contraction over d_out, outputs over d_in
+    HIP_TRY(ctx, launch_pack_weight((const bf16_t*)W, sj, si, d_out, d_in, (bf16_t*)packed, (hipStream_t)stream));
+  return MARLAAS_OK;
+}
+
 // ------------------------------------------------------------------ forward
 static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy, void* u_save, void* stream,
                     void* ws, size_t ws_bytes) {
@@ -652,7 +682,7 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                   fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ws + p.wt_off) : nullptr,
-                                  p.wt_bytes, st));
+                                  p.wt_bytes, (const bf16_t*)d->W_packed_fwd, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -821,10 +851,16 @@ extern "C" int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc*
     fuse.n_ext = n_ext; fuse.ranks_mult8 = mult8; fuse.u_out = nullptr; fuse.t0 = 0; fuse.ext_base = 0;
   }
   const int32_t* perm = map->identity ? nullptr : map->perm_dev;
+  // packed copies of every projection's weight (and factors stored contraction-contiguous, or no
+  // adapters): the decode kernel reads those
+  bool packed = !lora || form == FORM_NT;
+  for (int p = 0; p < n_proj; ++p) if (!descs[p].W_packed_fwd) packed = false;
+  if (packed)
+    for (int p = 0; p < n_proj; ++p) { proj[p].W = descs[p].W_packed_fwd; proj[p].ldw = packed_weight_ksteps(d0->d_in); }
   PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16_multi((const bf16_t*)d0->x, d0->ldx, form, d0->T, d0->d_in, perm,
                                       map->seg_off_dev, n, table, proj.data(), n_proj,
                                       d0->out_dtype == MARLAAS_F32, (float*)ctx->ws, mp.part_bytes, map->chunks_dev,
-                                      map->n_chunks, lora ? &fuse : nullptr, st));
+                                      map->n_chunks, lora ? &fuse : nullptr, packed ? 1 : 0, st));
   return MARLAAS_OK;
 }
 
@@ -923,7 +959,7 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                     out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                     fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
-                                    p.wt_bytes, st));
+                                    p.wt_bytes, (const bf16_t*)d->W_packed_bwd, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));

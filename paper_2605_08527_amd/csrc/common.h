@@ -35,8 +35,11 @@ struct RowChunk {
   int32_t row0, nrows, t, pad;
 };
 
-// Extended column e of the fused shrink: rank q of adapter t (e = rank offset of t + q).
+// Extended column e of the fused shrink: rank q of adapter entry t (e = rank offset of t + q), with
+// that entry's factor pointers copied in, so that a kernel finds its source row with one load.
 struct ExtCol {
+  const void* A;
+  const void* B;
   int32_t t, q;
 };
 
@@ -59,7 +62,7 @@ static constexpr int MAX_PROJ = 8;
 // slice of the caller's workspace (written at the start of the call); the passes only read them.
 //   entries[i], grads[i] : i = projection * n_adapters + adapter
 //   roff[i]              : sum of the ranks of entries 0 .. i - 1 (P + 1 values, P = entries)
-//   cols[e]              : (entry, rank index) of extended column e, for e < min(roff[P], ext_cap)
+//   cols[e]              : (factor pointers, entry, rank index) of extended column e, for e < min(roff[P], ext_cap)
 struct DevTables {
   AdapterEntry* entries = nullptr;
   GradEntry* grads = nullptr;
@@ -75,7 +78,7 @@ hipError_t enqueue_write_entries(const DevTables& d, int64_t first, int64_t coun
                                  hipStream_t stream);
 hipError_t enqueue_write_grads(const DevTables& d, int64_t first, int64_t count, const GradEntry* host,
                                hipStream_t stream);
-// Enqueue: roff and cols recomputed from the ranks in entries[0 .. P).
+// Enqueue: roff and cols recomputed from entries[0 .. P) (after any change of a rank or a pointer).
 hipError_t enqueue_derive(const DevTables& d, int64_t P, hipStream_t stream);
 
 // How a [contraction, output] operand is stored.
@@ -145,7 +148,10 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
-                            hipStream_t stream);
+                            const bf16_t* Bpacked, hipStream_t stream);
+// (Bpacked: optional packed copy of Bop for this contraction, used by small batches; with it the
+// shrink is only fused when the adapters' factors are stored contraction-contiguous, which the
+// caller says by passing fuse only then.)
 // Several projections of the same input in one pass (small batches only: 128 x 128 tiles with
 // the shrink carried as extended columns, or no adapters at all).  `proj_host` holds the n_proj
 // entries (host memory); `table` is the combined adapter table ([projection][adapter]), `fuse` (null:
@@ -160,7 +166,14 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
                                   const AdapterEntry* table, const ProjEntry* proj_host,
                                   int n_proj, int out_is_f32, float* partials,
                                   size_t partial_bytes, const RowChunk* chunks, int n_chunks,
-                                  const GemmFuse* fuse, hipStream_t stream);
+                                  const GemmFuse* fuse, int packed, hipStream_t stream);
+// Packed copy of a [contraction C, output O] operand for the decode kernel, in MFMA fragment order
+// (16 output columns x 32 contraction values per kilobyte, zero beyond the matrix).  Element (c, o)
+// of the source is at src[c * sc + o * so].
+size_t packed_weight_bytes(int64_t C, int64_t O);
+int64_t packed_weight_ksteps(int64_t C);
+hipError_t launch_pack_weight(const bf16_t* src, int64_t sc, int64_t so, int64_t C, int64_t O, bf16_t* dst,
+                              hipStream_t stream);
 // Scratch for a transposed copy of the weight: a large batch whose weight is stored
 // [contraction][output] runs faster on a [output][contraction] copy made per call (the copy
 // costs two passes over the weight, the GEMM gains about a quarter).  0: not used for these sizes.

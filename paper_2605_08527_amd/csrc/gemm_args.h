@@ -1,0 +1,63 @@
+// Kernel arguments and LDS layout helpers shared by the GEMM kernels (large-batch, small-batch and
+// decode) and the split-contraction finish kernel.
+#pragma once
+#include "common.h"
+
+namespace marlaas {
+
+struct GemmArgs {
+  const bf16_t* Aop; int64_t lda;
+  const bf16_t* Bop; int64_t ldb;
+  int64_t T, Kc, Nout;
+  const int32_t* perm;
+  const int32_t* seg_off;
+  int n_adapters;
+  const AdapterEntry* table;
+  int which;               // 0: L_t = entry.A, 1: L_t = entry.B
+  const float* U; int r_stride;
+  void* out; int64_t ldo;
+  int tiles_m, tiles_n;
+  // split-K (few row tiles, e.g. decode): workgroup (tile, ks) handles contraction values
+  // [ks * kchunk, (ks + 1) * kchunk) and leaves its fp32 sums in `partials`
+  // ([ks][tiles_m * 256][ldp], grouped row order); splitk_finish_kernel adds them up.
+  int ksplit; int64_t kchunk; float* partials;
+  int64_t ldp;             // row stride of the partial sums (tiles_n * tile width)
+  int64_t pm;              // rows of one split's partial sums (tiles_m * tile height)
+  const RowChunk* chunks; int n_chunks;   // row chunks of the grouped order (finish kernel)
+  // Fused shrink of the small-batch path: every column tile also computes 32 columns of
+  // X * [all adapters' shrink factors] (extended column e = rank offset of adapter t + q); the
+  // finish kernel picks each row's own adapter, scales and writes u_out.
+  const ExtCol* ext_cols; const int32_t* ext_roff; int n_ext;   // n_ext = sum of the ranks; 0: not fused
+  // ExtCol::t counts entries of the whole adapter bank, `table` may start inside it: entry index
+  // of table[0]; ext_roff[] are offsets in the bank's column space, ext_base the call's first one
+  int ext_t0, ext_base;
+  float* u_part; int64_t ldu;   // [ks][pm][ldu] fp32 partial sums of the extended columns
+  float* u_out;                 // [T][r_stride] (may be null)
+  // Several projections in one pass (small-batch kernels only; n_proj <= 1: the fields above
+  // describe the only projection).  Column tile tn belongs to the last projection whose tile0 <=
+  // tn; `table`, `ext_roff` and ExtCol::t then index [projection][adapter].
+  int n_proj;
+  int fin_cols;                 // column chunks of the finish kernel's grid, all projections
+  ProjEntry proj[MAX_PROJ];     // by value: read with wave-uniform loads from the kernel arguments
+};
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// LDS byte offset of 16-byte unit `unit` of row `row` in a [rows][64] bf16 tile.
+__device__ __forceinline__ int swz_rowk(int row, int unit) {
+  return row * 128 + ((unit ^ ((row >> 1) & 7)) << 4);
+}
+// s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
+#define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
+
+// Small-batch kernels: tile of the partial sums and of the finish kernel's grid.
+static constexpr int SK_BM = 128, SK_BN = 128, SK_BX = 32;
+
+// Decode kernel on a packed copy of the weight (gemm_decode.hip): same tiles, same partial-sum
+// layout and same finish kernel as gemm_skinny_kernel.  Bop (and every ProjEntry::W) is the packed
+// copy, ldb (ProjEntry::ldw) its k-steps per column block; the adapters' factors must be stored
+// contraction-contiguous when the shrink is fused (n_ext > 0).
+hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t stream);
+
+}  // namespace marlaas

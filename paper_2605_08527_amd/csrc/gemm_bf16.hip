@@ -27,7 +27,7 @@
 // the finish kernel adds the splits, applies the expand in fp32 and scatters
 // the rows.  transpose_bf16_kernel: per-call transposed copy of a weight that
 // is stored output-contiguous, for large batches.
-#include "common.h"
+#include "gemm_args.h"
 
 #include <atomic>
 #include <cstring>
@@ -50,49 +50,6 @@ static constexpr int SLOT_B_OFF = STAGE_BYTES;
 static constexpr int RING_SLOTS = 2;
 static constexpr int GEMM_LDS = RING_SLOTS * SLOT_BYTES + BM * 4;  // ring + token ids
 
-struct GemmArgs {
-  const bf16_t* Aop; int64_t lda;
-  const bf16_t* Bop; int64_t ldb;
-  int64_t T, Kc, Nout;
-  const int32_t* perm;
-  const int32_t* seg_off;
-  int n_adapters;
-  const AdapterEntry* table;
-  int which;               // 0: L_t = entry.A, 1: L_t = entry.B
-  const float* U; int r_stride;
-  void* out; int64_t ldo;
-  int tiles_m, tiles_n;
-  // split-K (few row tiles, e.g. decode): workgroup (tile, ks) handles contraction values
-  // [ks * kchunk, (ks + 1) * kchunk) and leaves its fp32 sums in `partials`
-  // ([ks][tiles_m * 256][ldp], grouped row order); splitk_finish_kernel adds them up.
-  int ksplit; int64_t kchunk; float* partials;
-  int64_t ldp;             // row stride of the partial sums (tiles_n * tile width)
-  int64_t pm;              // rows of one split's partial sums (tiles_m * tile height)
-  const RowChunk* chunks; int n_chunks;   // row chunks of the grouped order (finish kernel)
-  // Fused shrink of the small-batch path: every column tile also computes 32 columns of
-  // X * [all adapters' shrink factors] (extended column e = rank offset of adapter t + q); the
-  // finish kernel picks each row's own adapter, scales and writes u_out.
-  const ExtCol* ext_cols; const int32_t* ext_roff; int n_ext;   // n_ext = sum of the ranks; 0: not fused
-  // ExtCol::t counts entries of the whole adapter bank, `table` may start inside it: entry index
-  // of table[0]; ext_roff[] are offsets in the bank's column space, ext_base the call's first one
-  int ext_t0, ext_base;
-  float* u_part; int64_t ldu;   // [ks][pm][ldu] fp32 partial sums of the extended columns
-  float* u_out;                 // [T][r_stride] (may be null)
-  // Several projections in one pass (small-batch kernels only; n_proj <= 1: the fields above
-  // describe the only projection).  Column tile tn belongs to the last projection whose tile0 <=
-  // tn; `table`, `ext_roff` and ExtCol::t then index [projection][adapter].
-  int n_proj;
-  int fin_cols;                 // column chunks of the finish kernel's grid, all projections
-  ProjEntry proj[MAX_PROJ];     // by value: read with wave-uniform loads from the kernel arguments
-};
-
-typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// LDS byte offset of 16-byte unit `unit` of row `row` in a [rows][64] bf16 tile.
-__device__ __forceinline__ int swz_rowk(int row, int unit) {
-  return row * 128 + ((unit ^ ((row >> 1) & 7)) << 4);
-}
 // LDS byte offset of 16-byte unit `unit` (of 32) of k-row `k` in a [64][256] bf16 tile.
 __device__ __forceinline__ int kn_swz(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
 __device__ __forceinline__ int swz_kn(int k, int unit) {
@@ -275,8 +232,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   static_assert(MT == 8 && NT == 8 && DPW == 8, "the interleaved schedule below is written for 8 x 8 MFMA tiles per wave");
 
-// s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
-#define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 // raw barrier: LDS traffic of this wave is complete, DMA traffic is tracked by hand with vmcnt
 #define RING_BARRIER() asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
@@ -596,7 +551,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 // them in flight (48 KB of weight per compute unit), which is what covers the HBM latency.  Each
 // wave owns 64 x 64.  The result always goes to fp32 partial rows; splitk_finish_kernel adds the
 // splits, the LoRA expand and the rounding.
-static constexpr int SK_BM = 128, SK_BN = 128, SK_BX = 32;
 static constexpr int SK_A_BYTES = SK_BM * BK * 2;         // 16 KB
 static constexpr int SK_B_BYTES = SK_BN * BK * 2;         // 16 KB
 static constexpr int SK_X_BYTES = SK_BX * BK * 2;         // 4 KB: extended (shrink) columns
@@ -653,15 +607,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
       int e = tn * SK_BX + row;
       if (e >= a.n_ext) e = a.n_ext - 1;
       const ExtCol c = a.ext_cols[e];
-      const AdapterEntry en = a.table[c.t - a.ext_t0];
-      x_src = (const bf16_t*)(a.which ? en.A : en.B) + (int64_t)c.q * a.Kc + kbeg + unit * 8;
+      x_src = (const bf16_t*)(a.which ? c.A : c.B) + (int64_t)c.q * a.Kc + kbeg + unit * 8;
       x_step = BK;
     } else {                         // tile [64 k][32 e], 64-byte rows: factor stored [Kc][r], r % 8 == 0
       const int k = wave * 16 + (lane >> 2);
       int e = tn * SK_BX + (lane & 3) * 8;
       if (e >= a.n_ext) e = a.n_ext - 8;
       const ExtCol c = a.ext_cols[e];
-      const AdapterEntry en = a.table[c.t - a.ext_t0];
+      const AdapterEntry en = a.table[c.t - a.ext_t0];     // (this storage form needs the rank)
       x_src = (const bf16_t*)(a.which ? en.A : en.B) + (kbeg + k) * en.rank + c.q;
       x_step = (int64_t)BK * en.rank;
     }
@@ -1040,17 +993,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(GemmArgs a) {
         int e = tn * SK_BX + row;
         if (e >= a.n_ext) e = a.n_ext - 1;
         const ExtCol c = a.ext_cols[e];
-        const AdapterEntry en = a.table[c.t - a.ext_t0];
         uint4 w = zero4;
-        if ((k0 + lc * 8) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? en.A : en.B) + (int64_t)c.q * a.Kc + k0 + lc * 8);
+        if ((k0 + lc * 8) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? c.A : c.B) + (int64_t)c.q * a.Kc + k0 + lc * 8);
         *(uint4*)(xs + swz_rowk(row, lc)) = w;
       } else {
         const int lc = tid & 3, k = tid >> 2;               // 64 k-rows x 4 units
         int e = tn * SK_BX + lc * 8;
         if (e >= a.n_ext) e = a.n_ext - 8;
         const ExtCol c = a.ext_cols[e];
-        const AdapterEntry en = a.table[c.t - a.ext_t0];
         uint4 w = zero4;
+        const AdapterEntry en = a.table[c.t - a.ext_t0];
         if ((k0 + k) < kend) w = *(const uint4*)((const bf16_t*)(a.which ? en.A : en.B) + (k0 + k) * en.rank + c.q);
         *(uint4*)(xs + k * 64 + lc * 16) = w;
       }
@@ -1310,14 +1262,18 @@ static hipError_t launch_wide(const GemmArgs& a, hipStream_t stream) {
 }
 
 template <int FORM, bool OUT_F32>
-static hipError_t launch_one(const GemmArgs& a, int mode, hipStream_t stream) {
+static hipError_t launch_one(const GemmArgs& a, int mode, bool packed, hipStream_t stream) {
   static std::atomic<uint64_t> done_wide{0}, done_sk{0}, done_skx{0};
   hipError_t e0 = allow_lds((const void*)gemm_bf16_kernel<FORM, OUT_F32>, GEMM_LDS, done_wide);
   if (e0 == hipSuccess) e0 = allow_lds((const void*)gemm_skinny_kernel<FORM, false>, SK_LDS, done_sk);
   if (e0 == hipSuccess) e0 = allow_lds((const void*)gemm_skinny_kernel<FORM, true>, SK_LDS, done_skx);
   if (e0 != hipSuccess) return e0;
   const int G = a.tiles_m * a.tiles_n;
-  if (mode == 2 && a.n_ext > 0)
+  if (mode == 2 && packed) {
+    // packed weight: its fragments go straight into registers (gemm_decode.hip)
+    hipError_t ed = launch_gemm_decode(a, stream);
+    if (ed != hipSuccess) return ed;
+  } else if (mode == 2 && a.n_ext > 0)
     hipLaunchKernelGGL((gemm_skinny_kernel<FORM, true>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
   else if (mode == 2)
     hipLaunchKernelGGL((gemm_skinny_kernel<FORM, false>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
@@ -1429,7 +1385,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
-                            hipStream_t stream) {
+                            const bf16_t* Bpacked, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   if (ldb > (1 << 22)) return hipErrorInvalidValue;      // 32-bit byte offsets inside a weight tile
   GemmArgs a;
@@ -1458,8 +1414,12 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   }
   a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.ksplit = p.ksplit; a.kchunk = p.kchunk;
   a.ldp = p.ldp; a.pm = p.pm; a.partials = partials; a.chunks = chunks; a.n_chunks = n_chunks;
+  // small batch with a packed copy of the weight (and, when the shrink is fused, factors stored
+  // contraction-contiguous): the decode kernel reads the packed copy instead of Bop
+  const bool packed = Bpacked != nullptr && p.mode == 2 && (fuse == nullptr || form == FORM_NT);
+  if (packed) { a.Bop = Bpacked; a.ldb = packed_weight_ksteps(Kc); }
   if (form == FORM_NT)
-    return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, stream) : launch_one<FORM_NT, false>(a, p.mode, stream);
+    return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, packed, stream) : launch_one<FORM_NT, false>(a, p.mode, packed, stream);
   if (p.mode == 0 && wt_scratch != nullptr && wt_bytes >= gemm_wt_bytes(form, T, Kc, Nout) && gemm_wt_bytes(form, T, Kc, Nout) > 0) {
     // large batch, weight stored [Kc][Nout]: transpose it into scratch ([Nout][Kc]) and run the
     // contraction-contiguous kernel; the adapters' factors keep their storage
@@ -1470,7 +1430,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
     a.Bop = wt_scratch; a.ldb = Kc;
     return out_is_f32 ? launch_wide<FORM_NT, true, FORM_NN>(a, stream) : launch_wide<FORM_NT, false, FORM_NN>(a, stream);
   }
-  return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, stream) : launch_one<FORM_NN, false>(a, p.mode, stream);
+  return out_is_f32 ? launch_one<FORM_NN, true>(a, p.mode, packed, stream) : launch_one<FORM_NN, false>(a, p.mode, packed, stream);
 }
 
 // ---- several projections in one pass
@@ -1502,7 +1462,7 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
                                   const AdapterEntry* table, const ProjEntry* proj_host,
                                   int n_proj, int out_is_f32, float* partials,
                                   size_t partial_bytes, const RowChunk* chunks, int n_chunks,
-                                  const GemmFuse* fuse, hipStream_t stream) {
+                                  const GemmFuse* fuse, int packed, hipStream_t stream) {
   const int n_ext = fuse ? fuse->n_ext : 0;
   if (!gemm_multi_ok(form, T, Kc, proj_host, n_proj, n_ext, fuse ? fuse->ranks_mult8 : true,
                      partials ? partial_bytes : 0) || chunks == nullptr || n_proj > MAX_PROJ)
@@ -1529,9 +1489,12 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
   int fin_cols = 0;
   for (int q = 0; q < n_proj; ++q) fin_cols += (int)((proj_host[q].Nout + FIN_COLS - 1) / FIN_COLS);
   a.fin_cols = fin_cols;
+  // (packed: every ProjEntry::W is a packed copy and ProjEntry::ldw its k-steps per column block)
+  const bool pk = packed != 0 && (fuse == nullptr || form == FORM_NT);
+  if (packed != 0 && !pk) return hipErrorInvalidValue;
   if (form == FORM_NT)
-    return out_is_f32 ? launch_one<FORM_NT, true>(a, 2, stream) : launch_one<FORM_NT, false>(a, 2, stream);
-  return out_is_f32 ? launch_one<FORM_NN, true>(a, 2, stream) : launch_one<FORM_NN, false>(a, 2, stream);
+    return out_is_f32 ? launch_one<FORM_NT, true>(a, 2, pk, stream) : launch_one<FORM_NT, false>(a, 2, pk, stream);
+  return out_is_f32 ? launch_one<FORM_NN, true>(a, 2, pk, stream) : launch_one<FORM_NN, false>(a, 2, pk, stream);
 }
 
 }  // namespace marlaas

@@ -71,10 +71,11 @@ __global__ __launch_bounds__(DERIVE_THREADS) void derive_kernel(DevTables d, int
   }
   int32_t run = part[tid] - sum;
   for (int i = lo; i < hi; ++i) {
-    const int r = d.entries[i].rank;
+    const AdapterEntry en = d.entries[i];
+    const int r = en.rank;
     d.roff[i] = run;
     for (int q = 0; q < r; ++q)
-      if (run + q < d.ext_cap) { ExtCol c; c.t = i; c.q = q; d.cols[run + q] = c; }
+      if (run + q < d.ext_cap) { ExtCol c; c.A = en.A; c.B = en.B; c.t = i; c.q = q; d.cols[run + q] = c; }
     run += r;
   }
   if (tid == DERIVE_THREADS - 1) d.roff[P] = part[tid];

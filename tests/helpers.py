@@ -26,7 +26,7 @@ class HipLayer:
     adapters (and their gradient buffers) are registered in an adapter table object and the
     descriptor refers to it; otherwise the descriptor carries the host pointer lists."""
 
-    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None, table=False):
+    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None, table=False, packed=False):
         self.w = w
         self.ctx = ctx or api.marlaas_create(0)
         self.x, self.W = to_dev(w["x"]), to_dev(w["W"])
@@ -38,6 +38,11 @@ class HipLayer:
         self.map = api.marlaas_segmap_build(self.ctx, self.ids, self.n)
         self.table = None
         self.gA = self.gB = None
+        self.Wp_fwd = self.Wp_bwd = None
+        if packed and w["dtype"] == "bf16":          # packed copies of the frozen weight (small batches read them)
+            self.Wp_fwd = api.marlaas_pack_weight(self.ctx, self.W, w["layout"], 0)
+            if want_bwd:
+                self.Wp_bwd = api.marlaas_pack_weight(self.ctx, self.W, w["layout"], 1)
         if table and self.n > 0:
             self.table = api.marlaas_adapter_table_create(self.ctx, self.n, 1, int(max(w["ranks"])))
             if want_bwd:
@@ -48,10 +53,10 @@ class HipLayer:
                                                  float(w["scales"][t]), self.gA[t] if want_bwd else None,
                                                  self.gB[t] if want_bwd else None)
             self.desc = api.LoraDesc(self.x, self.W, None, None, None, None, self.map, layout=w["layout"],
-                                     out_dtype=out_dtype, table=self.table)
+                                     out_dtype=out_dtype, table=self.table, W_packed_fwd=self.Wp_fwd, W_packed_bwd=self.Wp_bwd)
         else:
             self.desc = api.LoraDesc(self.x, self.W, self.A, self.B, w["ranks"], w["scales"], self.map,
-                                     layout=w["layout"], out_dtype=out_dtype)
+                                     layout=w["layout"], out_dtype=out_dtype, W_packed_fwd=self.Wp_fwd, W_packed_bwd=self.Wp_bwd)
         self.out_dtype = out_dtype
         nbytes = api.marlaas_workspace_bytes(self.desc, want_bwd)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")

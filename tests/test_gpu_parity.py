@@ -23,9 +23,10 @@ def _oracle_all(oracle, w, bwd):
     return y, dX, dA, dB
 
 
-@pytest.fixture(params=[False, True], ids=["lists", "table"])
+@pytest.fixture(params=["lists", "table", "table+packed", "lists+packed"])
 def use_table(request):
-    """Adapters given as host pointer lists in the descriptor, or registered in an adapter table object."""
+    """Adapters given as host pointer lists in the descriptor, or registered in an adapter table object;
+    with or without packed copies of the weight (which small batches then read)."""
     return request.param
 
 
@@ -52,7 +53,7 @@ def check_u_save(oracle, w, L, u, tag=""):
 
 def _check_layer(oracle, w, bwd, out_dtype=torch.float32, tol=(1e-2, 1e-3), tag="", table=False):
     y_ref, dX_ref, dA_ref, dB_ref = _oracle_all(oracle, w, bwd)
-    L = HipLayer(w, out_dtype=out_dtype, want_bwd=bwd, table=table)
+    L = HipLayer(w, out_dtype=out_dtype, want_bwd=bwd, table=str(table).startswith("table"), packed=str(table).endswith("packed"))
     y, u = L.fwd(save_u=bwd)
     stats = {"y": assert_close(to_host(y), y_ref, tag + " y", *tol)}
     if bwd:
@@ -128,7 +129,7 @@ def test_config1_full(oracle, layout, seed, use_table):
 def test_config1_full_saves_u(oracle, layout, use_table):
     """The decode configuration with u_save requested: the fused shrink writes it from the finish kernel."""
     w = wl.make_config(1, seed=0, layout=layout)
-    L = HipLayer(w, table=use_table)
+    L = HipLayer(w, table=use_table.startswith("table"), packed=use_table.endswith("packed"))
     y, u = L.fwd(save_u=True)
     check_u_save(oracle, w, L, u, "cfg1")
 

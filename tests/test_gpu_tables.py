@@ -297,3 +297,32 @@ def test_segmap_object_is_reused_across_batches():
     api.marlaas_segmap_update(ctx, m, torch.tensor([1, 0, 1], dtype=torch.int32, device="cuda"), 2)
     perm, seg_off = api.marlaas_segmap_export(m)
     assert perm.tolist() == [1, 0, 2] and seg_off.tolist() == [0, 1, 3, 3]
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("direction", [0, 1])
+def test_packed_weight_is_a_permutation_of_the_weight(layout, direction):
+    """marlaas_pack_weight against the definition of the packed order, bit for bit: 1 KB blocks of
+    16 output columns x 32 contraction values, lane (lg, li) of a block holding the 8 values
+    k = 32 ks + 8 lg .. + 7 of column 16 nb + li, zeros beyond the matrix (sizes that leave partial
+    blocks in both directions, padded leading dimension)."""
+    rng = np.random.default_rng(17 + layout + 2 * direction)
+    d_in, d_out, pad = 200, 136, 8
+    shape = (d_in, d_out) if layout == 0 else (d_out, d_in)
+    bits = rng.integers(0, 1 << 16, size=(shape[0], shape[1] + pad), dtype=np.uint16)
+    Wbuf = to_dev(bits)
+    W = Wbuf[:, :shape[1]]
+    ctx = api.marlaas_create(0)
+    packed = api.marlaas_pack_weight(ctx, W, layout, direction)
+    torch.cuda.synchronize()
+    got = packed.cpu().numpy().view(np.uint16)
+    M = bits[:, :shape[1]] if layout == 0 else bits[:, :shape[1]].T          # [d_in, d_out]
+    CO = M if direction == 0 else M.T                                          # [contraction, output]
+    C, O = CO.shape
+    nb, ks = (O + 15) // 16, (C + 31) // 32
+    assert got.size == nb * ks * 512 == api.marlaas_packed_weight_bytes(d_in, d_out, direction) // 2
+    padded = np.zeros((ks * 32, nb * 16), np.uint16)
+    padded[:C, :O] = CO
+    # [ks, lg, e, nb, li] -> [nb, ks, lg, li, e]
+    want = padded.reshape(ks, 4, 8, nb, 16).transpose(3, 0, 1, 4, 2).reshape(-1)
+    assert np.array_equal(got, want)
