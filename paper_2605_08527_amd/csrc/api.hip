@@ -9,6 +9,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -22,6 +23,10 @@ struct marlaas_ctx {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   void* static_ws = nullptr;     // device address of this GPU's static scratch array
+  int32_t* sync_dev = nullptr;   // counters of the decode kernel (zero between launches)
+  int cu_count = 0;
+  int spin_limit = 1 << 20;
+  int decode_finish = 0;       // 1: the decode kernel completes the call itself where it can; 0: always the finish kernel
   std::string err;
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
@@ -36,6 +41,7 @@ struct marlaas_segmap {
   int32_t n = 0;
   bool built = false;
   int32_t* perm_dev = nullptr;      // [T_cap] grouped order (always built)
+  int32_t* grp_dev = nullptr;       // [T_cap] adapter of every grouped row (-1: none)
   int32_t* seg_off_dev = nullptr;   // [n_cap + 2]
   int32_t* block_hist = nullptr;    // counting-sort scratch
   int32_t* flags_dev = nullptr;     // [2]
@@ -156,6 +162,20 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   if (!ctx) return MARLAAS_ENOMEM;
   ctx->device = device;
   ctx->static_ws = sp;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->cu_count = prop.multiProcessorCount;
+  if (hipMalloc((void**)&ctx->sync_dev, DECODE_SYNC_INTS * sizeof(int32_t)) != hipSuccess ||
+      hipMemset(ctx->sync_dev, 0, DECODE_SYNC_INTS * sizeof(int32_t)) != hipSuccess) {
+    (void)hipFree(ctx->sync_dev);
+    delete ctx;
+    return MARLAAS_ENOMEM;
+  }
+  // MARLAAS_SPIN_LIMIT: polls of the decode kernel's one bounded wait (0: never wait, always take
+  // the slow recomputation; for tests of that path)
+  if (const char* sl = getenv("MARLAAS_SPIN_LIMIT")) ctx->spin_limit = atoi(sl) < 0 ? 0 : atoi(sl);
+  // MARLAAS_DECODE_FINISH=1: the decode kernel completes the call itself where it can (one launch;
+  // measured slower than the finish kernel on MI355X, so not the default)
+  if (const char* df = getenv("MARLAAS_DECODE_FINISH")) ctx->decode_finish = atoi(df) != 0;
   *out = ctx;
   return MARLAAS_OK;
 }
@@ -195,6 +215,7 @@ extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
   if (!ctx) return;
   (void)hipSetDevice(ctx->device);
   drop_spans(ctx);
+  (void)hipFree(ctx->sync_dev);
   delete ctx;
 }
 
@@ -215,6 +236,7 @@ extern "C" int marlaas_segmap_create(marlaas_ctx* ctx, int64_t T_max, int32_t n_
   hipError_t e = hipSuccess;
   do {
     if ((e = hipMalloc((void**)&m->perm_dev, sizeof(int32_t) * (size_t)(T_max > 0 ? T_max : 1))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->grp_dev, sizeof(int32_t) * (size_t)(T_max > 0 ? T_max : 1))) != hipSuccess) break;
     if ((e = hipMalloc((void**)&m->seg_off_dev, sizeof(int32_t) * nn)) != hipSuccess) break;
     if ((e = hipMalloc((void**)&m->block_hist, sizeof(int32_t) * nb * nn)) != hipSuccess) break;
     if ((e = hipMalloc((void**)&m->flags_dev, 2 * sizeof(int32_t))) != hipSuccess) break;
@@ -245,7 +267,7 @@ extern "C" int marlaas_segmap_update(marlaas_ctx* ctx, marlaas_segmap* m, const 
     return fail(ctx, MARLAAS_EUNSUPPORTED, "segmap_update reads the segment sizes back and cannot run inside a stream capture");
   m->built = false;
   const size_t nn = (size_t)n_adapters + 2;
-  HIP_TRY(ctx, launch_segmap(token_adapter, T, n_adapters, m->perm_dev, m->seg_off_dev, m->block_hist, m->flags_dev,
+  HIP_TRY(ctx, launch_segmap(token_adapter, T, n_adapters, m->perm_dev, m->grp_dev, m->seg_off_dev, m->block_hist, m->flags_dev,
                              m->chunks_dev, st));
   HIP_TRY(ctx, hipMemcpyAsync(m->readback, m->seg_off_dev, sizeof(int32_t) * nn, hipMemcpyDeviceToHost, st));
   HIP_TRY(ctx, hipMemcpyAsync(m->readback + nn, m->flags_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
@@ -284,6 +306,7 @@ extern "C" void marlaas_segmap_destroy(marlaas_segmap* map) {
   if (!map) return;
   (void)hipSetDevice(map->device);
   (void)hipFree(map->perm_dev);
+  (void)hipFree(map->grp_dev);
   (void)hipFree(map->seg_off_dev);
   (void)hipFree(map->block_hist);
   (void)hipFree(map->flags_dev);
@@ -631,6 +654,12 @@ extern "C" int marlaas_pack_weight(marlaas_ctx* ctx, const void* W, int64_t ldw,
   return MARLAAS_OK;
 }
 
+static DecodeSync decode_sync_of(const marlaas_ctx* ctx, const marlaas_segmap* map) {
+  DecodeSync s;
+  s.counters = ctx->decode_finish ? ctx->sync_dev : nullptr; s.grp_ids = map->grp_dev; s.spin_limit = ctx->spin_limit; s.cu_count = ctx->cu_count;
+  return s;
+}
+
 // ------------------------------------------------------------------ forward
 static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64_t ldy, void* u_save, void* stream,
                     void* ws, size_t ws_bytes) {
@@ -664,6 +693,7 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
   // A_t follows W for the shrink, B_t follows W for the expand.
   const int form = d->layout == MARLAAS_LAYOUT_MATH ? FORM_NN : FORM_NT;
   const int out_f32 = d->out_dtype == MARLAAS_F32;
+  const DecodeSync dsync = decode_sync_of(ctx, map);
   if (d->in_dtype == MARLAAS_BF16) {
     // small batches: the GEMM computes the shrink itself and no shrink kernel runs
     GemmFuse fuse;
@@ -682,7 +712,7 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                   fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ws + p.wt_off) : nullptr,
-                                  p.wt_bytes, (const bf16_t*)d->W_packed_fwd, st));
+                                  p.wt_bytes, (const bf16_t*)d->W_packed_fwd, &dsync, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -760,13 +790,15 @@ static void multi_proj_host(const marlaas_lora_desc* descs, int32_t n_proj, void
 
 // Workspace of the fused multi-projection pass: partial sums, then (descriptors without a shared
 // table object) the combined tables.
-struct MultiPlan { size_t part_bytes = 0, tab_off = 0, tab_bytes = 0, total = 0; };
+struct MultiPlan { size_t part_bytes = 0, tab_off = 0, tab_bytes = 0, total = 0; int rs = 0; };
 static MultiPlan plan_multi(const marlaas_lora_desc* descs, int32_t n_proj, const ProjEntry* proj, int n_ext, bool lora) {
   MultiPlan m;
   m.part_bytes = align_up(gemm_multi_bytes(descs[0].T, descs[0].d_in, proj, n_proj, lora ? n_ext : 0), WS_ALIGN);
   m.tab_off = m.part_bytes;
   if (lora && !multi_shares_table(descs, n_proj))
     m.tab_bytes = dev_tables_bytes((int64_t)n_proj * descs[0].n_adapters, ws_ext_cap(n_ext));
+  // the largest rank of any projection: row stride of u where the decode kernel stages it
+  for (int p = 0; p < n_proj; ++p) { const int r = (int)marlaas_u_stride(&descs[p]); if (r > m.rs) m.rs = r; }
   m.total = m.tab_off + m.tab_bytes;
   return m;
 }
@@ -857,10 +889,11 @@ extern "C" int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc*
   for (int p = 0; p < n_proj; ++p) if (!descs[p].W_packed_fwd) packed = false;
   if (packed)
     for (int p = 0; p < n_proj; ++p) { proj[p].W = descs[p].W_packed_fwd; proj[p].ldw = packed_weight_ksteps(d0->d_in); }
+  const DecodeSync dsync = decode_sync_of(ctx, map);
   PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16_multi((const bf16_t*)d0->x, d0->ldx, form, d0->T, d0->d_in, perm,
                                       map->seg_off_dev, n, table, proj.data(), n_proj,
                                       d0->out_dtype == MARLAAS_F32, (float*)ctx->ws, mp.part_bytes, map->chunks_dev,
-                                      map->n_chunks, lora ? &fuse : nullptr, packed ? 1 : 0, st));
+                                      map->n_chunks, lora ? &fuse : nullptr, packed ? 1 : 0, &dsync, mp.rs, st));
   return MARLAAS_OK;
 }
 
@@ -935,6 +968,7 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
   const int out_f32 = d->out_dtype == MARLAAS_F32;
   const bool have_ws = ctx->ws && ctx->ws_bytes >= p.total;
   float* part = (have_ws && p.part_bytes) ? (float*)((char*)ctx->ws + p.part_off) : nullptr;
+  const DecodeSync dsync = decode_sync_of(ctx, map);
   if (d->in_dtype == MARLAAS_BF16) {
     const bf16_t* x = (const bf16_t*)d->x;
     const bf16_t* dy = (const bf16_t*)dY;
@@ -959,7 +993,7 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                     out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                     fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
-                                    p.wt_bytes, (const bf16_t*)d->W_packed_bwd, st));
+                                    p.wt_bytes, (const bf16_t*)d->W_packed_bwd, &dsync, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));

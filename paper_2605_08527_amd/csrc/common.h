@@ -41,6 +41,8 @@ struct ExtCol {
   const void* A;
   const void* B;
   int32_t t, q;
+  float scale;      // of entry t
+  int32_t pad;
 };
 
 // One projection of a fused multi-projection forward (small batches): its weight, its output and
@@ -113,7 +115,8 @@ struct SegmapDev {
   int32_t* seg_off;   // [n + 2]
 };
 
-hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* seg_off,
+// perm[m] = token of grouped row m, grp_ids[m] = its adapter (-1: none)
+hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* grp_ids, int32_t* seg_off,
                          int32_t* block_hist, int32_t* flags, RowChunk* chunks, hipStream_t stream);
 int segmap_blocks(int64_t T);
 // Row chunks of a grouped order with these segment offsets (n + 2 entries): how many there are.
@@ -128,6 +131,17 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, int which, int lora_form, float* u,
                               int r_stride, int64_t T_lora, hipStream_t stream);
+
+// What lets the decode kernel finish a call by itself (no finish kernel): zeroed device counters
+// that stay zero between launches, the adapter of every grouped row, and the bounds that make its
+// one wait safe.  counters == nullptr: not available.
+struct DecodeSync {
+  int32_t* counters = nullptr;   // at least DECODE_SYNC_INTS
+  const int32_t* grp_ids = nullptr;
+  int spin_limit = 0;
+  int cu_count = 0;
+};
+static constexpr int DECODE_SYNC_INTS = 4096;
 
 struct GemmFuse {
   const ExtCol* cols;      // [n_ext] device
@@ -148,7 +162,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
-                            const bf16_t* Bpacked, hipStream_t stream);
+                            const bf16_t* Bpacked, const DecodeSync* sync, hipStream_t stream);
 // (Bpacked: optional packed copy of Bop for this contraction, used by small batches; with it the
 // shrink is only fused when the adapters' factors are stored contraction-contiguous, which the
 // caller says by passing fuse only then.)
@@ -166,7 +180,8 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
                                   const AdapterEntry* table, const ProjEntry* proj_host,
                                   int n_proj, int out_is_f32, float* partials,
                                   size_t partial_bytes, const RowChunk* chunks, int n_chunks,
-                                  const GemmFuse* fuse, int packed, hipStream_t stream);
+                                  const GemmFuse* fuse, int packed, const DecodeSync* sync, int r_stride,
+                                  hipStream_t stream);
 // Packed copy of a [contraction C, output O] operand for the decode kernel, in MFMA fragment order
 // (16 output columns x 32 contraction values per kilobyte, zero beyond the matrix).  Element (c, o)
 // of the source is at src[c * sc + o * so].

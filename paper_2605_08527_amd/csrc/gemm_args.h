@@ -38,6 +38,16 @@ struct GemmArgs {
   // tn; `table`, `ext_roff` and ExtCol::t then index [projection][adapter].
   int n_proj;
   int fin_cols;                 // column chunks of the finish kernel's grid, all projections
+  // Decode kernel that finishes the call itself (fin_in_kernel = 1: no finish kernel runs; the
+  // partial sums are then in accumulator order, [split][tile][unit][column block][lane] x 4).
+  //   sync    : device counters, all zero between launches: per tile the splits whose partial
+  //             sums are performed, then per tile the splits that are through with it; then per
+  //             row tile the workgroups whose partial u is performed and those through with u
+  //   grp_ids : adapter of every grouped row (-1: none)
+  //   spin_limit: polls of the kernel's one bounded wait
+  int fin_in_kernel, out_is_f32, lform, spin_limit;
+  int32_t* sync;
+  const int32_t* grp_ids;
   ProjEntry proj[MAX_PROJ];     // by value: read with wave-uniform loads from the kernel arguments
 };
 

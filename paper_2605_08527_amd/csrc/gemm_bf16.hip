@@ -1280,7 +1280,7 @@ static hipError_t launch_one(const GemmArgs& a, int mode, bool packed, hipStream
   else
     hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32>), dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || mode == 0) return e;
+  if (e != hipSuccess || mode == 0 || (packed && a.fin_in_kernel)) return e;
   const int64_t fin_blocks = (int64_t)a.fin_cols * a.n_chunks;
   hipLaunchKernelGGL((splitk_finish_kernel<FORM, OUT_F32>), dim3((unsigned)fin_blocks), dim3(FIN_THREADS), 0, stream, a);
   return hipGetLastError();
@@ -1379,13 +1379,25 @@ bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_e
   return p.mode == 2 && p.u_bytes > 0 && partial_bytes >= p.bytes + p.u_bytes;
 }
 
+// The decode kernel finishes the call itself (no finish kernel) when its counters exist, the
+// splits divide a tile's 32 units, and every workgroup of the launch fits on the chip at once, so
+// that the splits of a tile normally run at the same time (a split that does not see the others
+// in time leaves its share to the last one: correct either way, only slower).
+static bool decode_finishes_in_kernel(const DecodeSync* sync, int n_adapters, int r_stride, int tiles_m, int tiles_n, int ksplit) {
+  if (!sync || !sync->counters || (n_adapters > 0 && !sync->grp_ids)) return false;
+  if (n_adapters > 0 && r_stride > 128) return false;      // u of a tile's rows is staged in LDS
+  if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8) return false;
+  const int64_t tiles = (int64_t)tiles_m * tiles_n;
+  return tiles * ksplit <= sync->cu_count && 2 * tiles + 2 * tiles_m <= DECODE_SYNC_INTS;
+}
+
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
                             int form, int64_t T, int64_t Kc, int64_t Nout, const int32_t* perm,
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
                             int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
-                            const bf16_t* Bpacked, hipStream_t stream) {
+                            const bf16_t* Bpacked, const DecodeSync* sync, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   if (ldb > (1 << 22)) return hipErrorInvalidValue;      // 32-bit byte offsets inside a weight tile
   GemmArgs a;
@@ -1397,6 +1409,8 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   a.ext_t0 = 0; a.ext_base = 0;
   memset(a.proj, 0, sizeof a.proj);
   a.n_proj = 1; a.fin_cols = (int)((Nout + FIN_COLS - 1) / FIN_COLS);
+  a.fin_in_kernel = 0; a.out_is_f32 = out_is_f32; a.lform = form; a.spin_limit = 0;
+  a.sync = nullptr; a.grp_ids = nullptr;
   if (fuse) {
     // the caller skipped the shrink: the conditions of gemm_can_fuse_shrink() must hold
     if (!gemm_can_fuse_shrink(form, T, Kc, Nout, fuse->n_ext, fuse->ranks_mult8, partials ? partial_bytes : 0) || chunks == nullptr)
@@ -1417,7 +1431,12 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   // small batch with a packed copy of the weight (and, when the shrink is fused, factors stored
   // contraction-contiguous): the decode kernel reads the packed copy instead of Bop
   const bool packed = Bpacked != nullptr && p.mode == 2 && (fuse == nullptr || form == FORM_NT);
-  if (packed) { a.Bop = Bpacked; a.ldb = packed_weight_ksteps(Kc); }
+  if (packed) {
+    a.Bop = Bpacked; a.ldb = packed_weight_ksteps(Kc);
+    if (decode_finishes_in_kernel(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit)) {
+      a.fin_in_kernel = 1; a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit;
+    }
+  }
   if (form == FORM_NT)
     return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, packed, stream) : launch_one<FORM_NT, false>(a, p.mode, packed, stream);
   if (p.mode == 0 && wt_scratch != nullptr && wt_bytes >= gemm_wt_bytes(form, T, Kc, Nout) && gemm_wt_bytes(form, T, Kc, Nout) > 0) {
@@ -1462,7 +1481,8 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
                                   const AdapterEntry* table, const ProjEntry* proj_host,
                                   int n_proj, int out_is_f32, float* partials,
                                   size_t partial_bytes, const RowChunk* chunks, int n_chunks,
-                                  const GemmFuse* fuse, int packed, hipStream_t stream) {
+                                  const GemmFuse* fuse, int packed, const DecodeSync* sync, int r_stride,
+                                  hipStream_t stream) {
   const int n_ext = fuse ? fuse->n_ext : 0;
   if (!gemm_multi_ok(form, T, Kc, proj_host, n_proj, n_ext, fuse ? fuse->ranks_mult8 : true,
                      partials ? partial_bytes : 0) || chunks == nullptr || n_proj > MAX_PROJ)
@@ -1492,6 +1512,12 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
   // (packed: every ProjEntry::W is a packed copy and ProjEntry::ldw its k-steps per column block)
   const bool pk = packed != 0 && (fuse == nullptr || form == FORM_NT);
   if (packed != 0 && !pk) return hipErrorInvalidValue;
+  a.fin_in_kernel = 0; a.out_is_f32 = out_is_f32; a.lform = form; a.spin_limit = 0;
+  a.sync = nullptr; a.grp_ids = nullptr;
+  if (pk && decode_finishes_in_kernel(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit)) {
+    a.fin_in_kernel = 1; a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit;
+    a.r_stride = r_stride;
+  }
   if (form == FORM_NT)
     return out_is_f32 ? launch_one<FORM_NT, true>(a, 2, pk, stream) : launch_one<FORM_NT, false>(a, 2, pk, stream);
   return out_is_f32 ? launch_one<FORM_NN, true>(a, 2, pk, stream) : launch_one<FORM_NN, false>(a, 2, pk, stream);

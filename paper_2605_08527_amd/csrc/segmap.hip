@@ -80,7 +80,8 @@ __global__ __launch_bounds__(1024) void segmap_scan(int32_t* __restrict__ block_
 __global__ __launch_bounds__(SEG_THREADS) void segmap_scatter(const int32_t* __restrict__ ids,
                                                               int64_t T, int n,
                                                               const int32_t* __restrict__ block_base,
-                                                              int32_t* __restrict__ perm) {
+                                                              int32_t* __restrict__ perm,
+                                                              int32_t* __restrict__ grp_ids) {
   extern __shared__ int32_t smem[];
   int32_t* cursor = smem;              // [n + 1]
   int32_t* grp = smem + (n + 1);       // [SEG_THREADS]
@@ -102,6 +103,7 @@ __global__ __launch_bounds__(SEG_THREADS) void segmap_scatter(const int32_t* __r
       for (int j = 0; j < (int)threadIdx.x; ++j) before += (grp[j] == b);
       for (int j = threadIdx.x + 1; j < SEG_THREADS; ++j) after += (grp[j] == b);
       perm[cursor[b] + before] = (int32_t)i;
+      grp_ids[cursor[b] + before] = b < n ? b : -1;      // adapter of that grouped row
     }
     __syncthreads();  // every slot of this group has been read from cursor
     if (b >= 0 && after == 0) cursor[b] += before + 1;
@@ -144,7 +146,7 @@ int64_t segmap_chunk_bound(int64_t T, int n) { return T / ROW_CHUNK + n + 2; }
 // plain fill (a kernel, not a memset node)
 __global__ void segmap_clear_flags(int32_t* flags) { flags[threadIdx.x] = 0; }
 
-hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* seg_off,
+hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* grp_ids, int32_t* seg_off,
                          int32_t* block_hist, int32_t* flags, RowChunk* chunks, hipStream_t stream) {
   int nblk = segmap_blocks(T);
   hipLaunchKernelGGL(segmap_clear_flags, dim3(1), dim3(2), 0, stream, flags);
@@ -156,7 +158,7 @@ hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, in
                      block_hist, nblk, n, seg_off);
   if (nblk > 0) {
     hipLaunchKernelGGL(segmap_scatter, dim3(nblk), dim3(SEG_THREADS),
-                       (n + 1 + SEG_THREADS) * sizeof(int32_t), stream, ids, T, n, block_hist, perm);
+                       (n + 1 + SEG_THREADS) * sizeof(int32_t), stream, ids, T, n, block_hist, perm, grp_ids);
   }
   hipLaunchKernelGGL(segmap_chunks, dim3(1), dim3(1024), (n + 2) * sizeof(int32_t), stream, seg_off, n, chunks);
   return hipGetLastError();

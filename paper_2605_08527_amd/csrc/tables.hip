@@ -75,7 +75,7 @@ __global__ __launch_bounds__(DERIVE_THREADS) void derive_kernel(DevTables d, int
     const int r = en.rank;
     d.roff[i] = run;
     for (int q = 0; q < r; ++q)
-      if (run + q < d.ext_cap) { ExtCol c; c.A = en.A; c.B = en.B; c.t = i; c.q = q; d.cols[run + q] = c; }
+      if (run + q < d.ext_cap) { ExtCol c; c.A = en.A; c.B = en.B; c.t = i; c.q = q; c.scale = en.scale; c.pad = 0; d.cols[run + q] = c; }
     run += r;
   }
   if (tid == DERIVE_THREADS - 1) d.roff[P] = part[tid];

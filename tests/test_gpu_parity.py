@@ -23,10 +23,14 @@ def _oracle_all(oracle, w, bwd):
     return y, dX, dA, dB
 
 
-@pytest.fixture(params=["lists", "table", "table+packed", "lists+packed"])
-def use_table(request):
+@pytest.fixture(params=["lists", "table", "table+packed", "lists+packed", "table+in-kernel+packed"])
+def use_table(request, monkeypatch):
     """Adapters given as host pointer lists in the descriptor, or registered in an adapter table object;
-    with or without packed copies of the weight (which small batches then read)."""
+    with or without packed copies of the weight (which small batches then read); and, with packed
+    copies, the decode kernel finishing the call itself instead of the finish kernel
+    (MARLAAS_DECODE_FINISH=1, read when the context is created)."""
+    if "in-kernel" in request.param:
+        monkeypatch.setenv("MARLAAS_DECODE_FINISH", "1")
     return request.param
 
 

@@ -326,3 +326,51 @@ def test_packed_weight_is_a_permutation_of_the_weight(layout, direction):
     # [ks, lg, e, nb, li] -> [nb, ks, lg, li, e]
     want = padded.reshape(ks, 4, 8, nb, 16).transpose(3, 0, 1, 4, 2).reshape(-1)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("mode", ["finish-kernel", "in-kernel", "in-kernel-no-wait"])
+@pytest.mark.parametrize("table", [False, True], ids=["lists", "table"])
+def test_packed_multi_projection_and_the_in_kernel_finish(oracle, table, mode, monkeypatch):
+    """q / k / v with packed weights, then a single projection forward and backward, on the three
+    ways the decode kernel's results get finished: by the finish kernel (the default), by the
+    decode kernel itself (MARLAAS_DECODE_FINISH=1: the splits of a tile and the tiles that carry u
+    meet through counters, one bounded wait), and that with MARLAAS_SPIN_LIMIT=0, where the wait is
+    never satisfied: every split leaves its share to the last one through with the tile and u is
+    recomputed in plain fp32.  Same results within tolerance on all three."""
+    if mode != "finish-kernel":
+        monkeypatch.setenv("MARLAAS_DECODE_FINISH", "1")
+    if mode == "in-kernel-no-wait":
+        monkeypatch.setenv("MARLAAS_SPIN_LIMIT", "0")
+    rng = np.random.default_rng(23)
+    T, K, Ns = 200, 520, (384, 136, 200)
+    ranks = ((8, 16, 24, 32), (16, 16, 8, 8), (32, 8, 16, 24))
+    ids = rng.integers(-1, 4, size=T).astype(np.int32)
+    ws = _projections(151, T, K, Ns, ranks, [2.0, 0.5, 1.0, 0.25], ids, wl.TORCH)
+    ctx, seg, keep, descs, ys, wsbuf, tb = _multi_setup(ws, table)
+    packed = [api.marlaas_pack_weight(ctx, W, wl.TORCH, 0) for (W, _, _) in keep]
+    for d, pk in zip(descs, packed):
+        d.packed = (pk, None)
+        d.c.W_packed_fwd = pk.data_ptr()
+    wsbuf = torch.empty(max(api.marlaas_workspace_bytes_multi(descs), 256), dtype=torch.uint8, device="cuda")
+    api.marlaas_set_workspace(ctx, wsbuf)
+    for rep in range(2):                       # twice: the kernel's counters must be back at zero
+        for y in ys:
+            y.fill_(float("nan"))
+        api.marlaas_lora_fwd_multi(ctx, descs, ys)
+        torch.cuda.synchronize()
+        for p, (w, y) in enumerate(zip(ws, ys)):
+            assert_close(to_host(y), oracle.fwd(*_oracle_args(w), layout=wl.TORCH), "rep %d projection %d" % (rep, p))
+    # single projection, forward (torch layout) and backward (math layout: its backward factors are contraction-contiguous)
+    for layout in (wl.TORCH, wl.MATH):
+        w = _small_workload(61 + layout, layout, T=256, K=1024, N=768)
+        L = HipLayer(w, want_bwd=True, table=table, packed=True)
+        for rep in range(2):
+            y, u = L.fwd(save_u=True)
+            assert_close(to_host(y), oracle.fwd(*_oracle_args(w), layout=layout), "y")
+            dX, dA, dB = L.bwd(u_saved=u)
+            dX_ref, dA_ref, dB_ref = oracle.bwd(*_oracle_args(w), w["dY"], layout=layout)
+            dA_ref, dB_ref = oracle_grads_in_layout(dA_ref, dB_ref, layout)
+            assert_close(to_host(dX), dX_ref, "dX")
+            for t in range(L.n):
+                assert_close(to_host(dA[t]), dA_ref[t], "dA[%d]" % t)
+                assert_close(to_host(dB[t]), dB_ref[t], "dB[%d]" % t)
