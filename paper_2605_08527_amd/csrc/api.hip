@@ -26,7 +26,7 @@ struct marlaas_ctx {
   int32_t* sync_dev = nullptr;   // counters of the decode kernel (zero between launches)
   int cu_count = 0;
   int spin_limit = 1 << 20;
-  int decode_finish = 0;       // 1: the decode kernel completes the call itself where it can; 0: always the finish kernel
+  int decode_finish = DECODE_FINISH_LAUNCH;   // how the decode kernel's calls get finished (DECODE_FINISH_*)
   std::string err;
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
@@ -173,9 +173,13 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   // MARLAAS_SPIN_LIMIT: polls of the decode kernel's one bounded wait (0: never wait, always take
   // the slow recomputation; for tests of that path)
   if (const char* sl = getenv("MARLAAS_SPIN_LIMIT")) ctx->spin_limit = atoi(sl) < 0 ? 0 : atoi(sl);
-  // MARLAAS_DECODE_FINISH=1: the decode kernel completes the call itself where it can (one launch;
-  // measured slower than the finish kernel on MI355X, so not the default)
-  if (const char* df = getenv("MARLAAS_DECODE_FINISH")) ctx->decode_finish = atoi(df) != 0;
+  // MARLAAS_DECODE_FINISH: who finishes the decode kernel's calls.  2 (default): a second launch of
+  // the decode kernel's own finish; 1: the decode kernel itself, in one launch (measured slower on
+  // MI355X); 0: the generic finish kernel
+  if (const char* df = getenv("MARLAAS_DECODE_FINISH")) {
+    const int v = atoi(df);
+    ctx->decode_finish = v == 0 ? DECODE_FINISH_GENERIC : v == 1 ? DECODE_FINISH_IN_KERNEL : DECODE_FINISH_LAUNCH;
+  }
   *out = ctx;
   return MARLAAS_OK;
 }
@@ -656,7 +660,7 @@ extern "C" int marlaas_pack_weight(marlaas_ctx* ctx, const void* W, int64_t ldw,
 
 static DecodeSync decode_sync_of(const marlaas_ctx* ctx, const marlaas_segmap* map) {
   DecodeSync s;
-  s.counters = ctx->decode_finish ? ctx->sync_dev : nullptr; s.grp_ids = map->grp_dev; s.spin_limit = ctx->spin_limit; s.cu_count = ctx->cu_count;
+  s.mode = ctx->decode_finish; s.counters = ctx->sync_dev; s.grp_ids = map->grp_dev; s.spin_limit = ctx->spin_limit; s.cu_count = ctx->cu_count;
   return s;
 }
 

@@ -132,11 +132,16 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               const AdapterEntry* table, int which, int lora_form, float* u,
                               int r_stride, int64_t T_lora, hipStream_t stream);
 
-// What lets the decode kernel finish a call by itself (no finish kernel): zeroed device counters
-// that stay zero between launches, the adapter of every grouped row, and the bounds that make its
-// one wait safe.  counters == nullptr: not available.
+// How the decode kernel's call gets finished (splits added, expand added, rows rounded and
+// scattered), and what the ways other than the generic finish kernel need: the adapter of every
+// grouped row; for the in-kernel way also zeroed device counters that stay zero between launches
+// and the bounds of its one wait.
+enum { DECODE_FINISH_GENERIC = 0,    // splitk_finish_kernel on fp32 rows (any split count)
+       DECODE_FINISH_IN_KERNEL = 1,  // the decode kernel itself: one launch
+       DECODE_FINISH_LAUNCH = 2 };   // a second launch of the decode kernel's own finish
 struct DecodeSync {
-  int32_t* counters = nullptr;   // at least DECODE_SYNC_INTS
+  int mode = DECODE_FINISH_GENERIC;  // the way asked for; the launcher falls back to the generic one
+  int32_t* counters = nullptr;       // at least DECODE_SYNC_INTS
   const int32_t* grp_ids = nullptr;
   int spin_limit = 0;
   int cu_count = 0;

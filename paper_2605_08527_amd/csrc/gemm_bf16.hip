@@ -1379,16 +1379,20 @@ bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_e
   return p.mode == 2 && p.u_bytes > 0 && partial_bytes >= p.bytes + p.u_bytes;
 }
 
-// The decode kernel finishes the call itself (no finish kernel) when its counters exist, the
-// splits divide a tile's 32 units, and every workgroup of the launch fits on the chip at once, so
-// that the splits of a tile normally run at the same time (a split that does not see the others
-// in time leaves its share to the last one: correct either way, only slower).
-static bool decode_finishes_in_kernel(const DecodeSync* sync, int n_adapters, int r_stride, int tiles_m, int tiles_n, int ksplit) {
-  if (!sync || !sync->counters || (n_adapters > 0 && !sync->grp_ids)) return false;
-  if (n_adapters > 0 && r_stride > 128) return false;      // u of a tile's rows is staged in LDS
-  if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8) return false;
+// Way the decode kernel's call is finished: the one asked for where its conditions hold, else the
+// generic finish kernel.  Both other ways need the splits to divide a tile's 32 units and u of a
+// tile's rows to fit in LDS; the in-kernel one also its counters and every workgroup of the
+// launch on the chip at once, so that the splits of a tile normally run at the same time (a split
+// that does not see the others in time leaves its share to the last one: correct either way).
+static int decode_finish_mode(const DecodeSync* sync, int n_adapters, int r_stride, int tiles_m, int tiles_n, int ksplit) {
+  if (!sync || sync->mode == DECODE_FINISH_GENERIC || (n_adapters > 0 && !sync->grp_ids)) return DECODE_FINISH_GENERIC;
+  if (n_adapters > 0 && r_stride > 128) return DECODE_FINISH_GENERIC;
+  if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8) return DECODE_FINISH_GENERIC;
+  if (sync->mode == DECODE_FINISH_LAUNCH) return DECODE_FINISH_LAUNCH;
   const int64_t tiles = (int64_t)tiles_m * tiles_n;
-  return tiles * ksplit <= sync->cu_count && 2 * tiles + 2 * tiles_m <= DECODE_SYNC_INTS;
+  if (sync->counters && tiles * ksplit <= sync->cu_count && 2 * tiles + 2 * tiles_m <= DECODE_SYNC_INTS)
+    return DECODE_FINISH_IN_KERNEL;
+  return DECODE_FINISH_LAUNCH;
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, int64_t ldb,
@@ -1433,9 +1437,8 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   const bool packed = Bpacked != nullptr && p.mode == 2 && (fuse == nullptr || form == FORM_NT);
   if (packed) {
     a.Bop = Bpacked; a.ldb = packed_weight_ksteps(Kc);
-    if (decode_finishes_in_kernel(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit)) {
-      a.fin_in_kernel = 1; a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit;
-    }
+    a.fin_in_kernel = decode_finish_mode(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit);
+    if (a.fin_in_kernel) { a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit; }
   }
   if (form == FORM_NT)
     return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, packed, stream) : launch_one<FORM_NT, false>(a, p.mode, packed, stream);
@@ -1514,8 +1517,9 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
   if (packed != 0 && !pk) return hipErrorInvalidValue;
   a.fin_in_kernel = 0; a.out_is_f32 = out_is_f32; a.lform = form; a.spin_limit = 0;
   a.sync = nullptr; a.grp_ids = nullptr;
-  if (pk && decode_finishes_in_kernel(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit)) {
-    a.fin_in_kernel = 1; a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit;
+  if (pk) a.fin_in_kernel = decode_finish_mode(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit);
+  if (a.fin_in_kernel) {
+    a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit;
     a.r_stride = r_stride;
   }
   if (form == FORM_NT)

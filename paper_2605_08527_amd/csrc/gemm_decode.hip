@@ -117,7 +117,9 @@ __device__ __forceinline__ int row_shr(int old, int src) {
   return __builtin_amdgcn_update_dpp(old, src, 0x110 + N, 0xf, 0xf, false);
 }
 
-template <bool EXT>
+// PHASE 0: the products (and, with fin_in_kernel = 1, the finish); PHASE 1: only the finish, as a
+// launch of its own after a PHASE 0 launch with fin_in_kernel = 2 on the same arguments.
+template <bool EXT, int PHASE>
 __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   uint64_t* rL_s = (uint64_t*)(smem + D_RING_BYTES);       // per row of the tile: expand factor of its adapter,
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   }
   const int64_t kbeg = (int64_t)ks_idx * a.kchunk;
   const int64_t kend = (kbeg + a.kchunk) < a.Kc ? (kbeg + a.kchunk) : a.Kc;
-  const int ntile = (int)((kend - kbeg) / DK);
+  const int ntile = PHASE == 0 ? (int)((kend - kbeg) / DK) : 0;
   D_STAMP(0);
   D_STAMP_CLEAR();
 
@@ -200,14 +202,14 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   const int erow = wave * 4 + ((lane & 31) >> 3);            // extended columns: 4 rows per wave (lanes 0-31)
   uint64_t e_ptr = 0;
   int32_t e_q = 0;
-  if (EXT) {
+  if (EXT && PHASE == 0) {
     int e = tn * SK_BX + erow;
     if (e >= a.n_ext) e = a.n_ext - 1;
     const char* ce = (const char*)(a.ext_cols + e);
     asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(e_ptr) : "v"(ce + (a.which ? 0 : 8)) : "memory");
     asm volatile("global_load_dword %0, %1, off" : "=v"(e_q) : "v"(ce + 20) : "memory");
   }
-  const int n_first = (a.perm ? 2 : 0) + (has_grp ? 2 : 0) + (EXT ? 2 : 0);      // requests so far
+  const int n_first = (a.perm ? 2 : 0) + (has_grp ? 2 : 0) + (EXT && PHASE == 0 ? 2 : 0);      // requests so far
 
   // ---- weight fragments: straight from the packed weight, one contiguous kilobyte per wave and
   // instruction.  Column block cb of this wave is block n0 / 16 + 2 wn + cb of the packed copy
@@ -411,7 +413,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
 
   // ---- k tail (the last split when Kc is not a multiple of 64): one masked tile, staged through
   // registers into slot 0; every wave handles its own k-step, values beyond kend are zeros
-  if (kbeg + (int64_t)ntile * DK < kend) {
+  if (PHASE == 0 && kbeg + (int64_t)ntile * DK < kend) {
     const int64_t k0 = kbeg + (int64_t)ntile * DK;
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
     {
@@ -465,7 +467,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   // ---- add the two k-halves through LDS: wave (g, wn) keeps its indices 4 g .. 4 g + 3 and hands
   // the other four to wave (1 - g, wn), which walks the row blocks in the same rotation; the
   // extended columns all go to the g = 0 wave
-  {
+  if (PHASE == 0) {
     f32x4* red = (f32x4*)smem;
     const int partner = (1 - g) * 4 + wn;
 #pragma unroll
@@ -507,7 +509,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
 
   const int64_t ustride = a.pm * a.ldu;
   float* up0 = EXT ? a.u_part + (m0 + 32 * wn + li) * a.ldu + tn * SK_BX + 4 * lg : nullptr;   // rows 16 (2 wn + j) + li, ext columns 16 xb + 4 lg ..
-  if (!a.fin_in_kernel) {
+  if (PHASE == 0 && !a.fin_in_kernel) {
     // ---- partial sums as plain fp32 rows, [ks][pm][ldp]: splitk_finish_kernel completes the call
     float* part = a.partials + ks_idx * a.pm * a.ldp + (m0 + li) * a.ldp + pn0 + wn * 32 + 4 * lg;
 #pragma unroll
@@ -538,7 +540,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   const int64_t fstride = (int64_t)ntiles_all * (SK_BM * SK_BN);          // floats between splits
   float* pf0 = a.partials + (int64_t)tile_id * (SK_BM * SK_BN) + lane * 4; // split 0, unit 0, column block 0
   const bool carries = EXT && tn * SK_BX < a.n_ext;
-  if (a.ksplit > 1) {
+  if (PHASE == 0 && (a.ksplit > 1 || a.fin_in_kernel == 2)) {
     float* pf = pf0 + ks_idx * fstride;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -547,13 +549,14 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
       for (int cb = 0; cb < 2; ++cb) store4_agent(pf + (unit * 2 + cb) * 256, acc[i][cb]);
     }
   }
-  if (carries && g == 0) {
+  if (PHASE == 0 && carries && g == 0) {
     float* up = up0 + ks_idx * ustride;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int xb = 0; xb < 2; ++xb) store4_agent(up + (int64_t)(j * 16) * a.ldu + xb * 16, eacc[j][xb]);
   }
+  if (PHASE == 0 && a.fin_in_kernel == 2) return;          // the PHASE 1 launch finishes the call
   // while the stores travel: per 16-row block, the octets (8 consecutive ranks of one adapter's
   // factor) its rows' adapters have.  The MFMA expand needs factors stored [column][rank] with
   // ranks that are multiples of 8; other blocks (count -1) take the plain fp32 expand.  One lane
@@ -606,28 +609,33 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   const int n_sig = (a.n_ext + SK_BX - 1) / SK_BX < a.tiles_n ? (a.n_ext + SK_BX - 1) / SK_BX : a.tiles_n;
   const int u_need = n_sig * a.ksplit;
   const bool wants_u = EXT && lora_on;
-  wait_vm<0>();                          // this thread's partial sums are performed
-  __syncthreads();                       // every thread's are
-  D_STAMP(9);
-  if (tid == 0) {
-    if (a.ksplit > 1) __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (carries) __hip_atomic_fetch_add(u_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // one bounded wait for the other splits of the tile and for u
-    int ok_p = a.ksplit == 1, ok_u = !wants_u;
-    for (int it = 0; it < a.spin_limit && !(ok_p && ok_u); ++it) {
-      // (both counters are read in one round trip)
-      const int va = __hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int vu = __hip_atomic_load(u_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      ok_p = ok_p || va >= a.ksplit;
-      ok_u = ok_u || vu >= u_need;
-      if (!(ok_p && ok_u)) __builtin_amdgcn_s_sleep(2);
+  bool gave_up = false, u_ok = true;
+  if (PHASE == 0) {
+    wait_vm<0>();                        // this thread's partial sums are performed
+    __syncthreads();                     // every thread's are
+    D_STAMP(9);
+    if (tid == 0) {
+      if (a.ksplit > 1) __hip_atomic_fetch_add(arrive, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (carries) __hip_atomic_fetch_add(u_ready, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // one bounded wait for the other splits of the tile and for u
+      int ok_p = a.ksplit == 1, ok_u = !wants_u;
+      for (int it = 0; it < a.spin_limit && !(ok_p && ok_u); ++it) {
+        // (both counters are read in one round trip)
+        const int va = __hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int vu = __hip_atomic_load(u_ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok_p = ok_p || va >= a.ksplit;
+        ok_u = ok_u || vu >= u_need;
+        if (!(ok_p && ok_u)) __builtin_amdgcn_s_sleep(2);
+      }
+      flag_s[0] = ok_p; flag_s[1] = ok_u;
     }
-    flag_s[0] = ok_p; flag_s[1] = ok_u;
+    __syncthreads();
+    D_STAMP(7);
+    gave_up = flag_s[0] == 0;
+    u_ok = flag_s[1] != 0;
+  } else {
+    __syncthreads();                     // the octet lists are complete
   }
-  __syncthreads();
-  D_STAMP(7);
-  const bool gave_up = flag_s[0] == 0;
-  const bool u_ok = flag_s[1] != 0;
   const int rs = a.r_stride;
   float* u_s = (float*)smem;             // [128][rs], rows of the tile (the ring is free)
   const int per = 32 / a.ksplit;         // units of a share (the host allows ksplit 1, 2, 4, 8 here)
@@ -733,7 +741,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   auto finish_share = [&](int share) {
     const int u0 = share * per;
     const int r0 = (u0 >> 2) * 16, nrows = per >= 4 ? per * 4 : 16;
-    const bool from_regs = a.ksplit == 1;            // the only split: the sums are this wave's accumulators
+    const bool from_regs = PHASE == 0 && a.ksplit == 1;   // the only split: the sums are this wave's accumulators
     const int rounds = from_regs ? 4 : (per + 7) >> 3;
 #pragma unroll 1
     for (int it = 0; it < rounds; ++it) {
@@ -826,7 +834,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
   for (int pass = 0; pass < 2; ++pass) {
     int todo = gave_up ? 0 : 1 << ks_idx;
     if (pass == 1) {
-      if (a.ksplit == 1) break;
+      if (PHASE == 1 || a.ksplit == 1) break;
       if (tid == 0) {
         const int old = __hip_atomic_fetch_add(done, 1 + (gave_up ? 256 << ks_idx : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // a split that did its share and is not asked to do more is through with u as well: both
@@ -850,7 +858,7 @@ __global__ __launch_bounds__(D_THREADS) void gemm_decode_kernel(GemmArgs a) {
       if ((todo >> share) & 1) finish_share(share);
     if (pass == 0) D_STAMP(8);
   }
-  if (EXT) {
+  if (EXT && PHASE == 0) {
     // the last workgroup of the row tile through with u clears its two counters
     if (tid == 0) {
       const int old = u_old >= 0 ? u_old : __hip_atomic_fetch_add(u_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -911,19 +919,20 @@ static hipError_t allow_lds_once(const void* kernel, int bytes, std::atomic<uint
   return e;
 }
 
-hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t stream) {
-  static std::atomic<uint64_t> done0{0}, done1{0};
+template <bool EXT, int PHASE>
+static hipError_t launch_phase(const GemmArgs& a, hipStream_t stream) {
+  static std::atomic<uint64_t> done{0};
+  hipError_t e = allow_lds_once((const void*)gemm_decode_kernel<EXT, PHASE>, D_LDS, done);
+  if (e != hipSuccess) return e;
   const int G = a.tiles_m * a.tiles_n * a.ksplit;
-  if (a.n_ext > 0) {
-    hipError_t e = allow_lds_once((const void*)gemm_decode_kernel<true>, D_LDS, done1);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_decode_kernel<true>), dim3(G), dim3(D_THREADS), D_LDS, stream, a);
-  } else {
-    hipError_t e = allow_lds_once((const void*)gemm_decode_kernel<false>, D_LDS, done0);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_decode_kernel<false>), dim3(G), dim3(D_THREADS), D_LDS, stream, a);
-  }
+  hipLaunchKernelGGL((gemm_decode_kernel<EXT, PHASE>), dim3(G), dim3(D_THREADS), D_LDS, stream, a);
   return hipGetLastError();
+}
+
+hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t stream) {
+  hipError_t e = a.n_ext > 0 ? launch_phase<true, 0>(a, stream) : launch_phase<false, 0>(a, stream);
+  if (e != hipSuccess || a.fin_in_kernel != 2) return e;
+  return a.n_ext > 0 ? launch_phase<true, 1>(a, stream) : launch_phase<false, 1>(a, stream);
 }
 
 }  // namespace marlaas

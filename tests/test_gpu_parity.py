@@ -23,14 +23,16 @@ def _oracle_all(oracle, w, bwd):
     return y, dX, dA, dB
 
 
-@pytest.fixture(params=["lists", "table", "table+packed", "lists+packed", "table+in-kernel+packed"])
+@pytest.fixture(params=["lists", "table", "table+packed", "lists+packed", "table+in-kernel+packed", "table+generic+packed"])
 def use_table(request, monkeypatch):
     """Adapters given as host pointer lists in the descriptor, or registered in an adapter table object;
     with or without packed copies of the weight (which small batches then read); and, with packed
-    copies, the decode kernel finishing the call itself instead of the finish kernel
-    (MARLAAS_DECODE_FINISH=1, read when the context is created)."""
+    copies, the other two ways of finishing the decode kernel's call: by the kernel itself and by
+    the generic finish kernel (MARLAAS_DECODE_FINISH=1 / 0, read when the context is created)."""
     if "in-kernel" in request.param:
         monkeypatch.setenv("MARLAAS_DECODE_FINISH", "1")
+    if "generic" in request.param:
+        monkeypatch.setenv("MARLAAS_DECODE_FINISH", "0")
     return request.param
 
 

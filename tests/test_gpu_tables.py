@@ -328,16 +328,19 @@ def test_packed_weight_is_a_permutation_of_the_weight(layout, direction):
     assert np.array_equal(got, want)
 
 
-@pytest.mark.parametrize("mode", ["finish-kernel", "in-kernel", "in-kernel-no-wait"])
+@pytest.mark.parametrize("mode", ["finish-launch", "generic-finish", "in-kernel", "in-kernel-no-wait"])
 @pytest.mark.parametrize("table", [False, True], ids=["lists", "table"])
-def test_packed_multi_projection_and_the_in_kernel_finish(oracle, table, mode, monkeypatch):
-    """q / k / v with packed weights, then a single projection forward and backward, on the three
-    ways the decode kernel's results get finished: by the finish kernel (the default), by the
-    decode kernel itself (MARLAAS_DECODE_FINISH=1: the splits of a tile and the tiles that carry u
-    meet through counters, one bounded wait), and that with MARLAAS_SPIN_LIMIT=0, where the wait is
-    never satisfied: every split leaves its share to the last one through with the tile and u is
-    recomputed in plain fp32.  Same results within tolerance on all three."""
-    if mode != "finish-kernel":
+def test_packed_multi_projection_and_the_ways_to_finish(oracle, table, mode, monkeypatch):
+    """q / k / v with packed weights, then a single projection forward and backward, on the ways
+    the decode kernel's results get finished: by a second launch of its own finish (the default),
+    by the generic finish kernel (MARLAAS_DECODE_FINISH=0), by the decode kernel itself
+    (MARLAAS_DECODE_FINISH=1: the splits of a tile and the tiles that carry u meet through
+    counters, one bounded wait), and that with MARLAAS_SPIN_LIMIT=0, where the wait is never
+    satisfied: every split leaves its share to the last one through with the tile and u is
+    recomputed in plain fp32.  Same results within tolerance on all of them."""
+    if mode == "generic-finish":
+        monkeypatch.setenv("MARLAAS_DECODE_FINISH", "0")
+    if mode.startswith("in-kernel"):
         monkeypatch.setenv("MARLAAS_DECODE_FINISH", "1")
     if mode == "in-kernel-no-wait":
         monkeypatch.setenv("MARLAAS_SPIN_LIMIT", "0")
