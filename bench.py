@@ -69,6 +69,10 @@ def parse_args():
     ap.add_argument("--no-event-stats", action="store_true", help="skip the extra event-timed iterations (for profiles)")
     ap.add_argument("--no-packed-weight", action="store_true",
                     help="decode configuration without the packed copy of the weight (the kernels then stage W through LDS)")
+    ap.add_argument("--stack-layers", type=int, default=8,
+                    help="layers of the decode layer-stack measurement of the decode configuration (0: skip)")
+    ap.add_argument("--layer-stack-only", action="store_true",
+                    help="time only the decode layer stack and print its line (for profiles)")
     ap.add_argument("--seed", type=int, default=0)
     return ap.parse_args()
 
@@ -363,6 +367,48 @@ def multi_projection_decode(case, args, steps, warmup, torch, api):
     return out
 
 
+def layer_stack_decode(args, torch, api, wl):
+    """One decode token step through a stack of layers under one HIP graph (harness/layer_stack.py):
+    per layer q/k/v in one call, o, gate/up in one call, down; 8B-class shapes (4096, kv 1024, ffn
+    14336), the decode configuration's batch and token -> adapter map, every projection with its own
+    packed weight and rank-16 adapters.  The layers' weights (3.5 GB at 8 layers) exceed every cache,
+    so each replay streams them from HBM.  Reported: event-timed replays (median, min), the step's
+    algorithmic bytes over the median against the HBM peak."""
+    from harness.layer_stack import DecodeStack
+    sh, ranks, scales, ids = wl.config_ids(1, args.seed)
+    T, d, n = sh["T"], sh["d_in"], sh["n"]
+    d_kv, d_ff, L = 1024, 14336, args.stack_layers
+    ctx = api.marlaas_create(0)
+    stack = DecodeStack(api, torch, ctx, torch.from_numpy(ids).cuda(), T, d, d_kv, d_ff, L, ranks, scales,
+                        seed=args.seed, packed=not args.no_packed_weight)
+    graph = stack.capture()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    reps = 30
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    t0 = time.perf_counter()
+    for b, e in ev:
+        b.record()
+        graph.replay()
+        e.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / reps
+    times = sorted(b.elapsed_time(e) for b, e in ev)
+    med, mn = times[len(times) // 2], times[0]
+    finite = bool(torch.isfinite(stack.out.float()).all().item())
+    nbytes = stack.algorithmic_bytes(np.bincount(ids[ids >= 0], minlength=n) > 0)
+    return dict(workload="decode step through %d layers (q/k/v, o, gate/up, down; d=%d, kv=%d, ffn=%d), T=%d, "
+                         "%d adapters r=16 per projection, one HIP graph" % (L, d, d_kv, d_ff, T, n),
+                layers=L, library_calls_per_step=4 * L, glue_kernels_per_step=4 * L,
+                ms_per_step_median=med, ms_per_step_min=mn, ms_per_step_wall=wall_ms, ms_per_layer=med / L,
+                tokens_per_s=T / (med * 1e-3), replays_timed=reps, outputs_finite=finite,
+                weight_bytes=stack.weight_bytes(),
+                roofline=dict(bound="hbm", achieved=nbytes / (med * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                              frac=nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, traffic=None,
+                              algorithmic_bytes=nbytes, span="event-timed median of one replay of the captured step"))
+
+
 def cpu_info():
     try:
         for line in open("/proc/cpuinfo"):
@@ -435,6 +481,15 @@ def main():
                        "weight_sets_rotated": max(2, args.rotate // 2), "segmap": "prebuilt, outside the timed region"},
             "roofline": m["roofline"], "separate_calls_ms_per_step": m["separate_ms_per_step"]}))
         return
+    if args.layer_stack_only:
+        m = layer_stack_decode(args, torch, api, wl)
+        print(json.dumps({
+            "metric": METRIC, "value": m["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": m["replays_timed"],
+            "warmup": 3, "ms_per_step": m["ms_per_step_median"], "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": m["workload"], "layout": "torch", "launch": "graph", "out_dtype": "bf16"},
+            "roofline": m["roofline"], "layer_stack": m}))
+        return
     results = {}
     for cfg in cfgs:
         if cfg not in (1, 2, 3, 4):
@@ -457,6 +512,8 @@ def main():
                                                             event_stats=False)["ms_per_step"]
             if cfg == 1 and not args.no_multi_projection:
                 extra["multi_projection"] = multi_projection_decode(case, args, steps, warmup, torch, api)
+            if cfg == 1 and args.stack_layers > 0:
+                extra["layer_stack"] = layer_stack_decode(args, torch, api, wl)
             if cfg == 4:
                 # the timed steps reuse a prebuilt segment map; regrouping a batch into an existing map
                 # object (five small kernels, a read-back of the offsets and one wait) costs this much

@@ -26,7 +26,7 @@ struct marlaas_ctx {
   int32_t* sync_dev = nullptr;   // counters of the decode kernel (zero between launches)
   int cu_count = 0;
   int spin_limit = 1 << 20;
-  int decode_finish = DECODE_FINISH_LAUNCH;   // how the decode kernel's calls get finished (DECODE_FINISH_*)
+  int decode_finish = DECODE_FINISH_AUTO;     // how the decode kernel's calls get finished (DECODE_FINISH_*)
   std::string err;
   bool profile = false;
   struct Span { int kernel; hipEvent_t beg, end; };
@@ -173,12 +173,13 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   // MARLAAS_SPIN_LIMIT: polls of the decode kernel's one bounded wait (0: never wait, always take
   // the slow recomputation; for tests of that path)
   if (const char* sl = getenv("MARLAAS_SPIN_LIMIT")) ctx->spin_limit = atoi(sl) < 0 ? 0 : atoi(sl);
-  // MARLAAS_DECODE_FINISH: who finishes the decode kernel's calls.  2 (default): a second launch of
-  // the decode kernel's own finish; 1: the decode kernel itself, in one launch (measured slower on
-  // MI355X); 0: the generic finish kernel
+  // MARLAAS_DECODE_FINISH: who finishes the decode kernel's calls.  Unset or 3: the kernel itself
+  // when the contraction is not split, a second launch of its own finish when it is; 2: always
+  // that second launch; 1: always the kernel itself where its conditions hold; 0: the generic
+  // finish kernel
   if (const char* df = getenv("MARLAAS_DECODE_FINISH")) {
     const int v = atoi(df);
-    ctx->decode_finish = v == 0 ? DECODE_FINISH_GENERIC : v == 1 ? DECODE_FINISH_IN_KERNEL : DECODE_FINISH_LAUNCH;
+    ctx->decode_finish = v == 0 ? DECODE_FINISH_GENERIC : v == 1 ? DECODE_FINISH_IN_KERNEL : v == 2 ? DECODE_FINISH_LAUNCH : DECODE_FINISH_AUTO;
   }
   *out = ctx;
   return MARLAAS_OK;

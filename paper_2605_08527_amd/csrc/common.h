@@ -138,7 +138,8 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
 // and the bounds of its one wait.
 enum { DECODE_FINISH_GENERIC = 0,    // splitk_finish_kernel on fp32 rows (any split count)
        DECODE_FINISH_IN_KERNEL = 1,  // the decode kernel itself: one launch
-       DECODE_FINISH_LAUNCH = 2 };   // a second launch of the decode kernel's own finish
+       DECODE_FINISH_LAUNCH = 2,     // a second launch of the decode kernel's own finish
+       DECODE_FINISH_AUTO = 3 };     // whichever of the two is faster for the split count
 struct DecodeSync {
   int mode = DECODE_FINISH_GENERIC;  // the way asked for; the launcher falls back to the generic one
   int32_t* counters = nullptr;       // at least DECODE_SYNC_INTS

@@ -1380,17 +1380,24 @@ bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_e
 }
 
 // Way the decode kernel's call is finished: the one asked for where its conditions hold, else the
-// generic finish kernel.  Both other ways need the splits to divide a tile's 32 units and u of a
-// tile's rows to fit in LDS; the in-kernel one also its counters and every workgroup of the
-// launch on the chip at once, so that the splits of a tile normally run at the same time (a split
-// that does not see the others in time leaves its share to the last one: correct either way).
+// next best.  Both ways other than the generic finish kernel need the splits to divide a tile's
+// 32 units and u of a tile's rows to fit in LDS.  The in-kernel way also needs its counters; with
+// several splits it is only taken when every workgroup of the launch fits on the chip at once, so
+// that the splits of a tile normally run at the same time (a split that does not see the others
+// in time leaves its share to the last one: correct either way).  DECODE_FINISH_AUTO: in the
+// kernel when there is one split (the sums never leave the registers; only u crosses workgroups,
+// and the column tiles that carry it are the first to be scheduled), a launch of its own otherwise
+// (measured: the counters' round trips cost more than the second launch once 16 MB of partial
+// sums have to cross anyway).
 static int decode_finish_mode(const DecodeSync* sync, int n_adapters, int r_stride, int tiles_m, int tiles_n, int ksplit) {
   if (!sync || sync->mode == DECODE_FINISH_GENERIC || (n_adapters > 0 && !sync->grp_ids)) return DECODE_FINISH_GENERIC;
   if (n_adapters > 0 && r_stride > 128) return DECODE_FINISH_GENERIC;
   if (ksplit != 1 && ksplit != 2 && ksplit != 4 && ksplit != 8) return DECODE_FINISH_GENERIC;
-  if (sync->mode == DECODE_FINISH_LAUNCH) return DECODE_FINISH_LAUNCH;
+  int want = sync->mode;
+  if (want == DECODE_FINISH_AUTO) want = ksplit == 1 ? DECODE_FINISH_IN_KERNEL : DECODE_FINISH_LAUNCH;
+  if (want == DECODE_FINISH_LAUNCH) return DECODE_FINISH_LAUNCH;
   const int64_t tiles = (int64_t)tiles_m * tiles_n;
-  if (sync->counters && tiles * ksplit <= sync->cu_count && 2 * tiles + 2 * tiles_m <= DECODE_SYNC_INTS)
+  if (sync->counters && 2 * tiles + 2 * tiles_m <= DECODE_SYNC_INTS && (ksplit == 1 || tiles * ksplit <= sync->cu_count))
     return DECODE_FINISH_IN_KERNEL;
   return DECODE_FINISH_LAUNCH;
 }

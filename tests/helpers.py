@@ -104,3 +104,18 @@ def assert_close(got, ref, what, tol_max=TOL_MAX, tol_mean=TOL_MEAN):
     assert np.all(np.isfinite(got)), "%s has non-finite values" % what
     assert mx <= tol_max and mean <= tol_mean, "%s: max rel %.3e mean rel %.3e norm %.3e" % (what, mx, mean, nrm)
     return mx, mean
+
+
+def bf16_floor(ref):
+    """Error of the oracle's own values after rounding to bf16: (max, mean) of the metric."""
+    rounded = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
+    mx, mean, _ = wl.rel_err_stats(rounded, ref)
+    return mx, mean
+
+
+def check_bf16(got, ref, what):
+    mx, mean, _ = wl.rel_err_stats(got, ref)
+    fmx, fmean = bf16_floor(ref)
+    assert np.all(np.isfinite(got)), what
+    assert mean <= 1.05 * fmean + 2e-5 and mx <= 2.0 ** -8 * 1.01, \
+        "%s (bf16 out): max %.3e mean %.3e, rounding floor max %.3e mean %.3e" % (what, mx, mean, fmx, fmean)

@@ -16,7 +16,7 @@ import torch
 
 from paper_2605_08527_amd import api
 from harness import workloads as wl
-from helpers import HipLayer, assert_close, to_host
+from helpers import HipLayer, assert_close, check_bf16, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -34,21 +34,6 @@ def _sample_rows(ids, n_extra, seed, tile=256):
     at_edges = order[np.concatenate([edges - 1, edges])] if edges.size else np.zeros(0, np.int64)
     extra = rng.integers(0, T, size=n_extra)
     return np.unique(np.concatenate([first, last, at_edges, extra, [0, T - 1]])).astype(np.int64)
-
-
-def _bf16_floor(ref):
-    """Error of the oracle's own values after rounding to bf16: (max, mean) of the metric."""
-    rounded = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
-    mx, mean, _ = wl.rel_err_stats(rounded, ref)
-    return mx, mean
-
-
-def _check_bf16(got, ref, what):
-    mx, mean, _ = wl.rel_err_stats(got, ref)
-    fmx, fmean = _bf16_floor(ref)
-    assert np.all(np.isfinite(got)), what
-    assert mean <= 1.05 * fmean + 2e-5 and mx <= 2.0 ** -8 * 1.01, \
-        "%s (bf16 out): max %.3e mean %.3e, rounding floor max %.3e mean %.3e" % (what, mx, mean, fmx, fmean)
 
 
 @pytest.mark.parametrize("seed", [0, 1, 2])
@@ -92,10 +77,10 @@ def test_full_size(oracle, cfg, adapters, seed):
     del L
     torch.cuda.empty_cache()
     yb, ub = Lb.fwd(save_u=bwd)
-    _check_bf16(to_host(yb[rows_t]), y_ref, tag + " y")
+    check_bf16(to_host(yb[rows_t]), y_ref, tag + " y")
     if bwd:
         dXb, dAb, dBb = Lb.bwd(u_saved=ub)
-        _check_bf16(to_host(dXb[rows_t]), dX_ref, tag + " dX")
+        check_bf16(to_host(dXb[rows_t]), dX_ref, tag + " dX")
         for s, t in enumerate(adapters[:4]):
             assert_close(to_host(dAb[t]), dA_ref[s].T, tag + " dA[%d] (bf16-output pass)" % t)
             assert_close(to_host(dBb[t]), dB_ref[s].T, tag + " dB[%d] (bf16-output pass)" % t)
