@@ -40,6 +40,7 @@
  * all row-major; x[T,d_in], dY[T,d_out] row-major with leading dimensions.
  * dtype flag: 0 = bf16 bit patterns (uint16), 1 = IEEE fp32.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -246,4 +247,38 @@ int oracle_bwd(int dtype, int layout, int64_t T, int64_t K, int64_t N, int n_ada
   }
   free_list(Ad, n_adapters); free_list(Bd, n_adapters);
   return fail ? -1 : 0;
+}
+
+/*
+ * One optimizer step on the LoRA parameters of the task being trained.
+ *
+ * The manager keeps, per task, the LoRA parameters theta_t and an optimizer
+ * state phi_t, and the training engine maps (theta_t, phi_t) of version v to
+ * version v + 1 (Section 4.2; the PolicyUpdate line of Algorithm 1).  The
+ * paper does not name the optimizer.  Reading taken here: AdamW, i.e. Adam
+ * with decoupled weight decay as published by Loshchilov and Hutter
+ * ("Decoupled Weight Decay Regularization", their Algorithm 2, schedule
+ * multiplier 1), with phi_t = (first moment m, second moment v, step count):
+ *
+ *   step  = number of this update, 1 for the first
+ *   p    <- p - lr * wd * p
+ *   m    <- beta1 * m + (1 - beta1) * g
+ *   v    <- beta2 * v + (1 - beta2) * g * g
+ *   p    <- p - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *
+ * element by element, in place, in fp64.  g is the gradient the backward
+ * above produces (dA_t or dB_t).  Returns -1 on a negative size or step < 1.
+ */
+int oracle_adamw_step(int64_t n, double* p, double* m, double* v, const double* g,
+                      double lr, double beta1, double beta2, double eps, double wd, int64_t step) {
+  if (n < 0 || step < 1) return -1;
+  const double c1 = 1.0 - pow(beta1, (double)step);
+  const double c2 = 1.0 - pow(beta2, (double)step);
+  for (int64_t i = 0; i < n; ++i) {
+    p[i] -= lr * wd * p[i];
+    m[i] = beta1 * m[i] + (1.0 - beta1) * g[i];
+    v[i] = beta2 * v[i] + (1.0 - beta2) * g[i] * g[i];
+    p[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+  }
+  return 0;
 }

@@ -22,7 +22,7 @@ def build(force=False):
     """Compile lora_oracle.c with gcc (fp64, OpenMP, no BLAS)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O3", "-march=x86-64-v3", "-fopenmp", "-fPIC", "-shared", "-std=c11",
-               "-Wall", "-Wextra", "-o", _SO, _SRC]
+               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
 
@@ -35,6 +35,7 @@ def _load():
         lib.oracle_num_threads.restype = ctypes.c_int
         lib.oracle_fwd.restype = ctypes.c_int
         lib.oracle_bwd.restype = ctypes.c_int
+        lib.oracle_adamw_step.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -133,3 +134,18 @@ def bwd(x, W, A, B, ranks, scales, token_adapter, dY, layout=0, rows=None, want_
     if rc != 0:
         raise RuntimeError("oracle_bwd failed (bad token id or out of memory)")
     return dX, dA, dB
+
+
+def adamw_step(p, m, v, g, lr, beta1, beta2, eps, weight_decay, step):
+    """One AdamW step in fp64 on arrays of any (equal) shape; `step` is the number of this update
+    (1 for the first).  Returns new (p, m, v) as float64 arrays; the inputs are not modified."""
+    p2, m2, v2 = (np.array(a, dtype=np.float64, order="C", copy=True) for a in (p, m, v))
+    g2 = np.ascontiguousarray(g, dtype=np.float64)
+    assert p2.shape == m2.shape == v2.shape == g2.shape
+    rc = _load().oracle_adamw_step(
+        ctypes.c_int64(p2.size), _ptr(p2), _ptr(m2), _ptr(v2), _ptr(g2), ctypes.c_double(lr),
+        ctypes.c_double(beta1), ctypes.c_double(beta2), ctypes.c_double(eps), ctypes.c_double(weight_decay),
+        ctypes.c_int64(step))
+    if rc != 0:
+        raise RuntimeError("oracle_adamw_step failed (step must be >= 1)")
+    return p2, m2, v2
