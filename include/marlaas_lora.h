@@ -21,7 +21,7 @@
  *    leading dimensions are in elements and must keep rows 16-byte aligned;
  *    d_in and d_out must be multiples of 8.  Otherwise MARLAAS_EALIGN.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    The passes (marlaas_lora_fwd, marlaas_lora_bwd, marlaas_lora_fwd_multi,
+ *    The passes (marlaas_lora_fwd, marlaas_lora_bwd, marlaas_lora_bwd_adamw, marlaas_lora_fwd_multi,
  *    marlaas_adapter_table_update) only enqueue kernels on it and return: they
  *    allocate nothing, copy nothing from host memory, wait for nothing, and may
  *    be recorded into a HIP graph by stream capture, first call included.
@@ -280,6 +280,39 @@ int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc* descs, int
 int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, const void* dY, int64_t lddy,
                      const void* u_saved, void* dX, int64_t lddx, void* const* dA,
                      void* const* dB, int accumulate, void* stream);
+
+/*
+ * Backward with the policy update attached: the training engine's step for
+ * the task(s) being trained (paper Sec. 4.2, Alg. 1: (theta_t, phi_t) of
+ * version v becomes version v + 1; Sec. 4.5: one task is trained per update).
+ * dX as in marlaas_lora_bwd; dA_t and dB_t are not written anywhere: each
+ * gradient element is consumed where its reduction completes, by one AdamW
+ * step (Adam with decoupled weight decay; the paper names no optimizer)
+ *   p <- p - lr wd p;  m <- b1 m + (1 - b1) g;  v <- b2 v + (1 - b2) g^2;
+ *   p <- p - lr (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps)
+ * in fp32 on the task's optimizer state phi_t.
+ * states: HOST array of n_adapters entries (1 <= n_adapters <= 8, bf16 inputs;
+ * else MARLAAS_EUNSUPPORTED).  Per adapter, device pointers: fp32 master copies
+ * of A_t and B_t, first and second moments of each (all shaped like A_t / B_t,
+ * dense, same layout), and A_next / B_next: bf16 buffers that receive the
+ * factors of the next version (the master values rounded to nearest even).
+ * They may be the current A_t / B_t (update in place: every kernel that reads a
+ * factor has been enqueued before the one that overwrites it) or separate
+ * buffers to be committed with marlaas_adapter_table_update while the old
+ * version is still being served.  An adapter without tokens in the batch is
+ * left untouched (no decay, no step).  hp->step is the number of this update,
+ * 1 for the first; it and the other hyper-parameters travel in the kernel
+ * arguments, so a captured graph replays the step count it was captured with.
+ */
+typedef struct { float lr, beta1, beta2, eps, weight_decay; int32_t step; } marlaas_adamw;
+typedef struct {
+  float* master_A; float* master_B;
+  float* m_A; float* v_A; float* m_B; float* v_B;
+  void* A_next; void* B_next;
+} marlaas_adapter_state;
+int marlaas_lora_bwd_adamw(marlaas_ctx* ctx, const marlaas_lora_desc* desc, const void* dY, int64_t lddy,
+                           const void* u_saved, void* dX, int64_t lddx,
+                           const marlaas_adapter_state* states, const marlaas_adamw* hp, void* stream);
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, every kernel launch of

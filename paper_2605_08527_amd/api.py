@@ -23,12 +23,23 @@ EXPORTS = [
     "marlaas_segmap_create", "marlaas_segmap_update",
     "marlaas_adapter_table_create", "marlaas_adapter_table_destroy", "marlaas_adapter_table_update",
     "marlaas_adapter_table_version", "marlaas_adapter_table_plan_version",
-    "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd",
+    "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd", "marlaas_lora_bwd_adamw",
     "marlaas_lora_fwd_static", "marlaas_packed_weight_bytes", "marlaas_pack_weight",
     "marlaas_workspace_bytes_multi", "marlaas_lora_fwd_multi",
     "marlaas_u_stride", "marlaas_profile_enable", "marlaas_profile_read",
 ]
 MARLAAS_KERNEL_SHRINK, MARLAAS_KERNEL_GEMM, MARLAAS_KERNEL_REDUCE = 1, 2, 3
+
+
+class marlaas_adamw(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("step", ctypes.c_int32)]
+
+
+class marlaas_adapter_state(ctypes.Structure):
+    _fields_ = [("master_A", ctypes.c_void_p), ("master_B", ctypes.c_void_p), ("m_A", ctypes.c_void_p),
+                ("v_A", ctypes.c_void_p), ("m_B", ctypes.c_void_p), ("v_B", ctypes.c_void_p),
+                ("A_next", ctypes.c_void_p), ("B_next", ctypes.c_void_p)]
 
 
 class marlaas_lora_desc(ctypes.Structure):
@@ -101,6 +112,9 @@ def load():
     lib.marlaas_lora_bwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
                                      vp, vp, ctypes.c_int, vp]
     lib.marlaas_lora_bwd.restype = ctypes.c_int
+    lib.marlaas_lora_bwd_adamw.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
+                                           ctypes.POINTER(marlaas_adapter_state), ctypes.POINTER(marlaas_adamw), vp]
+    lib.marlaas_lora_bwd_adamw.restype = ctypes.c_int
     lib.marlaas_workspace_bytes_multi.argtypes = [ctypes.POINTER(marlaas_lora_desc), i32]
     lib.marlaas_workspace_bytes_multi.restype = ctypes.c_size_t
     lib.marlaas_lora_fwd_multi.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), i32, ctypes.POINTER(ctypes.c_void_p),
@@ -392,6 +406,22 @@ def marlaas_lora_bwd(ctx, desc, dY, dX=None, dA=None, dB=None, u_saved=None, acc
     lddx = (dX.stride(0) if dX.shape[0] > 0 else dX.shape[1]) if dX is not None else 0
     _check(ctx, load().marlaas_lora_bwd(ctx.handle, desc.ref, _ptr(dY), lddy, _ptr(u_saved), _ptr(dX), lddx,
                                         pa, pb, 1 if accumulate else 0, _stream_ptr(stream)))
+
+
+def marlaas_lora_bwd_adamw(ctx, desc, dY, states, hp, dX=None, u_saved=None, stream=None):
+    """states: per adapter a dict of tensors master_A, master_B, m_A, v_A, m_B, v_B (fp32) and A_next,
+    B_next (bf16); hp: dict lr, beta1, beta2, eps, weight_decay, step."""
+    n = desc.shape[3]
+    keys = [f[0] for f in marlaas_adapter_state._fields_]
+    arr = (marlaas_adapter_state * max(n, 1))()
+    for t, st in enumerate(states):
+        for k in keys:
+            setattr(arr[t], k, st[k].data_ptr())
+    h = marlaas_adamw(hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"], int(hp["step"]))
+    lddy = dY.stride(0) if dY.shape[0] > 0 else dY.shape[1]
+    lddx = (dX.stride(0) if dX.shape[0] > 0 else dX.shape[1]) if dX is not None else 0
+    _check(ctx, load().marlaas_lora_bwd_adamw(ctx.handle, desc.ref, _ptr(dY), lddy, _ptr(u_saved), _ptr(dX), lddx,
+                                              arr, ctypes.byref(h), _stream_ptr(stream)))
 
 
 def marlaas_profile_enable(ctx, on):

@@ -14,6 +14,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <cmath>
 #include <vector>
 
 using namespace marlaas;
@@ -507,8 +508,11 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   if (want_bwd) {
     p.v_off = off; off += uv;
     if (d->in_dtype == MARLAAS_BF16) {
-      const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs);
-      const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs);
+      // (few adapters: room for the reductions' sums even where one chunk covers a segment, so
+      // that a backward with the optimizer step attached can always run)
+      const bool always = d->n_adapters <= OPT_MAX_ADAPTERS;
+      const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs, always);
+      const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs, always);
       const size_t pg = gemm_splitk_bytes(d->T, d->d_out, d->d_in, n_ext);
       if (pa > part) part = pa;
       if (pb > part) part = pb;
@@ -903,17 +907,19 @@ extern "C" int marlaas_lora_fwd_multi(marlaas_ctx* ctx, const marlaas_lora_desc*
 }
 
 // ------------------------------------------------------------------ backward
-extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY, int64_t lddy,
-                                const void* u_saved, void* dX, int64_t lddx, void* const* dA,
-                                void* const* dB, int accumulate, void* stream) {
+// opt: optimizer steps in place of gradient outputs (both reductions then end in the update of the
+// factor they differentiate; opt[0] for A, opt[1] for B), or null
+static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY, int64_t lddy,
+                    const void* u_saved, void* dX, int64_t lddx, void* const* dA,
+                    void* const* dB, int accumulate, const ReduceOpt* opt, void* stream) {
   if (!ctx) return MARLAAS_EINVAL;
   int rc = check_sizes(ctx, d);
   if (rc != MARLAAS_OK) return rc;
   const bool grads_in_table = dA == MARLAAS_GRADS_IN_TABLE || dB == MARLAAS_GRADS_IN_TABLE;
   if (grads_in_table && (dA != dB || !d->table))
     return fail(ctx, MARLAAS_EINVAL, "MARLAAS_GRADS_IN_TABLE must be passed for both dA and dB, with a descriptor that has an adapter table");
-  const bool want_grads = dA != nullptr || dB != nullptr;
-  if (want_grads && (!dA || !dB)) return fail(ctx, MARLAAS_EINVAL, "dA and dB must both be given or both be null");
+  const bool want_grads = dA != nullptr || dB != nullptr || opt != nullptr;
+  if (!opt && want_grads && (!dA || !dB)) return fail(ctx, MARLAAS_EINVAL, "dA and dB must both be given or both be null");
   if (accumulate != 0 && accumulate != 1) return fail(ctx, MARLAAS_EINVAL, "accumulate must be 0 or 1");
   if ((rc = check_tensors(ctx, d)) != MARLAAS_OK) return rc;
   const int64_t esz = d->in_dtype == MARLAAS_BF16 ? 2 : 4;
@@ -931,7 +937,7 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
       if (tb->hranks[i] > 0 && !tb->hgrads[i].dA)
         return fail(ctx, MARLAAS_EINVAL, "adapter %d was registered without gradient buffers", t);
     }
-  } else if (want_grads) {
+  } else if (want_grads && !opt) {
     for (int t = 0; t < d->n_adapters; ++t)
       if (!dA[t] || !dB[t] || !aligned16(dA[t]) || !aligned16(dB[t]))
         return fail(ctx, MARLAAS_EINVAL, "gradient buffers of adapter %d are null or misaligned", t);
@@ -953,7 +959,7 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
   if (d->n_adapters > 0 && (rc = resolve_bank(ctx, d, (char*)ctx->ws + p.tab_off, p.tab_bytes, st, &bank)) != MARLAAS_OK) return rc;
   const AdapterEntry* table = bank.entries;
   const GradEntry* grads = bank.grads;
-  if (want_grads && !grads_in_table && d->n_adapters > 0) {
+  if (want_grads && !opt && !grads_in_table && d->n_adapters > 0) {
     // explicit gradient pointer lists belong to descriptors that carry their own A / B lists; the
     // per-call copy of the tables in the workspace receives them
     if (!bank.in_ws)
@@ -1001,11 +1007,12 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
                                     p.wt_bytes, (const bf16_t*)d->W_packed_bwd, &dsync, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, st));
+                                      table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[1] : nullptr, st));
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, grads, 0, da_form, v, rs, accumulate, part, part ? p.part_bytes : 0, st));
+                                      table, grads, 0, da_form, v, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[0] : nullptr, st));
     }
   } else {
+    if (opt) return fail(ctx, MARLAAS_EUNSUPPORTED, "the optimizer step is attached to the bf16 backward only");
     const float* x = (const float*)d->x;
     const float* dy = (const float*)dY;
     if (need_u)
@@ -1026,4 +1033,38 @@ extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, co
     }
   }
   return MARLAAS_OK;
+}
+
+extern "C" int marlaas_lora_bwd(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY, int64_t lddy,
+                                const void* u_saved, void* dX, int64_t lddx, void* const* dA,
+                                void* const* dB, int accumulate, void* stream) {
+  return bwd_impl(ctx, d, dY, lddy, u_saved, dX, lddx, dA, dB, accumulate, nullptr, stream);
+}
+
+extern "C" int marlaas_lora_bwd_adamw(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY, int64_t lddy,
+                                      const void* u_saved, void* dX, int64_t lddx,
+                                      const marlaas_adapter_state* states, const marlaas_adamw* hp, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!d || !states || !hp) return fail(ctx, MARLAAS_EINVAL, "descriptor, states and hyper-parameters must be given");
+  if (d->n_adapters < 1 || d->n_adapters > OPT_MAX_ADAPTERS)
+    return fail(ctx, MARLAAS_EUNSUPPORTED, "the fused optimizer step takes 1..%d adapters (one task is trained per update)", OPT_MAX_ADAPTERS);
+  if (d->in_dtype != MARLAAS_BF16) return fail(ctx, MARLAAS_EUNSUPPORTED, "the optimizer step is attached to the bf16 backward only");
+  if (hp->step < 1 || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) || !(hp->eps >= 0.f))
+    return fail(ctx, MARLAAS_EINVAL, "step must be >= 1, beta1 and beta2 in [0, 1), eps >= 0");
+  ReduceOpt opt[2];
+  for (int w = 0; w < 2; ++w) {
+    opt[w].on = 1;
+    opt[w].lr = hp->lr; opt[w].beta1 = hp->beta1; opt[w].beta2 = hp->beta2; opt[w].eps = hp->eps; opt[w].wd = hp->weight_decay;
+    opt[w].inv_c1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, (double)hp->step)));
+    opt[w].inv_c2 = (float)(1.0 / (1.0 - std::pow((double)hp->beta2, (double)hp->step)));
+    for (int t = 0; t < OPT_MAX_ADAPTERS; ++t) opt[w].f[t] = OptFactor{nullptr, nullptr, nullptr, nullptr};
+  }
+  for (int t = 0; t < d->n_adapters; ++t) {
+    const marlaas_adapter_state& s = states[t];
+    if (!s.master_A || !s.master_B || !s.m_A || !s.v_A || !s.m_B || !s.v_B || !s.A_next || !s.B_next)
+      return fail(ctx, MARLAAS_EINVAL, "state of adapter %d has a null pointer", t);
+    opt[0].f[t] = OptFactor{s.master_A, s.m_A, s.v_A, (bf16_t*)s.A_next};
+    opt[1].f[t] = OptFactor{s.master_B, s.m_B, s.v_B, (bf16_t*)s.B_next};
+  }
+  return bwd_impl(ctx, d, dY, lddy, u_saved, dX, lddx, nullptr, nullptr, 0, opt, stream);
 }

@@ -209,12 +209,22 @@ bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_e
 
 // out_t(c, q) (+)= sum_{m in seg t} X[perm[m], c] * V[m, q]
 // out_form FORM_NN: out_t[c * r_t + q]; FORM_NT: out_t[q * C + c].
+// Optimizer step applied where a gradient element is completed (AdamW; see lora_small.hip):
+// per adapter the fp32 master copy, the two moments and the bf16 output of the factor the
+// reduction produces the gradient of.  on = 0: gradients are written as usual.
+struct OptFactor { float* master; float* m; float* v; bf16_t* out; };
+static constexpr int OPT_MAX_ADAPTERS = 8;
+struct ReduceOpt {
+  int on;
+  float lr, beta1, beta2, eps, wd, inv_c1, inv_c2;   // inv_c: 1 / (1 - beta^step)
+  OptFactor f[OPT_MAX_ADAPTERS];
+};
 hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, const GradEntry* grads, int which,
                               int out_form, const float* V, int r_stride, int accumulate,
-                              float* partials, size_t partial_bytes, hipStream_t stream);
-size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int max_rank);
+                              float* partials, size_t partial_bytes, const ReduceOpt* opt, hipStream_t stream);
+size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int max_rank, bool always = false);
 
 // fp32 path (plain ALU arithmetic, any shape)
 hipError_t launch_shrink_f32(const float* X, int64_t ldx, int64_t C, const int32_t* perm,

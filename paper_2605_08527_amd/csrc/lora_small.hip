@@ -300,7 +300,9 @@ struct ReduceArgs {
   const float* V; int r_stride;
   int accumulate;
   int slabs; int tchunk; int chunks_max;   // tchunk multiple of RD_TOK
-  float* partials;                         // [adapter][chunk][C][r_stride] when chunks_max > 1
+  float* partials;                         // [adapter][chunk][C][r_stride] when to_partials
+  int to_partials;                         // 1: the chunks' sums go to `partials`, reduce_finalize_kernel completes
+  ReduceOpt opt;                           // (finalize) optimizer step on every completed gradient element
 };
 
 // LDS byte offset of 16-byte unit `unit` (of 32) of token row `tk` in the [64][256] X tile.
@@ -444,8 +446,8 @@ __global__ __launch_bounds__(RD_THREADS, NQT >= 8 ? 1 : 2) void reduce_bf16_kern
     }
   }
   // D layout: row (column c of X) = 4 * (lane / 16) + v, column (q) = lane % 16
-  float* outp = a.which ? a.grads[t].dB : a.grads[t].dA;
-  float* part = a.chunks_max > 1
+  float* outp = a.to_partials ? nullptr : (a.which ? a.grads[t].dB : a.grads[t].dA);
+  float* part = a.to_partials
       ? a.partials + ((int64_t)t * a.chunks_max + ch) * a.C * a.r_stride : nullptr;
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
@@ -466,7 +468,12 @@ __global__ __launch_bounds__(RD_THREADS, NQT >= 8 ? 1 : 2) void reduce_bf16_kern
         }
 }
 
-// out_t (+)= sum over the chunks of adapter t, in chunk order
+// out_t (+)= sum over the chunks of adapter t, in chunk order.  With an optimizer step attached
+// (a.opt.on) the completed gradient element is consumed on the spot instead: one AdamW update
+// (Adam with decoupled weight decay; the policy update of the task being trained, paper Sec. 4.2
+// and Alg. 1, whose optimizer state is kept per task) of the fp32 master value and its two
+// moments, and the bf16 value of the next version of the factor.  Adapters without tokens in the
+// batch are not trained by it and are left alone.
 template <int OFORM>
 __global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
   const int t = blockIdx.y;
@@ -481,8 +488,21 @@ __global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
   float sum = 0.f;
   for (int ch = 0; ch < nch; ++ch)
     sum += a.partials[(((int64_t)t * a.chunks_max + ch) * a.C + c) * a.r_stride + q];
+  const int64_t off = OFORM == FORM_NN ? c * r + q : (int64_t)q * a.C + c;
+  if (a.opt.on) {
+    if (len == 0) return;
+    const OptFactor f = a.opt.f[t];
+    float p = f.master[off];
+    p -= a.opt.lr * a.opt.wd * p;
+    const float m = a.opt.beta1 * f.m[off] + (1.f - a.opt.beta1) * sum;
+    const float v = a.opt.beta2 * f.v[off] + (1.f - a.opt.beta2) * sum * sum;
+    p -= a.opt.lr * (m * a.opt.inv_c1) / (sqrtf(v * a.opt.inv_c2) + a.opt.eps);
+    f.master[off] = p; f.m[off] = m; f.v[off] = v;
+    f.out[off] = float_to_bf16_bits(p);
+    return;
+  }
   float* outp = a.which ? a.grads[t].dB : a.grads[t].dA;
-  float* o = outp + (OFORM == FORM_NN ? c * r + q : (int64_t)q * a.C + c);
+  float* o = outp + off;
   *o = a.accumulate ? *o + sum : sum;
 }
 
@@ -502,10 +522,10 @@ static void reduce_plan(int64_t C, int n_adapters, int max_seg, int* tchunk, int
   }
 }
 
-size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int r_stride) {
+size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int r_stride, bool always) {
   int tc, cm;
   reduce_plan(C, n_adapters, max_seg, &tc, &cm);
-  if (cm <= 1) return 0;
+  if (cm <= 1 && !always) return 0;
   return (size_t)n_adapters * cm * C * r_stride * sizeof(float);
 }
 
@@ -513,7 +533,7 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, const GradEntry* grads, int which,
                               int out_form, const float* V, int r_stride, int accumulate,
-                              float* partials, size_t partial_bytes, hipStream_t stream) {
+                              float* partials, size_t partial_bytes, const ReduceOpt* opt, hipStream_t stream) {
   if (n_adapters <= 0) return hipSuccess;
   ReduceArgs a;
   a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
@@ -527,6 +547,16 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
     if (a.tchunk < RD_TOK) a.tchunk = RD_TOK;
   }
   a.partials = partials;
+  a.to_partials = a.chunks_max > 1;
+  a.opt.on = 0;
+  if (opt && opt->on) {
+    // the optimizer step lives in the finalize kernel: the sums always go through `partials`
+    if (n_adapters > OPT_MAX_ADAPTERS || partials == nullptr ||
+        partial_bytes < (size_t)n_adapters * a.chunks_max * C * r_stride * sizeof(float))
+      return hipErrorInvalidValue;
+    a.opt = *opt;
+    a.to_partials = 1;
+  }
   const size_t lds = (size_t)RD_TOK * RD_COLS * 2 + (size_t)2 * RD_TOK * (r_stride * 2 + 16);   // r_stride >= every r_pad
   typedef void (*rkern_t)(ReduceArgs);
   const int nq = r_stride / 16;
@@ -544,7 +574,7 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   hipLaunchKernelGGL(kern, dim3(a.slabs * a.chunks_max, n_adapters), dim3(RD_THREADS), lds, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.chunks_max > 1) {
+  if (a.to_partials) {
     auto fin = out_form == FORM_NN ? reduce_finalize_kernel<FORM_NN> : reduce_finalize_kernel<FORM_NT>;
     hipLaunchKernelGGL(fin, dim3((unsigned)((C * r_stride + 255) / 256), n_adapters), dim3(256), 0, stream, a);
     e = hipGetLastError();
