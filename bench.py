@@ -161,9 +161,12 @@ def build_case(cfg, args, torch, api, wl):
                                              case["dA"][t] if sh["bwd"] else None, case["dB"][t] if sh["bwd"] else None)
         # small batches read a packed copy of the frozen weight, written once per weight (outside the timed region)
         Wp = api.marlaas_pack_weight(ctx, W, layout, 0) if (cfg == 1 and not args.no_packed_weight) else None
+        # large batches whose contraction runs along W's strided dimension read a transposed copy kept with
+        # the frozen weight (written once, outside the timed region)
+        Wt = api.marlaas_transpose_weight(ctx, W, layout) if (cfg != 1 and (sh["bwd"] if layout else True)) else None
         desc = api.LoraDesc(x, W, None, None, None, None, segmap, layout=layout, out_dtype=torch.bfloat16, table=table,
-                            W_packed_fwd=Wp)
-        sets.append(dict(x=x, W=W, A=A, B=B, table=table, desc=desc, Wp=Wp))
+                            W_packed_fwd=Wp, W_t=Wt)
+        sets.append(dict(x=x, W=W, A=A, B=B, table=table, desc=desc, Wp=Wp, Wt=Wt))
     case["sets"] = sets
     case["y"] = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
     ws_bytes = api.marlaas_workspace_bytes(sets[0]["desc"], sh["bwd"])
@@ -593,7 +596,7 @@ def main():
         "tflops": h["tflops"], "roofline": h["roofline"],
     }
     for k in ("cpu_baseline", "event_iterations", "event_median_ms", "event_min_ms", "event_unit", "clocks",
-              "vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection", "extras_error"):
+              "vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection", "layer_stack", "extras_error"):
         if k in h:
             line[k] = h[k]
     line["others"] = [dict(results[c], workload=names[c]) for c in cfgs if c != head_cfg]

@@ -95,6 +95,12 @@ typedef struct {
    * (decode) then read the packed copy and not W.  NULL means not available. */
   const void* W_packed_fwd;
   const void* W_packed_bwd;
+  /* Optional (bf16 only): dense transposed copy of W written once by marlaas_transpose_weight
+   * (math: [d_out, d_in]; torch: [d_in, d_out]).  W is frozen for the life of the model (paper
+   * Sec. 1 principle (1)), so the large-batch product whose contraction runs along W's strided
+   * dimension (math: the forward, torch: the backward) reads this copy instead of transposing W into the
+   * workspace on every call.  NULL means not available. */
+  const void* W_t;
 } marlaas_lora_desc;
 
 /* Create a context bound to HIP device `device`.  *out is NULL on failure. */
@@ -193,6 +199,14 @@ int64_t marlaas_adapter_table_plan_version(const marlaas_adapter_table* table);
 size_t marlaas_packed_weight_bytes(int64_t d_in, int64_t d_out, int32_t direction);
 int marlaas_pack_weight(marlaas_ctx* ctx, const void* W, int64_t ldw, int64_t d_in, int64_t d_out,
                         int32_t layout, int32_t direction, void* packed, void* stream);
+
+/*
+ * Dense transposed copy of a frozen bf16 weight for the descriptor's W_t: `out` is a caller-owned
+ * device buffer of 2 * d_in * d_out bytes, written by one kernel on `stream`; it stays valid until
+ * W changes.
+ */
+int marlaas_transpose_weight(marlaas_ctx* ctx, const void* W, int64_t ldw, int64_t d_in, int64_t d_out,
+                             int32_t layout, void* out, void* stream);
 
 /*
  * Scratch memory.  The caller hands over one device buffer (e.g. a torch

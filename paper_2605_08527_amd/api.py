@@ -24,7 +24,7 @@ EXPORTS = [
     "marlaas_adapter_table_create", "marlaas_adapter_table_destroy", "marlaas_adapter_table_update",
     "marlaas_adapter_table_version", "marlaas_adapter_table_plan_version",
     "marlaas_workspace_bytes", "marlaas_set_workspace", "marlaas_lora_fwd", "marlaas_lora_bwd", "marlaas_lora_bwd_adamw",
-    "marlaas_lora_fwd_static", "marlaas_packed_weight_bytes", "marlaas_pack_weight",
+    "marlaas_lora_fwd_static", "marlaas_packed_weight_bytes", "marlaas_pack_weight", "marlaas_transpose_weight",
     "marlaas_workspace_bytes_multi", "marlaas_lora_fwd_multi",
     "marlaas_u_stride", "marlaas_profile_enable", "marlaas_profile_read",
 ]
@@ -53,7 +53,7 @@ class marlaas_lora_desc(ctypes.Structure):
         ("ranks", ctypes.POINTER(ctypes.c_int32)), ("scales", ctypes.POINTER(ctypes.c_float)),
         ("map", ctypes.c_void_p),
         ("table", ctypes.c_void_p), ("proj", ctypes.c_int32), ("reserved", ctypes.c_int32),
-        ("W_packed_fwd", ctypes.c_void_p), ("W_packed_bwd", ctypes.c_void_p),
+        ("W_packed_fwd", ctypes.c_void_p), ("W_packed_bwd", ctypes.c_void_p), ("W_t", ctypes.c_void_p),
     ]
 
 
@@ -107,6 +107,8 @@ def load():
     lib.marlaas_packed_weight_bytes.restype = ctypes.c_size_t
     lib.marlaas_pack_weight.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp]
     lib.marlaas_pack_weight.restype = ctypes.c_int
+    lib.marlaas_transpose_weight.argtypes = [vp, vp, i64, i64, i64, i32, vp, vp]
+    lib.marlaas_transpose_weight.restype = ctypes.c_int
     lib.marlaas_lora_fwd_static.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp]
     lib.marlaas_lora_fwd_static.restype = ctypes.c_int
     lib.marlaas_lora_bwd.argtypes = [vp, ctypes.POINTER(marlaas_lora_desc), vp, i64, vp, vp, i64,
@@ -296,7 +298,7 @@ class LoraDesc:
     """Owns a marlaas_lora_desc and keeps the host arrays it points to alive."""
 
     def __init__(self, x, W, A, B, ranks, scales, segmap, layout=MARLAAS_LAYOUT_MATH, out_dtype=None,
-                 table=None, proj=0, W_packed_fwd=None, W_packed_bwd=None):
+                 table=None, proj=0, W_packed_fwd=None, W_packed_bwd=None, W_t=None):
         """With `table` (an AdapterTable) the adapters come from the table's projection `proj` and
         A, B, ranks, scales are ignored (pass None).  W_packed_*: tensors written by marlaas_pack_weight."""
         if table is not None:
@@ -314,7 +316,8 @@ class LoraDesc:
         self.c.W, self.c.ldw = W.data_ptr(), W.stride(0)
         self.c.table = table.handle if table is not None else None
         self.c.proj, self.c.reserved = int(proj), 0
-        self.packed = (W_packed_fwd, W_packed_bwd)
+        self.packed = (W_packed_fwd, W_packed_bwd, W_t)
+        self.c.W_t = W_t.data_ptr() if W_t is not None else None
         self.c.W_packed_fwd = W_packed_fwd.data_ptr() if W_packed_fwd is not None else None
         self.c.W_packed_bwd = W_packed_bwd.data_ptr() if W_packed_bwd is not None else None
         self._A = (ctypes.c_void_p * max(n, 1))(*[a.data_ptr() for a in A])
@@ -367,6 +370,16 @@ def marlaas_pack_weight(ctx, W, layout, direction=0, stream=None):
     out = torch.empty(marlaas_packed_weight_bytes(d_in, d_out, direction), dtype=torch.uint8, device=W.device)
     _check(ctx, load().marlaas_pack_weight(ctx.handle, _ptr(W), W.stride(0), d_in, d_out, int(layout), int(direction),
                                            _ptr(out), _stream_ptr(stream)))
+    return out
+
+
+def marlaas_transpose_weight(ctx, W, layout, stream=None):
+    """A new bf16 CUDA tensor holding the dense transposed copy of W (for the descriptor's W_t)."""
+    assert W.dtype == torch.bfloat16 and W.is_cuda
+    d_in, d_out = (W.shape[0], W.shape[1]) if layout == MARLAAS_LAYOUT_MATH else (W.shape[1], W.shape[0])
+    out = torch.empty((W.shape[1], W.shape[0]), dtype=torch.bfloat16, device=W.device)
+    _check(ctx, load().marlaas_transpose_weight(ctx.handle, _ptr(W), W.stride(0), d_in, d_out, int(layout), _ptr(out),
+                                                _stream_ptr(stream)))
     return out
 
 

@@ -524,6 +524,7 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   if (d->in_dtype == MARLAAS_BF16) {
     size_t wt = d->layout == MARLAAS_LAYOUT_MATH ? gemm_wt_bytes(FORM_NN, d->T, d->d_in, d->d_out) : 0;
     if (want_bwd && d->layout == MARLAAS_LAYOUT_TORCH) wt = gemm_wt_bytes(FORM_NN, d->T, d->d_out, d->d_in);
+    if (d->W_t) wt = 0;                  // the caller keeps the transposed copy
     p.wt_bytes = align_up(wt, WS_ALIGN);
     p.wt_off = off; off += p.wt_bytes;
   }
@@ -554,8 +555,10 @@ static int check_tensors(marlaas_ctx* ctx, const marlaas_lora_desc* d) {
   if (d->T > 0 && !d->x) return fail(ctx, MARLAAS_EINVAL, "x is null");
   if (!d->W) return fail(ctx, MARLAAS_EINVAL, "W is null");
   if (!aligned16(d->x) || !aligned16(d->W)) return fail(ctx, MARLAAS_EALIGN, "x and W must be 16-byte aligned");
-  if (!aligned16(d->W_packed_fwd) || !aligned16(d->W_packed_bwd)) return fail(ctx, MARLAAS_EALIGN, "packed weights must be 16-byte aligned");
-  if ((d->W_packed_fwd || d->W_packed_bwd) && d->in_dtype != MARLAAS_BF16) return fail(ctx, MARLAAS_EINVAL, "packed weights exist for bf16 only");
+  if (!aligned16(d->W_packed_fwd) || !aligned16(d->W_packed_bwd) || !aligned16(d->W_t))
+    return fail(ctx, MARLAAS_EALIGN, "packed and transposed weights must be 16-byte aligned");
+  if ((d->W_packed_fwd || d->W_packed_bwd || d->W_t) && d->in_dtype != MARLAAS_BF16)
+    return fail(ctx, MARLAAS_EINVAL, "packed and transposed weights exist for bf16 only");
   if (d->ldx < d->d_in || (d->ldx * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldx=%lld", (long long)d->ldx);
   const int64_t wcols = d->layout == MARLAAS_LAYOUT_MATH ? d->d_out : d->d_in;
   if (d->ldw < wcols || (d->ldw * esz) % 16) return fail(ctx, MARLAAS_EALIGN, "ldw=%lld", (long long)d->ldw);
@@ -663,6 +666,21 @@ extern "C" int marlaas_pack_weight(marlaas_ctx* ctx, const void* W, int64_t ldw,
   return MARLAAS_OK;
 }
 
+extern "C" int marlaas_transpose_weight(marlaas_ctx* ctx, const void* W, int64_t ldw, int64_t d_in, int64_t d_out,
+                                        int32_t layout, void* out, void* stream) {
+  if (!ctx) return MARLAAS_EINVAL;
+  if (!W || !out) return fail(ctx, MARLAAS_EINVAL, "transpose_weight: null pointer");
+  if (d_in <= 0 || d_out <= 0 || d_in > (1 << 24) || d_out > (1 << 24)) return fail(ctx, MARLAAS_EINVAL, "transpose_weight: bad sizes");
+  if ((d_in & 7) || (d_out & 7)) return fail(ctx, MARLAAS_EALIGN, "d_in and d_out must be multiples of 8");
+  if (layout != MARLAAS_LAYOUT_MATH && layout != MARLAAS_LAYOUT_TORCH) return fail(ctx, MARLAAS_EINVAL, "transpose_weight: bad layout");
+  const int64_t rows = layout == MARLAAS_LAYOUT_MATH ? d_in : d_out, cols = layout == MARLAAS_LAYOUT_MATH ? d_out : d_in;
+  if (ldw < cols || (ldw & 7)) return fail(ctx, MARLAAS_EALIGN, "transpose_weight: ldw=%lld", (long long)ldw);
+  if (!aligned16(W) || !aligned16(out)) return fail(ctx, MARLAAS_EALIGN, "transpose_weight: pointers must be 16-byte aligned");
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  HIP_TRY(ctx, launch_transpose_bf16((const bf16_t*)W, ldw, (bf16_t*)out, rows, rows, cols, (hipStream_t)stream));
+  return MARLAAS_OK;
+}
+
 static DecodeSync decode_sync_of(const marlaas_ctx* ctx, const marlaas_segmap* map) {
   DecodeSync s;
   s.mode = ctx->decode_finish; s.counters = ctx->sync_dev; s.grp_ids = map->grp_dev; s.spin_limit = ctx->spin_limit; s.cu_count = ctx->cu_count;
@@ -721,7 +739,7 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                   fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ws + p.wt_off) : nullptr,
-                                  p.wt_bytes, (const bf16_t*)d->W_packed_fwd, &dsync, st));
+                                  p.wt_bytes, d->layout == MARLAAS_LAYOUT_MATH ? (const bf16_t*)d->W_t : nullptr, (const bf16_t*)d->W_packed_fwd, &dsync, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -1004,7 +1022,7 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                     out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                     fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
-                                    p.wt_bytes, (const bf16_t*)d->W_packed_bwd, &dsync, st));
+                                    p.wt_bytes, d->layout == MARLAAS_LAYOUT_TORCH ? (const bf16_t*)d->W_t : nullptr, (const bf16_t*)d->W_packed_bwd, &dsync, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[1] : nullptr, st));

@@ -167,7 +167,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
+                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes, const bf16_t* Bt_kept,
                             const bf16_t* Bpacked, const DecodeSync* sync, hipStream_t stream);
 // (Bpacked: optional packed copy of Bop for this contraction, used by small batches; with it the
 // shrink is only fused when the adapters' factors are stored contraction-contiguous, which the
@@ -199,6 +199,8 @@ hipError_t launch_pack_weight(const bf16_t* src, int64_t sc, int64_t so, int64_t
 // [contraction][output] runs faster on a [output][contraction] copy made per call (the copy
 // costs two passes over the weight, the GEMM gains about a quarter).  0: not used for these sizes.
 size_t gemm_wt_bytes(int form, int64_t T, int64_t Kc, int64_t Nout);
+// dst[c][r] = src[r][c], bf16, R x C (both multiples of 8)
+hipError_t launch_transpose_bf16(const bf16_t* src, int64_t lds, bf16_t* dst, int64_t ldd, int64_t R, int64_t C, hipStream_t stream);
 // scratch for partial sums; n_ext = sum of the adapter ranks (0: no adapters)
 size_t gemm_splitk_bytes(int64_t T, int64_t Kc, int64_t Nout, int n_ext);
 // Small batches: the GEMM can compute the shrink itself (as extra output columns over every

@@ -1236,6 +1236,13 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
   }
 }
 
+hipError_t launch_transpose_bf16(const bf16_t* src, int64_t lds, bf16_t* dst, int64_t ldd, int64_t R, int64_t C, hipStream_t stream) {
+  if (R <= 0 || C <= 0) return hipSuccess;
+  hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((C + 63) / 64), (unsigned)((R + 63) / 64)), dim3(256), 0, stream, src, lds, dst,
+                     ldd, R, C);
+  return hipGetLastError();
+}
+
 // rows of a batch from which transposing the weight into scratch pays for itself
 static constexpr int64_t WT_MIN_ROWS = 4096;
 
@@ -1407,7 +1414,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes,
+                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes, const bf16_t* Bt_kept,
                             const bf16_t* Bpacked, const DecodeSync* sync, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   if (ldb > (1 << 22)) return hipErrorInvalidValue;      // 32-bit byte offsets inside a weight tile
@@ -1449,6 +1456,11 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   }
   if (form == FORM_NT)
     return out_is_f32 ? launch_one<FORM_NT, true>(a, p.mode, packed, stream) : launch_one<FORM_NT, false>(a, p.mode, packed, stream);
+  if (p.mode == 0 && Bt_kept != nullptr) {
+    // large batch, weight stored [Kc][Nout], and the caller keeps a transposed copy of it
+    a.Bop = Bt_kept; a.ldb = Kc;
+    return out_is_f32 ? launch_wide<FORM_NT, true, FORM_NN>(a, stream) : launch_wide<FORM_NT, false, FORM_NN>(a, stream);
+  }
   if (p.mode == 0 && wt_scratch != nullptr && wt_bytes >= gemm_wt_bytes(form, T, Kc, Nout) && gemm_wt_bytes(form, T, Kc, Nout) > 0) {
     // large batch, weight stored [Kc][Nout]: transpose it into scratch ([Nout][Kc]) and run the
     // contraction-contiguous kernel; the adapters' factors keep their storage

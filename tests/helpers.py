@@ -26,7 +26,7 @@ class HipLayer:
     adapters (and their gradient buffers) are registered in an adapter table object and the
     descriptor refers to it; otherwise the descriptor carries the host pointer lists."""
 
-    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None, table=False, packed=False):
+    def __init__(self, w, out_dtype=torch.float32, want_bwd=False, ctx=None, table=False, packed=False, kept_wt=False):
         self.w = w
         self.ctx = ctx or api.marlaas_create(0)
         self.x, self.W = to_dev(w["x"]), to_dev(w["W"])
@@ -39,6 +39,9 @@ class HipLayer:
         self.table = None
         self.gA = self.gB = None
         self.Wp_fwd = self.Wp_bwd = None
+        # a transposed copy of the frozen weight kept across calls (large batches read it where the
+        # contraction runs along W's strided dimension)
+        self.W_t = api.marlaas_transpose_weight(self.ctx, self.W, w["layout"]) if (kept_wt and w["dtype"] == "bf16") else None
         if packed and w["dtype"] == "bf16":          # packed copies of the frozen weight (small batches read them)
             self.Wp_fwd = api.marlaas_pack_weight(self.ctx, self.W, w["layout"], 0)
             if want_bwd:
@@ -53,10 +56,10 @@ class HipLayer:
                                                  float(w["scales"][t]), self.gA[t] if want_bwd else None,
                                                  self.gB[t] if want_bwd else None)
             self.desc = api.LoraDesc(self.x, self.W, None, None, None, None, self.map, layout=w["layout"],
-                                     out_dtype=out_dtype, table=self.table, W_packed_fwd=self.Wp_fwd, W_packed_bwd=self.Wp_bwd)
+                                     out_dtype=out_dtype, table=self.table, W_packed_fwd=self.Wp_fwd, W_packed_bwd=self.Wp_bwd, W_t=self.W_t)
         else:
             self.desc = api.LoraDesc(self.x, self.W, self.A, self.B, w["ranks"], w["scales"], self.map,
-                                     layout=w["layout"], out_dtype=out_dtype, W_packed_fwd=self.Wp_fwd, W_packed_bwd=self.Wp_bwd)
+                                     layout=w["layout"], out_dtype=out_dtype, W_packed_fwd=self.Wp_fwd, W_packed_bwd=self.Wp_bwd, W_t=self.W_t)
         self.out_dtype = out_dtype
         nbytes = api.marlaas_workspace_bytes(self.desc, want_bwd)
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")

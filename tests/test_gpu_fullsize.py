@@ -49,7 +49,7 @@ def test_full_size(oracle, cfg, adapters, seed):
     if bwd:
         dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=w["layout"], rows=rows, adapters=adapters)
     # ---- gate: fp32 outputs
-    L = HipLayer(w, out_dtype=torch.float32, want_bwd=bwd, table=True)
+    L = HipLayer(w, out_dtype=torch.float32, want_bwd=bwd, table=True, kept_wt=(seed == 1))
     y, u = L.fwd(save_u=True)
     tag = "cfg%d seed%d" % (cfg, seed)
     assert_close(to_host(y[rows_t]), y_ref, tag + " y")
@@ -86,17 +86,23 @@ def test_full_size(oracle, cfg, adapters, seed):
             assert_close(to_host(dBb[t]), dB_ref[s].T, tag + " dB[%d] (bf16-output pass)" % t)
 
 
+@pytest.mark.parametrize("kept_wt", [False, True], ids=["transpose-per-call", "kept-transpose"])
 @pytest.mark.parametrize("layout", [wl.MATH, wl.TORCH])
-def test_partial_last_round_of_tiles(oracle, layout):
+def test_partial_last_round_of_tiles(oracle, layout, kept_wt):
     """17 x 16 = 272 tiles of 256 x 256: one more than a full round of workgroups, the last row
     tile holding the end of the grouped order (the last adapters and the rows without an
-    adapter).  Forward and backward, both layouts (one of which transposes the weight into
-    scratch at this size), fp32 outputs, sampled rows."""
+    adapter).  Forward and backward, both layouts (one product of each reads the weight along its
+    strided dimension: from a copy transposed into scratch by the call, or from the transposed
+    copy the descriptor carries), fp32 outputs, sampled rows."""
     rng = np.random.default_rng(31)
     T, K, N, ranks = 4352, 1024, 4096, [16, 8, 32, 16, 24, 16]
     ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
     w = wl.make_layer(23, T, K, N, ranks, [2.0, 1.0, 0.5, 2.0, 1.0, 0.5], ids, dtype="bf16", layout=layout, want_dY=True)
-    L = HipLayer(w, out_dtype=torch.float32, want_bwd=True)
+    L = HipLayer(w, out_dtype=torch.float32, want_bwd=True, kept_wt=kept_wt)
+    if kept_wt:      # the copy is the transpose, bit for bit, and the workspace no longer holds one
+        assert torch.equal(L.W_t, L.W.t().contiguous())
+        need, without = api.marlaas_workspace_bytes(L.desc, True), api.marlaas_workspace_bytes(HipLayer(w, want_bwd=True).desc, True)
+        assert need < without if layout == wl.MATH else need <= without     # (torch layout: this backward is planned with a split contraction)
     rows = _sample_rows(ids, 64, 7)
     rows_t = torch.from_numpy(rows).cuda()
     args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
