@@ -231,10 +231,8 @@ int marlaas_set_workspace(marlaas_ctx* ctx, void* dev_ptr, size_t bytes);
  * u_save (nullable): device fp32 [T, marlaas_u_stride(desc)]; receives
  * s_t (x A_t) per token in the grouped order of the map, for reuse by
  * marlaas_lora_bwd (its content is otherwise opaque).
- * Results do not depend on timing, with one exception: when few tokens carry
- * adapters and the shrink runs as its own kernel, its contraction is split
- * over workgroups and summed with fp32 atomics, so u (and what depends on it)
- * can differ in the last bits between runs.
+ * Results do not depend on timing: every sum that is split over workgroups is
+ * added up in a fixed order.
  */
 int marlaas_lora_fwd(marlaas_ctx* ctx, const marlaas_lora_desc* desc, void* y, int64_t ldy,
                      void* u_save, void* stream);

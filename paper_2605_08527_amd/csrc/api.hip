@@ -492,6 +492,7 @@ static int64_t ws_ext_cap(int64_t n_ext) { return n_ext < EXT_CAP_MAX ? n_ext : 
 
 struct WsPlan {
   size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;   // part: reused by every kernel with partial sums
+  size_t u2_off = 0, v2_off = 0, uv2_bytes = 0;   // two-term bf16 splits of u and v, [T][2 r_stride] (bf16 inputs)
   size_t wt_off = 0, wt_bytes = 0;   // transposed copy of the weight (large batches, output-contiguous storage)
   size_t tab_off = 0, tab_bytes = 0; // per-call copy of the adapter tables (descriptors without a table object)
 };
@@ -502,12 +503,21 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   const size_t uv = align_up((size_t)(d->T > 0 ? d->T : 1) * rs * sizeof(float), WS_ALIGN);
   size_t off = 0;
   p.u_off = off; off += uv;
+  const bool bf = d->in_dtype == MARLAAS_BF16 && d->n_adapters > 0;
+  if (bf) { p.uv2_bytes = uv; p.u2_off = off; off += uv; }
   size_t part = 0;
   const int n_ext = sum_ranks_of(d);
   if (d->in_dtype == MARLAAS_BF16) part = gemm_splitk_bytes(d->T, d->d_in, d->d_out, n_ext);
+  if (bf) {
+    const size_t ps = shrink_partial_bytes(d->d_in, d->map->T_lora, d->n_adapters, (int)rs);
+    if (ps > part) part = ps;
+  }
   if (want_bwd) {
     p.v_off = off; off += uv;
+    if (bf) { p.v2_off = off; off += uv; }
     if (d->in_dtype == MARLAAS_BF16) {
+      const size_t pv = d->n_adapters > 0 ? shrink_partial_bytes(d->d_out, d->map->T_lora, d->n_adapters, (int)rs) : 0;
+      if (pv > part) part = pv;
       // (few adapters: room for the reductions' sums even where one chunk covers a segment, so
       // that a backward with the optimizer step attached can always run)
       const bool always = d->n_adapters <= OPT_MAX_ADAPTERS;
@@ -732,9 +742,13 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
         fuse.u_out = u;
       }
     }
+    bool have_u2 = false;
+    bf16_t* u2 = (have_ws && p.uv2_bytes) ? (bf16_t*)((char*)ws + p.u2_off) : nullptr;
     if (lora && !fused)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
-                                      map->max_seg, table, 0, form, u, rs, map->T_lora, st));
+                                      map->max_seg, table, 0, form, u, rs, map->T_lora, part, part ? p.part_bytes : 0, u2,
+                                      &have_u2, st));
+    (void)have_u2;
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
@@ -1003,7 +1017,7 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
     const bf16_t* dy = (const bf16_t*)dY;
     if (need_u)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, 0, fform, u, rs, map->T_lora, st));
+                                      table, 0, fform, u, rs, map->T_lora, part, part ? p.part_bytes : 0, nullptr, nullptr, st));
     // small batches: the dX GEMM computes v itself (and leaves it in `v` for the dA reduction)
     GemmFuse fuse;
     bool fused = false;
@@ -1014,9 +1028,12 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
         fuse.u_out = v;
       }
     }
+    bool have_v2 = false;
+    bf16_t* v2 = (have_ws && p.uv2_bytes && dX) ? (bf16_t*)((char*)ctx->ws + p.v2_off) : nullptr;
     if (lora && (dX || want_grads) && !fused)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, 1, bform, v, rs, map->T_lora, st));
+                                      table, 1, bform, v, rs, map->T_lora, part, part ? p.part_bytes : 0, v2, &have_v2, st));
+    (void)have_v2;
     if (dX && d->T > 0)
       PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,

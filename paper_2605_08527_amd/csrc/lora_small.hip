@@ -36,7 +36,24 @@ struct ShrinkArgs {
   const AdapterEntry* table; int which;
   float* u; int r_stride;
   int ksplit; int kchunk;   // kchunk is a multiple of SH_KSTG
+  // ksplit > 1: split ks leaves its unscaled sums in partials[ks][T_lora][r_stride] and
+  // shrink_finalize_kernel adds them in split order (the result does not depend on timing)
+  float* partials; int64_t T_lora;
+  // optional second output for the large-batch GEMM's DMA: row m holds [u_hi (r_pad) | u_lo (r_pad)]
+  // of its adapter in bf16, u_hi = bf16(u), u_lo = bf16(u - u_hi); row stride 2 * r_stride
+  bf16_t* u2;
 };
+
+// u (scaled, fp32) and its two-term bf16 split for row m, rank index q of an adapter with padded rank r_pad
+__device__ __forceinline__ void shrink_store(const ShrinkArgs& a, int64_t m, int q, int r_pad, float val) {
+  a.u[m * a.r_stride + q] = val;
+  if (a.u2) {
+    const bf16_t h = float_to_bf16_bits(val);
+    bf16_t* row = a.u2 + m * (2 * a.r_stride);
+    row[q] = h;
+    row[r_pad + q] = float_to_bf16_bits(val - bf16_bits_to_float(h));
+  }
+}
 
 // grid: x = row blocks of the largest segment * ksplit, y = adapter
 // NQT: 16-wide output tiles held per wave (covers the largest padded rank of the call)
@@ -155,9 +172,8 @@ __global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 1 : 2)) void shrink_bf16_ke
       for (int v = 0; v < 4; ++v) {
         const int mr = row0 + wave * 16 + 4 * g + v;
         if (mr < hi) {
-          float* up = a.u + (int64_t)mr * a.r_stride + qt * 16 + li;
-          const float val = e.scale * acc[qt][v];
-          if (a.ksplit > 1) atomicAdd(up, val); else *up = val;
+          if (a.ksplit > 1) a.partials[((int64_t)ks * a.T_lora + mr) * a.r_stride + qt * 16 + li] = acc[qt][v];
+          else shrink_store(a, mr, qt * 16 + li, r_pad, e.scale * acc[qt][v]);
         }
       }
 }
@@ -234,20 +250,51 @@ __global__ __launch_bounds__(64 * SS_WAVES) void shrink_small_nt_kernel(ShrinkAr
   }
 }
 
-// plain fill (a kernel, not a memset node, so that callers may capture the pass in a HIP graph)
-__global__ __launch_bounds__(256) void zero_f32_kernel(float4* p, int64_t n4) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+// Second step of a shrink with a split contraction: block = (adapter, 16 grouped rows), thread =
+// (row, 16 rank indices apart); the splits are added in split order, then scaled.
+__global__ __launch_bounds__(256) void shrink_finalize_kernel(ShrinkArgs a) {
+  const int t = blockIdx.y;
+  const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
+  const int64_t m = lo + (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (m >= hi) return;
+  const AdapterEntry e = a.table[t];
+  const int r_pad = (e.rank + 15) & ~15;
+  for (int q = threadIdx.x & 15; q < r_pad; q += 16) {
+    float sum = 0.f;
+    for (int ks = 0; ks < a.ksplit; ++ks) sum += a.partials[((int64_t)ks * a.T_lora + m) * a.r_stride + q];
+    shrink_store(a, m, q, r_pad, e.scale * sum);
+  }
+}
+
+// Splits of the shrink's contraction: enough blocks to fill the chip when the rows alone do not.
+static int shrink_splits(int64_t C, int64_t T_lora, int n_adapters) {
+  const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
+  const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
+  int ksplit = 1;
+  if (real_blocks < 512) {
+    ksplit = (int)((1024 + real_blocks - 1) / real_blocks);
+    if (ksplit > kst) ksplit = kst;
+  }
+  return ksplit;
+}
+
+size_t shrink_partial_bytes(int64_t C, int64_t T_lora, int n_adapters, int r_stride) {
+  if (T_lora <= 0 || n_adapters <= 0) return 0;
+  const int ks = shrink_splits(C, T_lora, n_adapters);
+  return ks > 1 ? (size_t)ks * T_lora * r_stride * sizeof(float) : 0;
 }
 
 hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, int which, int lora_form, float* u,
-                              int r_stride, int64_t T_lora, hipStream_t stream) {
+                              int r_stride, int64_t T_lora, float* partials, size_t partial_bytes,
+                              bf16_t* u2, bool* wrote_u2, hipStream_t stream) {
+  if (wrote_u2) *wrote_u2 = false;
   if (n_adapters <= 0 || max_seg <= 0 || T_lora <= 0) return hipSuccess;
   ShrinkArgs a;
   a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
   a.which = which; a.u = u; a.r_stride = r_stride;
+  a.partials = nullptr; a.T_lora = T_lora; a.u2 = nullptr;
   const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
   if (lora_form == FORM_NT && real_blocks <= 96) {
     a.ksplit = 1; a.kchunk = 0;
@@ -258,18 +305,18 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   }
   const int rb_max = (max_seg + SH_ROWS - 1) / SH_ROWS;
   const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
-  int ksplit = 1;
-  if (real_blocks < 512) {
-    ksplit = (int)((1024 + real_blocks - 1) / real_blocks);
-    if (ksplit > kst) ksplit = kst;
-  }
+  int ksplit = shrink_splits(C, T_lora, n_adapters);
+  // (no room for the splits' sums: fewer splits)
+  const size_t per_split = (size_t)T_lora * r_stride * sizeof(float);
+  if (ksplit > 1 && (partials == nullptr || partial_bytes < (size_t)ksplit * per_split))
+    ksplit = partials ? (int)(partial_bytes / per_split) : 1;
+  if (ksplit < 1) ksplit = 1;
   a.kchunk = ((kst + ksplit - 1) / ksplit) * SH_KSTG;
   ksplit = (int)((C + a.kchunk - 1) / a.kchunk);
   a.ksplit = ksplit;
-  if (ksplit > 1) {
-    const int64_t n4 = T_lora * r_stride / 4;   // r_stride is a multiple of 16
-    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, (float4*)u, n4);
-  }
+  a.partials = partials;
+  a.u2 = u2;
+  if (wrote_u2) *wrote_u2 = u2 != nullptr;
   const size_t lds = (size_t)r_stride * SH_PITCH;   // r_stride >= every r_pad
   typedef void (*kern_t)(ShrinkArgs);
   const int nq = r_stride / 16;
@@ -285,6 +332,9 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(kern, dim3(rb_max * ksplit, n_adapters), dim3(SH_THREADS), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || ksplit == 1) return e;
+  hipLaunchKernelGGL(shrink_finalize_kernel, dim3((max_seg + 15) / 16, n_adapters), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
