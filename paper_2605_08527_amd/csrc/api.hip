@@ -27,6 +27,7 @@ struct marlaas_ctx {
   int32_t* sync_dev = nullptr;   // counters of the decode kernel (zero between launches)
   int cu_count = 0;
   int spin_limit = 1 << 20;
+  void* zero_dev = nullptr;    // 256 zero bytes (what masked DMA lanes fetch)
   int decode_finish = DECODE_FINISH_AUTO;     // how the decode kernel's calls get finished (DECODE_FINISH_*)
   std::string err;
   bool profile = false;
@@ -166,7 +167,9 @@ extern "C" int marlaas_create(marlaas_ctx** out, int device) {
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->cu_count = prop.multiProcessorCount;
   if (hipMalloc((void**)&ctx->sync_dev, DECODE_SYNC_INTS * sizeof(int32_t)) != hipSuccess ||
-      hipMemset(ctx->sync_dev, 0, DECODE_SYNC_INTS * sizeof(int32_t)) != hipSuccess) {
+      hipMemset(ctx->sync_dev, 0, DECODE_SYNC_INTS * sizeof(int32_t)) != hipSuccess ||
+      hipMalloc(&ctx->zero_dev, 256) != hipSuccess || hipMemset(ctx->zero_dev, 0, 256) != hipSuccess) {
+    (void)hipFree(ctx->zero_dev);
     (void)hipFree(ctx->sync_dev);
     delete ctx;
     return MARLAAS_ENOMEM;
@@ -222,6 +225,7 @@ extern "C" void marlaas_destroy(marlaas_ctx* ctx) {
   (void)hipSetDevice(ctx->device);
   drop_spans(ctx);
   (void)hipFree(ctx->sync_dev);
+  (void)hipFree(ctx->zero_dev);
   delete ctx;
 }
 
@@ -493,6 +497,7 @@ static int64_t ws_ext_cap(int64_t n_ext) { return n_ext < EXT_CAP_MAX ? n_ext : 
 struct WsPlan {
   size_t u_off = 0, v_off = 0, part_off = 0, part_bytes = 0, total = 0;   // part: reused by every kernel with partial sums
   size_t u2_off = 0, v2_off = 0, uv2_bytes = 0;   // two-term bf16 splits of u and v, [T][2 r_stride] (bf16 inputs)
+  size_t lt_off = 0, lt_bytes = 0;                // the row tiles' lists of extra contraction tiles (large-batch GEMM)
   size_t wt_off = 0, wt_bytes = 0;   // transposed copy of the weight (large batches, output-contiguous storage)
   size_t tab_off = 0, tab_bytes = 0; // per-call copy of the adapter tables (descriptors without a table object)
 };
@@ -504,7 +509,10 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
   size_t off = 0;
   p.u_off = off; off += uv;
   const bool bf = d->in_dtype == MARLAAS_BF16 && d->n_adapters > 0;
-  if (bf) { p.uv2_bytes = uv; p.u2_off = off; off += uv; }
+  if (bf) {
+    p.uv2_bytes = uv; p.u2_off = off; off += uv;
+    p.lt_bytes = align_up(lora_tiles_bytes(d->T), WS_ALIGN); p.lt_off = off; off += p.lt_bytes;
+  }
   size_t part = 0;
   const int n_ext = sum_ranks_of(d);
   if (d->in_dtype == MARLAAS_BF16) part = gemm_splitk_bytes(d->T, d->d_in, d->d_out, n_ext);
@@ -748,12 +756,16 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
                                       map->max_seg, table, 0, form, u, rs, map->T_lora, part, part ? p.part_bytes : 0, u2,
                                       &have_u2, st));
-    (void)have_u2;
+    LoraDma dma;
+    if (have_u2 && have_ws && p.lt_bytes) {
+      dma.u2 = u2; dma.tiles = (int32_t*)((char*)ws + p.lt_off); dma.tiles_bytes = p.lt_bytes;
+      dma.zero_line = (const bf16_t*)ctx->zero_dev; dma.ranks_mult8 = bank.mult8;
+    }
     PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16((const bf16_t*)d->x, d->ldx, (const bf16_t*)d->W, d->ldw, form, d->T, d->d_in,
                                   d->d_out, perm, map->seg_off_dev, d->n_adapters, table, 1, lora ? u : nullptr,
                                   rs, y, ldy, out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                   fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ws + p.wt_off) : nullptr,
-                                  p.wt_bytes, d->layout == MARLAAS_LAYOUT_MATH ? (const bf16_t*)d->W_t : nullptr, (const bf16_t*)d->W_packed_fwd, &dsync, st));
+                                  p.wt_bytes, d->layout == MARLAAS_LAYOUT_MATH ? (const bf16_t*)d->W_t : nullptr, &dma, (const bf16_t*)d->W_packed_fwd, &dsync, st));
   } else {
     if (lora)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_f32((const float*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
@@ -1033,13 +1045,17 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
     if (lora && (dX || want_grads) && !fused)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, 1, bform, v, rs, map->T_lora, part, part ? p.part_bytes : 0, v2, &have_v2, st));
-    (void)have_v2;
+    LoraDma dma;
+    if (have_v2 && p.lt_bytes) {
+      dma.u2 = v2; dma.tiles = (int32_t*)((char*)ctx->ws + p.lt_off); dma.tiles_bytes = p.lt_bytes;
+      dma.zero_line = (const bf16_t*)ctx->zero_dev; dma.ranks_mult8 = bank.mult8;
+    }
     if (dX && d->T > 0)
       PROFILED(ctx, MARLAAS_KERNEL_GEMM, st, launch_gemm_bf16(dy, lddy, (const bf16_t*)d->W, d->ldw, bform, d->T, d->d_out, d->d_in, perm,
                                     map->seg_off_dev, d->n_adapters, table, 0, lora ? v : nullptr, rs, dX, lddx,
                                     out_f32, part, part ? p.part_bytes : 0, map->chunks_dev, map->n_chunks,
                                     fused ? &fuse : nullptr, (have_ws && p.wt_bytes) ? (bf16_t*)((char*)ctx->ws + p.wt_off) : nullptr,
-                                    p.wt_bytes, d->layout == MARLAAS_LAYOUT_TORCH ? (const bf16_t*)d->W_t : nullptr, (const bf16_t*)d->W_packed_bwd, &dsync, st));
+                                    p.wt_bytes, d->layout == MARLAAS_LAYOUT_TORCH ? (const bf16_t*)d->W_t : nullptr, &dma, (const bf16_t*)d->W_packed_bwd, &dsync, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
                                       table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[1] : nullptr, st));

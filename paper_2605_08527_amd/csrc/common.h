@@ -152,6 +152,18 @@ struct DecodeSync {
 };
 static constexpr int DECODE_SYNC_INTS = 4096;
 
+// What lets the large-batch GEMM fetch the expand's operands by DMA: u (or v) as a two-term bf16
+// split written by the shrink, scratch for the row tiles' lists of extra contraction tiles
+// (lora_tiles_bytes(T) bytes), 16 zero bytes in device memory, and whether every rank is a
+// multiple of 8.
+struct LoraDma {
+  const bf16_t* u2 = nullptr;
+  int32_t* tiles = nullptr; size_t tiles_bytes = 0;
+  const bf16_t* zero_line = nullptr;
+  bool ranks_mult8 = false;
+};
+size_t lora_tiles_bytes(int64_t T);
+
 struct GemmFuse {
   const ExtCol* cols;      // [n_ext] device
   const int32_t* roff;     // [n_adapters + 1] device: rank offsets
@@ -170,7 +182,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes, const bf16_t* Bt_kept,
+                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes, const bf16_t* Bt_kept, const LoraDma* dma,
                             const bf16_t* Bpacked, const DecodeSync* sync, hipStream_t stream);
 // (Bpacked: optional packed copy of Bop for this contraction, used by small batches; with it the
 // shrink is only fused when the adapters' factors are stored contraction-contiguous, which the

@@ -48,8 +48,18 @@ struct GemmArgs {
   int fin_in_kernel, out_is_f32, lform, spin_limit;
   int32_t* sync;
   const int32_t* grp_ids;
+  // Large-batch kernel, LoRA expand by DMA (lora_dma = 1): U2 is u as a two-term bf16 split
+  // ([T][2 r_stride], row m = [u_hi (r_pad) | u_lo (r_pad)] of its adapter), lora_tiles the list
+  // of 64-wide extra contraction tiles of every 256-row tile (lora_tile_list_kernel), zero_line
+  // 16 readable zero bytes that masked DMA lanes fetch.
+  const bf16_t* U2; const int32_t* lora_tiles; const bf16_t* zero_line; int lora_dma;
   ProjEntry proj[MAX_PROJ];     // by value: read with wave-uniform loads from the kernel arguments
 };
+
+// List of one 256-row tile's extra contraction tiles: int32 [LT_STRIDE]: count (-1: more than
+// LT_MAX, the kernel then stages the expand through registers), then {adapter, first row, end row,
+// first contraction index} per tile.
+static constexpr int LT_MAX = 15, LT_STRIDE = 64;
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;

@@ -48,7 +48,8 @@ static constexpr int STAGE_BYTES = BM * BK * 2;            // 32 KB: one operand
 static constexpr int SLOT_BYTES = 2 * STAGE_BYTES;         // 64 KB: A part then B part
 static constexpr int SLOT_B_OFF = STAGE_BYTES;
 static constexpr int RING_SLOTS = 2;
-static constexpr int GEMM_LDS = RING_SLOTS * SLOT_BYTES + BM * 4;  // ring + token ids
+static constexpr int LT_LDS = 16 * (4 * 4 + 8);             // the tile's extra contraction tiles: first row, end row, first k, rank; factor
+static constexpr int GEMM_LDS = RING_SLOTS * SLOT_BYTES + BM * 4 + LT_LDS;  // ring + token ids + LoRA tile list
 
 // LDS byte offset of 16-byte unit `unit` (of 32) of k-row `k` in a [64][256] bf16 tile.
 __device__ __forceinline__ int kn_swz(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
@@ -112,6 +113,11 @@ template <int FORM, bool OUT_F32, int LFORM = FORM>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int32_t* tok_s = (int32_t*)(smem + RING_SLOTS * SLOT_BYTES);
+  uint64_t* ltL_s = (uint64_t*)(tok_s + BM);     // per extra contraction tile: factor of its adapter,
+  int32_t* ltlo_s = (int32_t*)(ltL_s + 16);      // first and end row of its segment inside the tile,
+  int32_t* lthi_s = ltlo_s + 16;
+  int32_t* ltkc_s = lthi_s + 16;                 // first contraction index, rank
+  int32_t* ltr_s = ltkc_s + 16;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -148,6 +154,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     int32_t tok = -1;
     if (m < a.T) tok = a.perm ? a.perm[m] : (int32_t)m;
     tok_s[i] = tok;
+  }
+  // LoRA expand by DMA: this row tile's list of extra contraction tiles (they run after the main loop)
+  int lt_cnt = -1;
+  if (a.lora_dma && a.ksplit == 1 && a.n_adapters > 0) {
+    const int32_t* lt = a.lora_tiles + (int64_t)tm * LT_STRIDE;
+    lt_cnt = lt[0];
+    if (tid < lt_cnt) {
+      const int t = lt[1 + 4 * tid];
+      const AdapterEntry e = a.table[t];
+      ltL_s[tid] = (uint64_t)(uintptr_t)(a.which ? e.B : e.A);
+      ltlo_s[tid] = lt[2 + 4 * tid]; lthi_s[tid] = lt[3 + 4 * tid]; ltkc_s[tid] = lt[4 + 4 * tid]; ltr_s[tid] = e.rank;
+    }
   }
   __syncthreads();
 
@@ -333,7 +351,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   // LoRA expand as extra contraction steps, one adapter segment at a time, staged through slot 1.
   // All global loads of a chunk are issued before any of them is used.
-  if (a.ksplit == 1 && a.n_adapters > 0 && a.U != nullptr) {
+  if (a.ksplit == 1 && a.n_adapters > 0 && a.U != nullptr && lt_cnt < 0) {
     char* La = smem + SLOT_BYTES;
     char* Lb = La + STAGE_BYTES;
     const int64_t T_lora = a.seg_off[a.n_adapters];
@@ -444,6 +462,60 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     RING_TILE(kt, 0, 0, 0);
   }
   __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
+
+  // ---- LoRA expand by DMA: per adapter segment of the tile's rows, 64-wide contraction tiles of
+  // [u_hi | u_lo] x [L_t ; L_t], fetched like the main loop's tiles: the x side from the bf16 split
+  // of u the shrink wrote (rows outside the segment fetch zeros), the weight side from the
+  // adapter's factor (the two halves of the contraction read the same ranks).  Tile i + 1 is in
+  // flight while tile i is multiplied.
+  if (lt_cnt > 0) {
+#define LORA_DMA(i_, slot_)                                                                               \
+    do {                                                                                                  \
+      const int _lo = ltlo_s[i_], _hi = lthi_s[i_], _kc = ltkc_s[i_], _r = ltr_s[i_];                      \
+      const int _rp = (_r + 15) & ~15, _kext = 2 * _rp;                                                   \
+      const bf16_t* _L = (const bf16_t*)(uintptr_t)ltL_s[i_];                                             \
+      _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) {                                                \
+        char* _sb = smem + (slot_) * SLOT_BYTES + dma_off + _j * 1024;                                    \
+        const int _row = (wave * DPW + _j) * 8 + (lane >> 3);                                             \
+        const int _kk = _kc + (((lane & 7) ^ ((_row >> 1) & 7)) << 3);                                    \
+        const int64_t _m = m0 + _row;                                                                     \
+        const bf16_t* _src = a.zero_line;                                                                 \
+        if (_m >= _lo && _m < _hi && _kk < _kext) _src = a.U2 + _m * (2 * a.r_stride) + _kk;              \
+        __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)_sb, 16, 0, 0);                            \
+      }                                                                                                   \
+      _Pragma("unroll") for (int _j = 0; _j < DPW; ++_j) {                                                \
+        char* _sb = smem + (slot_) * SLOT_BYTES + SLOT_B_OFF + dma_off + _j * 1024;                       \
+        const bf16_t* _src = a.zero_line;                                                                 \
+        if (LFORM == FORM_NT) {          /* L_t[n * r + q]: row-k tile, 8 rows of 128 bytes per instruction */ \
+          const int _row = (wave * DPW + _j) * 8 + (lane >> 3);                                           \
+          const int _kk = _kc + (((lane & 7) ^ ((_row >> 1) & 7)) << 3);                                  \
+          const int _q = _kk >= _rp ? _kk - _rp : _kk;                                                    \
+          const int64_t _n = n0 + _row;                                                                   \
+          if (_kk < _kext && _q < _r && _n < a.Nout) _src = _L + _n * _r + _q;                            \
+        } else {                         /* L_t[q * Nout + n]: k-n tile, 2 k-rows of 512 bytes per instruction */ \
+          const int _k = (wave * DPW + _j) * 2 + (lane >> 5);                                             \
+          const int _kk = _kc + _k;                                                                       \
+          const int _q = _kk >= _rp ? _kk - _rp : _kk;                                                    \
+          const int64_t _n = n0 + (((lane & 31) ^ kn_swz(_k)) << 3);                                      \
+          if (_kk < _kext && _q < _r && _n < a.Nout) _src = _L + (int64_t)_q * a.Nout + _n;               \
+        }                                                                                                 \
+        __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)_sb, 16, 0, 0);                            \
+      }                                                                                                   \
+    } while (0)
+    LORA_DMA(0, 0);
+    for (int i = 0; i < lt_cnt; ++i) {
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+      __syncthreads();               // tile i has landed everywhere, nobody still reads tile i - 1
+      if (i + 1 < lt_cnt) LORA_DMA(i + 1, (i + 1) & 1);
+      const char* Ls = smem + (i & 1) * SLOT_BYTES;
+      const int rp = (ltr_s[i] + 15) & ~15;
+      const int ksteps = (2 * rp - ltkc_s[i]) >= BK ? 2 : 1;     // 2 r_pad is a multiple of 32
+      for (int ks = 0; ks < ksteps; ++ks)
+        mma_kstep<LFORM>(Ls, Ls + SLOT_B_OFF, ks, a_off_row, a_swz, fg, b_off_row, b_swz, btr, acc);
+    }
+    __syncthreads();                 // the slots are reused below
+#undef LORA_DMA
+  }
   char* As = smem;                 // one 64-wide A tile
   char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile
 
@@ -1258,9 +1330,47 @@ static hipError_t allow_lds(const void* kernel, int bytes, std::atomic<uint64_t>
   return e;
 }
 
+// One thread per 256-row tile: the adapter segments that intersect the tile's rows, each cut into
+// 64-wide pieces of its 2 r_pad extra contraction values (the rows are grouped by adapter, so the
+// segments of a tile are consecutive adapters).
+__global__ __launch_bounds__(64) void lora_tile_list_kernel(const int32_t* __restrict__ seg_off, int n_adapters,
+                                                            const AdapterEntry* __restrict__ table, int tiles_m,
+                                                            int32_t* __restrict__ out) {
+  const int tm = blockIdx.x * 64 + threadIdx.x;
+  if (tm >= tiles_m) return;
+  int32_t* o = out + (int64_t)tm * LT_STRIDE;
+  const int64_t m0 = (int64_t)tm * BM;
+  const int64_t T_lora = seg_off[n_adapters];
+  const int64_t m_end = (m0 + BM) < T_lora ? (m0 + BM) : T_lora;
+  int cnt = 0;
+  if (m0 < m_end) {
+    int t = segment_of(seg_off, n_adapters, (int)m0);
+    while (cnt >= 0 && t < n_adapters && (int64_t)seg_off[t] < m_end) {
+      const int64_t lo = seg_off[t] > m0 ? (int64_t)seg_off[t] : m0;
+      const int64_t hi = (int64_t)seg_off[t + 1] < m_end ? (int64_t)seg_off[t + 1] : m_end;
+      if (hi > lo) {
+        const int kext = 2 * ((table[t].rank + 15) & ~15);
+        for (int kc = 0; kc < kext; kc += BK) {
+          if (cnt == LT_MAX) { cnt = -1; break; }
+          o[1 + 4 * cnt] = t; o[2 + 4 * cnt] = (int32_t)lo; o[3 + 4 * cnt] = (int32_t)hi; o[4 + 4 * cnt] = kc;
+          ++cnt;
+        }
+      }
+      ++t;
+    }
+  }
+  o[0] = cnt;
+}
+
 template <int FORM, bool OUT_F32, int LFORM = FORM>
 static hipError_t launch_wide(const GemmArgs& a, hipStream_t stream) {
   static std::atomic<uint64_t> done{0};
+  if (a.lora_dma) {
+    hipLaunchKernelGGL(lora_tile_list_kernel, dim3((a.tiles_m + 63) / 64), dim3(64), 0, stream, a.seg_off, a.n_adapters, a.table,
+                       a.tiles_m, (int32_t*)a.lora_tiles);
+    hipError_t el = hipGetLastError();
+    if (el != hipSuccess) return el;
+  }
   hipError_t e0 = allow_lds((const void*)gemm_bf16_kernel<FORM, OUT_F32, LFORM>, GEMM_LDS, done);
   if (e0 != hipSuccess) return e0;
   hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32, LFORM>), dim3(a.tiles_m * a.tiles_n * a.ksplit), dim3(GEMM_THREADS),
@@ -1284,8 +1394,10 @@ static hipError_t launch_one(const GemmArgs& a, int mode, bool packed, hipStream
     hipLaunchKernelGGL((gemm_skinny_kernel<FORM, true>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
   else if (mode == 2)
     hipLaunchKernelGGL((gemm_skinny_kernel<FORM, false>), dim3(G * a.ksplit), dim3(256), SK_LDS, stream, a);
-  else
-    hipLaunchKernelGGL((gemm_bf16_kernel<FORM, OUT_F32>), dim3(G * a.ksplit), dim3(GEMM_THREADS), GEMM_LDS, stream, a);
+  else {
+    hipError_t ew = launch_wide<FORM, OUT_F32, FORM>(a, stream);
+    if (ew != hipSuccess) return ew;
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || mode == 0 || (packed && a.fin_in_kernel)) return e;
   const int64_t fin_blocks = (int64_t)a.fin_cols * a.n_chunks;
@@ -1386,6 +1498,10 @@ bool gemm_can_fuse_shrink(int form, int64_t T, int64_t Kc, int64_t Nout, int n_e
   return p.mode == 2 && p.u_bytes > 0 && partial_bytes >= p.bytes + p.u_bytes;
 }
 
+size_t lora_tiles_bytes(int64_t T) {
+  return T > 0 ? (size_t)((T + BM - 1) / BM) * LT_STRIDE * sizeof(int32_t) : 0;
+}
+
 // Way the decode kernel's call is finished: the one asked for where its conditions hold, else the
 // next best.  Both ways other than the generic finish kernel need the splits to divide a tile's
 // 32 units and u of a tile's rows to fit in LDS.  The in-kernel way also needs its counters; with
@@ -1414,7 +1530,7 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
                             const int32_t* seg_off, int n_adapters, const AdapterEntry* table,
                             int which, const float* U, int r_stride, void* out, int64_t ldo,
                             int out_is_f32, float* partials, size_t partial_bytes, const RowChunk* chunks,
-                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes, const bf16_t* Bt_kept,
+                            int n_chunks, const GemmFuse* fuse, bf16_t* wt_scratch, size_t wt_bytes, const bf16_t* Bt_kept, const LoraDma* dma,
                             const bf16_t* Bpacked, const DecodeSync* sync, hipStream_t stream) {
   if (T <= 0 || Nout <= 0) return hipSuccess;
   if (ldb > (1 << 22)) return hipErrorInvalidValue;      // 32-bit byte offsets inside a weight tile
@@ -1446,6 +1562,13 @@ hipError_t launch_gemm_bf16(const bf16_t* Aop, int64_t lda, const bf16_t* Bop, i
   }
   a.tiles_m = p.tiles_m; a.tiles_n = p.tiles_n; a.ksplit = p.ksplit; a.kchunk = p.kchunk;
   a.ldp = p.ldp; a.pm = p.pm; a.partials = partials; a.chunks = chunks; a.n_chunks = n_chunks;
+  // large batch, unsplit: the expand's operands by DMA when the shrink left u as a bf16 split, the
+  // row tiles' lists have room, and every 16-byte piece of a factor row stays inside the row
+  a.U2 = nullptr; a.lora_tiles = nullptr; a.zero_line = nullptr; a.lora_dma = 0;
+  if (dma && dma->u2 && dma->tiles && dma->zero_line && p.mode == 0 && p.ksplit == 1 && n_adapters > 0 && U != nullptr &&
+      (form == FORM_NN || dma->ranks_mult8) && dma->tiles_bytes >= (size_t)p.tiles_m * LT_STRIDE * sizeof(int32_t)) {
+    a.U2 = dma->u2; a.lora_tiles = dma->tiles; a.zero_line = dma->zero_line; a.lora_dma = 1;
+  }
   // small batch with a packed copy of the weight (and, when the shrink is fused, factors stored
   // contraction-contiguous): the decode kernel reads the packed copy instead of Bop
   const bool packed = Bpacked != nullptr && p.mode == 2 && (fuse == nullptr || form == FORM_NT);
@@ -1536,6 +1659,7 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
   if (packed != 0 && !pk) return hipErrorInvalidValue;
   a.fin_in_kernel = 0; a.out_is_f32 = out_is_f32; a.lform = form; a.spin_limit = 0;
   a.sync = nullptr; a.grp_ids = nullptr;
+  a.U2 = nullptr; a.lora_tiles = nullptr; a.zero_line = nullptr; a.lora_dma = 0;
   if (pk) a.fin_in_kernel = decode_finish_mode(sync, n_adapters, r_stride, p.tiles_m, p.tiles_n, p.ksplit);
   if (a.fin_in_kernel) {
     a.sync = sync->counters; a.grp_ids = sync->grp_ids; a.spin_limit = sync->spin_limit;

@@ -148,3 +148,35 @@ def test_mid_size_batches(oracle, layout, T):
         ga, gb = (dA_ref[s].T, dB_ref[s].T) if layout == wl.TORCH else (dA_ref[s], dB_ref[s])
         assert_close(to_host(dA[t]), ga, "mid dA[%d]" % t)
         assert_close(to_host(dB[t]), gb, "mid dB[%d]" % t)
+
+
+@pytest.mark.parametrize("n_adapters", [150, 400], ids=["12-segments-per-tile", "more-segments-than-the-list-holds"])
+@pytest.mark.parametrize("layout", [wl.MATH, wl.TORCH])
+def test_many_short_segments_in_a_row_tile(oracle, layout, n_adapters):
+    """Large batch whose 256-row tiles each hold many adapter segments (ranks 8 .. 32, multiples of
+    8): the expand's extra contraction tiles are listed per row tile and fetched by DMA after the
+    main loop; with 400 adapters a row tile has more of them than its list holds and the kernel
+    stages the expand through registers instead.  Forward and backward, sampled rows, every tenth
+    adapter's gradients."""
+    rng = np.random.default_rng(43 + n_adapters)
+    T, K, N = 4352, 512, 4096
+    ranks = [int(r) for r in rng.choice([8, 16, 24, 32], size=n_adapters)]
+    scales = [float(s) for s in rng.choice([2.0, 1.0, 0.5], size=n_adapters)]
+    ids = rng.integers(-1, n_adapters, size=T).astype(np.int32)
+    w = wl.make_layer(47, T, K, N, ranks, scales, ids, dtype="bf16", layout=layout, want_dY=True)
+    L = HipLayer(w, out_dtype=torch.float32, want_bwd=True, table=True, kept_wt=True)
+    rows = _sample_rows(ids, 200, 13)
+    rows_t = torch.from_numpy(rows).cuda()
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    y, u = L.fwd(save_u=True)
+    assert_close(to_host(y[rows_t]), oracle.fwd(*args, layout=layout, rows=rows), "y")
+    assert bool(torch.isfinite(y).all())
+    dX, dA, dB = L.bwd(u_saved=u)
+    sel = list(range(0, n_adapters, 10))
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=layout, rows=rows, adapters=sel)
+    assert_close(to_host(dX[rows_t]), dX_ref, "dX")
+    assert bool(torch.isfinite(dX).all())
+    for s, t in enumerate(sel):
+        ga, gb = (dA_ref[s].T, dB_ref[s].T) if layout == wl.TORCH else (dA_ref[s], dB_ref[s])
+        assert_close(to_host(dA[t]), ga, "dA[%d]" % t)
+        assert_close(to_host(dB[t]), gb, "dB[%d]" % t)
