@@ -755,7 +755,7 @@ static int fwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, void* y, int64
     if (lora && !fused)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16((const bf16_t*)d->x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters,
                                       map->max_seg, table, 0, form, u, rs, map->T_lora, part, part ? p.part_bytes : 0, u2,
-                                      &have_u2, st));
+                                      &have_u2, (const bf16_t*)ctx->zero_dev, bank.mult8, st));
     LoraDma dma;
     if (have_u2 && have_ws && p.lt_bytes) {
       dma.u2 = u2; dma.tiles = (int32_t*)((char*)ws + p.lt_off); dma.tiles_bytes = p.lt_bytes;
@@ -1029,7 +1029,7 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
     const bf16_t* dy = (const bf16_t*)dY;
     if (need_u)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, 0, fform, u, rs, map->T_lora, part, part ? p.part_bytes : 0, nullptr, nullptr, st));
+                                      table, 0, fform, u, rs, map->T_lora, part, part ? p.part_bytes : 0, nullptr, nullptr, (const bf16_t*)ctx->zero_dev, bank.mult8, st));
     // small batches: the dX GEMM computes v itself (and leaves it in `v` for the dA reduction)
     GemmFuse fuse;
     bool fused = false;
@@ -1044,7 +1044,7 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
     bf16_t* v2 = (have_ws && p.uv2_bytes && dX) ? (bf16_t*)((char*)ctx->ws + p.v2_off) : nullptr;
     if (lora && (dX || want_grads) && !fused)
       PROFILED(ctx, MARLAAS_KERNEL_SHRINK, st, launch_shrink_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, 1, bform, v, rs, map->T_lora, part, part ? p.part_bytes : 0, v2, &have_v2, st));
+                                      table, 1, bform, v, rs, map->T_lora, part, part ? p.part_bytes : 0, v2, &have_v2, (const bf16_t*)ctx->zero_dev, bank.mult8, st));
     LoraDma dma;
     if (have_v2 && p.lt_bytes) {
       dma.u2 = v2; dma.tiles = (int32_t*)((char*)ctx->ws + p.lt_off); dma.tiles_bytes = p.lt_bytes;

@@ -131,7 +131,7 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, int which, int lora_form, float* u,
                               int r_stride, int64_t T_lora, float* partials, size_t partial_bytes,
-                              bf16_t* u2, bool* wrote_u2, hipStream_t stream);
+                              bf16_t* u2, bool* wrote_u2, const bf16_t* zero_line, bool ranks_mult8, hipStream_t stream);
 // scratch for the sums of a shrink whose contraction is split (0: it is not)
 size_t shrink_partial_bytes(int64_t C, int64_t T_lora, int n_adapters, int r_stride);
 

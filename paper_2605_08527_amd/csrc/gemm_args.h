@@ -68,6 +68,18 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 __device__ __forceinline__ int swz_rowk(int row, int unit) {
   return row * 128 + ((unit ^ ((row >> 1) & 7)) << 4);
 }
+// 8 consecutive contraction values of one column from a [k][n] tile: two
+// transposing 64-bit reads (each returns 4 consecutive k for this lane's column).
+__device__ __forceinline__ bf16x8 lds_read_frag_tr(const char* p0, const char* p1) {
+  typedef short4v __attribute__((address_space(3))) * lds_s4;
+  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p0);
+  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p1);
+  union { short s[8]; bf16x8 v; } r;
+  r.s[0] = a[0]; r.s[1] = a[1]; r.s[2] = a[2]; r.s[3] = a[3];
+  r.s[4] = b[0]; r.s[5] = b[1]; r.s[6] = b[2]; r.s[7] = b[3];
+  return r.v;
+}
+
 // s_waitcnt immediate that waits only for the vector-memory counter (6 bits, split 3:0 / 15:14)
 #define VMCNT(n) (0x0F70 | ((n) & 15) | ((((n) >> 4) & 3) << 14))
 

@@ -57,18 +57,6 @@ __device__ __forceinline__ int swz_kn(int k, int unit) {
   return k * 512 + ((unit ^ kn_swz(k)) << 4);
 }
 
-// 8 consecutive contraction values of one column from a [k][n] tile: two
-// transposing 64-bit reads (each returns 4 consecutive k for this lane's column).
-__device__ __forceinline__ bf16x8 lds_read_frag_tr(const char* p0, const char* p1) {
-  typedef short4v __attribute__((address_space(3))) * lds_s4;
-  short4v a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p0);
-  short4v b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)p1);
-  union { short s[8]; bf16x8 v; } r;
-  r.s[0] = a[0]; r.s[1] = a[1]; r.s[2] = a[2]; r.s[3] = a[3];
-  r.s[4] = b[0]; r.s[5] = b[1]; r.s[6] = b[2]; r.s[7] = b[3];
-  return r.v;
-}
-
 __device__ __forceinline__ uint4 pack8(const bf16_t* o) {
   uint4 pk;
   pk.x = o[0] | ((uint32_t)o[1] << 16); pk.y = o[2] | ((uint32_t)o[3] << 16);
@@ -442,33 +430,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     }
   }
 
-  // ---- main loop over full k-tiles
-  if (ntile > 0) {
-    bf16x8 xa0[4], xa1[4], wb0[NT], wb1[NT];
-    if (ntile > 1) {
-      RING_DMA(1, 0);
-      __builtin_amdgcn_s_waitcnt(VMCNT(DPW));     // tile 0 landed, the A part of tile 1 in flight
-    } else {
-      __builtin_amdgcn_s_waitcnt(VMCNT(0));
-    }
-    RING_BARRIER();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) RING_READ_X(0, 0, i, xa0[i]);
-#pragma unroll
-    for (int i = 0; i < NT; ++i) RING_READ_W(0, 0, i, wb0[i]);
-    int64_t kt = 0;
-    for (; kt + 2 < ntile; ++kt) RING_TILE(kt, 1, 1, 1);
-    if (kt + 1 < ntile) { RING_TILE(kt, 1, 0, 1); ++kt; }
-    RING_TILE(kt, 0, 0, 0);
-  }
-  __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
-
-  // ---- LoRA expand by DMA: per adapter segment of the tile's rows, 64-wide contraction tiles of
-  // [u_hi | u_lo] x [L_t ; L_t], fetched like the main loop's tiles: the x side from the bf16 split
-  // of u the shrink wrote (rows outside the segment fetch zeros), the weight side from the
-  // adapter's factor (the two halves of the contraction read the same ranks).  Tile i + 1 is in
-  // flight while tile i is multiplied.
-  if (lt_cnt > 0) {
+  // One extra contraction tile of the LoRA expand (entry i_ of the row tile's list) into ring slot
+  // slot_: 8 + 8 DMA instructions per wave, every lane's source picked on its own.
 #define LORA_DMA(i_, slot_)                                                                               \
     do {                                                                                                  \
       const int _lo = ltlo_s[i_], _hi = lthi_s[i_], _kc = ltkc_s[i_], _r = ltr_s[i_];                      \
@@ -502,20 +465,57 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
         __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)_sb, 16, 0, 0);                            \
       }                                                                                                   \
     } while (0)
-    LORA_DMA(0, 0);
+  int lslot0 = 0;                  // ring slot of the first extra contraction tile
+  bool lora_requested = false;
+
+  // ---- main loop over full k-tiles
+  if (ntile > 0) {
+    bf16x8 xa0[4], xa1[4], wb0[NT], wb1[NT];
+    if (ntile > 1) {
+      RING_DMA(1, 0);
+      __builtin_amdgcn_s_waitcnt(VMCNT(DPW));     // tile 0 landed, the A part of tile 1 in flight
+    } else {
+      __builtin_amdgcn_s_waitcnt(VMCNT(0));
+    }
+    RING_BARRIER();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) RING_READ_X(0, 0, i, xa0[i]);
+#pragma unroll
+    for (int i = 0; i < NT; ++i) RING_READ_W(0, 0, i, wb0[i]);
+    int64_t kt = 0;
+    for (; kt + 2 < ntile; ++kt) RING_TILE(kt, 1, 1, 1);
+    if (kt + 1 < ntile) { RING_TILE(kt, 1, 0, 1); ++kt; }
+    if (lt_cnt > 0) {
+      // the slot the last k-tile does not use is free: the first extra tile travels while the last
+      // k-tile is multiplied
+      lslot0 = (int)((kt + 1) & 1);
+      LORA_DMA(0, lslot0);
+      lora_requested = true;
+    }
+    RING_TILE(kt, 0, 0, 0);
+  }
+  __syncthreads();   // all reads of the last k-tile are done; slot 0 is reused below
+
+  // ---- LoRA expand by DMA: per adapter segment of the tile's rows, 64-wide contraction tiles of
+  // [u_hi | u_lo] x [L_t ; L_t], fetched like the main loop's tiles: the x side from the bf16 split
+  // of u the shrink wrote (rows outside the segment fetch zeros), the weight side from the
+  // adapter's factor (the two halves of the contraction read the same ranks).  Tile i + 1 is in
+  // flight while tile i is multiplied.
+  if (lt_cnt > 0) {
+    if (!lora_requested) LORA_DMA(0, lslot0);
     for (int i = 0; i < lt_cnt; ++i) {
       __builtin_amdgcn_s_waitcnt(VMCNT(0));
       __syncthreads();               // tile i has landed everywhere, nobody still reads tile i - 1
-      if (i + 1 < lt_cnt) LORA_DMA(i + 1, (i + 1) & 1);
-      const char* Ls = smem + (i & 1) * SLOT_BYTES;
+      if (i + 1 < lt_cnt) LORA_DMA(i + 1, (lslot0 + i + 1) & 1);
+      const char* Ls = smem + ((lslot0 + i) & 1) * SLOT_BYTES;
       const int rp = (ltr_s[i] + 15) & ~15;
       const int ksteps = (2 * rp - ltkc_s[i]) >= BK ? 2 : 1;     // 2 r_pad is a multiple of 32
       for (int ks = 0; ks < ksteps; ++ks)
         mma_kstep<LFORM>(Ls, Ls + SLOT_B_OFF, ks, a_off_row, a_swz, fg, b_off_row, b_swz, btr, acc);
     }
     __syncthreads();                 // the slots are reused below
-#undef LORA_DMA
   }
+#undef LORA_DMA
   char* As = smem;                 // one 64-wide A tile
   char* Bs = smem + STAGE_BYTES;   // one 64-wide B tile
 

@@ -4,7 +4,7 @@
 // LoRA parameters are trained (paper Sec. 4.2), so these are the only weight
 // gradients of the layer.  Both kernels read their big operand (x or dY) once
 // and are bound by HBM; the small operand stays in LDS.
-#include "common.h"
+#include "gemm_args.h"
 
 #include <atomic>
 
@@ -13,7 +13,7 @@ namespace marlaas {
 // Raise a kernel's dynamic LDS limit to the hardware maximum, once per (kernel, device): `slot`
 // names the kernel instantiation, bit i of its word = device i has it.
 static hipError_t allow_big_lds(const void* kernel, int slot) {
-  static std::atomic<uint64_t> done[16];
+  static std::atomic<uint64_t> done[24];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
@@ -42,6 +42,7 @@ struct ShrinkArgs {
   // optional second output for the large-batch GEMM's DMA: row m holds [u_hi (r_pad) | u_lo (r_pad)]
   // of its adapter in bf16, u_hi = bf16(u), u_lo = bf16(u - u_hi); row stride 2 * r_stride
   bf16_t* u2;
+  const bf16_t* zero_line;  // 16 readable zero bytes (what masked DMA lanes of shrink_ring_kernel fetch)
 };
 
 // u (scaled, fp32) and its two-term bf16 split for row m, rank index q of an adapter with padded rank r_pad
@@ -178,6 +179,180 @@ __global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 1 : 2)) void shrink_bf16_ke
       }
 }
 
+// The same shrink with both operands moved global -> LDS by DMA through a ring of four 64-wide
+// k-tiles, for batches with many short segments: a block takes 128 rows of one adapter (half the
+// factor traffic of 64-row blocks), every request of a wave covers whole 128-byte row segments
+// (the register-staged kernel above fetches 64-byte pieces and its factor tile through VGPRs),
+// and three k-tiles are in flight per block.  x part of a slot: [128 rows][64 k], 16-byte units
+// XOR-swizzled like the GEMM's tiles; factor part: [r_pad][64 k] for factors stored [rank][C]
+// (LFORM NT), [64 k][r_pad] read with transposing LDS reads for factors stored [C][rank] (LFORM
+// NN, ranks multiples of 8).  Rows past the end of the segment repeat its last row (never stored),
+// rank rows past r and contraction units past the end fetch zeros.
+static constexpr int SR_ROWS = 128, SR_NS = 4;
+static constexpr int SR_X_BYTES = SR_ROWS * 64 * 2;
+
+__device__ __forceinline__ void sr_wait(int n) {      // at most n vector-memory requests outstanding (n <= 16)
+  switch (n) {
+    case 0: __builtin_amdgcn_s_waitcnt(VMCNT(0)); break;
+    case 1: __builtin_amdgcn_s_waitcnt(VMCNT(1)); break;
+    case 2: __builtin_amdgcn_s_waitcnt(VMCNT(2)); break;
+    case 3: __builtin_amdgcn_s_waitcnt(VMCNT(3)); break;
+    case 4: __builtin_amdgcn_s_waitcnt(VMCNT(4)); break;
+    case 5: __builtin_amdgcn_s_waitcnt(VMCNT(5)); break;
+    case 6: __builtin_amdgcn_s_waitcnt(VMCNT(6)); break;
+    case 7: __builtin_amdgcn_s_waitcnt(VMCNT(7)); break;
+    case 8: __builtin_amdgcn_s_waitcnt(VMCNT(8)); break;
+    case 9: __builtin_amdgcn_s_waitcnt(VMCNT(9)); break;
+    case 10: __builtin_amdgcn_s_waitcnt(VMCNT(10)); break;
+    case 11: __builtin_amdgcn_s_waitcnt(VMCNT(11)); break;
+    case 12: __builtin_amdgcn_s_waitcnt(VMCNT(12)); break;
+    case 13: __builtin_amdgcn_s_waitcnt(VMCNT(13)); break;
+    case 14: __builtin_amdgcn_s_waitcnt(VMCNT(14)); break;
+    case 15: __builtin_amdgcn_s_waitcnt(VMCNT(15)); break;
+    case 16: __builtin_amdgcn_s_waitcnt(VMCNT(16)); break;
+    default: __builtin_amdgcn_s_waitcnt(VMCNT(0)); break;
+  }
+}
+
+template <int LFORM, int NQT>
+__global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int t = blockIdx.y;
+  const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
+  const int rb = blockIdx.x / a.ksplit, ks = blockIdx.x - rb * a.ksplit;
+  const int row0 = lo + rb * SR_ROWS;
+  if (row0 >= hi) return;
+  const AdapterEntry e = a.table[t];
+  const bf16_t* L = (const bf16_t*)(a.which ? e.B : e.A);
+  const int r = e.rank;
+  const int r_pad = (r + 15) & ~15;
+  const int nqt = r_pad >> 4;
+  const int64_t kbeg = (int64_t)ks * a.kchunk;
+  const int64_t kend = (kbeg + a.kchunk) < a.C ? (kbeg + a.kchunk) : a.C;
+  if (kbeg >= kend) return;
+  const int ntile = (int)((kend - kbeg + 63) >> 6);
+  const int l_bytes = NQT * 16 * 128;                  // factor part of a slot (room for the template's largest r_pad)
+  const int slot_bytes = SR_X_BYTES + l_bytes;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, li = lane & 15;
+
+  // ---- DMA sources.  x: 16 instructions of 8 rows per k-tile, 4 per wave.
+  const bf16_t* xsrc[4];
+  int xk[4];                                           // first contraction index of the lane's unit inside a k-tile
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = (wave * 4 + j) * 8 + (lane >> 3);
+    const int unit = (lane & 7) ^ ((row >> 1) & 7);
+    int m = row0 + row;
+    if (m >= hi) m = hi - 1;
+    const int64_t tok = a.perm ? a.perm[m] : m;
+    xk[j] = unit * 8;
+    xsrc[j] = a.X + tok * a.ldx + kbeg + unit * 8;
+  }
+  // factor: n_li instructions per k-tile, instruction i = wave + 4 jj
+  constexpr int LPW = (2 * NQT + 3) / 4;
+  const int n_li = LFORM == FORM_NT ? 2 * nqt : 2 * NQT;
+  const bf16_t* lsrc[LPW];
+  int lk[LPW];                                         // contraction index (inside the k-tile) the lane's piece starts at
+  bool lon[LPW];                                       // the piece exists (rank row / ranks inside r)
+  int my_l = 0;
+#pragma unroll
+  for (int jj = 0; jj < LPW; ++jj) {
+    const int i = wave + 4 * jj;
+    lsrc[jj] = a.zero_line; lk[jj] = 0; lon[jj] = false;
+    if (i < n_li) {
+      ++my_l;
+      if (LFORM == FORM_NT) {            // L[q * C + k]: 8 rank rows of 128 bytes per instruction
+        const int q = i * 8 + (lane >> 3);
+        const int unit = (lane & 7) ^ ((q >> 1) & 7);
+        lk[jj] = unit * 8;
+        lon[jj] = q < r;
+        lsrc[jj] = L + (int64_t)q * a.C + kbeg + unit * 8;
+      } else {                           // L[k * r + q]: k-rows of 16 NQT values (pieces past r are zeros), 2 NQT lanes per row
+        constexpr int lpr = 2 * NQT;     // lanes (16-byte pieces) per k-row
+        const int krow = i * (64 / lpr) + lane / lpr;
+        const int q0 = (lane % lpr) * 8;
+        lk[jj] = krow;
+        lon[jj] = q0 < r;
+        lsrc[jj] = L + (kbeg + krow) * r + q0;
+      }
+    }
+  }
+  const int per_tile = 4 + my_l;
+#define SR_DMA(kt_)                                                                                       \
+  do {                                                                                                    \
+    char* _sb = smem + ((kt_) % SR_NS) * slot_bytes;                                                      \
+    const int64_t _k0 = kbeg + (int64_t)(kt_) * 64;                                                       \
+    _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                    \
+      const bf16_t* _src = (_k0 + xk[_j]) < kend ? xsrc[_j] + (int64_t)(kt_) * 64 : a.zero_line;          \
+      __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)(_sb + (wave * 4 + _j) * 1024), 16, 0, 0);   \
+    }                                                                                                     \
+    _Pragma("unroll") for (int _jj = 0; _jj < LPW; ++_jj)                                                 \
+      if (wave + 4 * _jj < n_li) {                                                                        \
+        const bf16_t* _src = a.zero_line;                                                                 \
+        if (lon[_jj] && (_k0 + lk[_jj]) < kend)                                                           \
+          _src = lsrc[_jj] + (LFORM == FORM_NT ? (int64_t)(kt_) * 64 : (int64_t)(kt_) * 64 * r);          \
+        __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)(_sb + SR_X_BYTES + (wave + 4 * _jj) * 1024), 16, 0, 0); \
+      }                                                                                                   \
+  } while (0)
+
+  f32x4 acc[2][NQT];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int q = 0; q < NQT; ++q) acc[rt][q] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+  for (int s0 = 0; s0 < SR_NS - 1; ++s0)
+    if (s0 < ntile) SR_DMA(s0);
+  constexpr int l_pitch = 32 * NQT;                    // bytes per k-row of an NN factor tile
+  for (int kt = 0; kt < ntile; ++kt) {
+    // tile kt has landed (everything but the younger tiles' requests), everywhere; nobody reads tile kt - 1 any more
+    const int last_issued = (kt + SR_NS - 2) < (ntile - 1) ? (kt + SR_NS - 2) : (ntile - 1);
+    sr_wait((last_issued - kt) * per_tile);
+    __syncthreads();
+    if (kt + SR_NS - 1 < ntile) SR_DMA(kt + SR_NS - 1);
+    const char* sb = smem + (kt % SR_NS) * slot_bytes;
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) {
+      bf16x8 xa[2];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+        xa[rt] = *(const bf16x8*)(sb + swz_rowk(wave * 32 + rt * 16 + li, k2 * 4 + g));
+#pragma unroll
+      for (int qt = 0; qt < NQT; ++qt)
+        if (qt < nqt) {
+          bf16x8 b;
+          if (LFORM == FORM_NT) {
+            b = *(const bf16x8*)(sb + SR_X_BYTES + swz_rowk(qt * 16 + li, k2 * 4 + g));
+          } else {
+            const char* p = sb + SR_X_BYTES + (k2 * 32 + g * 8 + (li >> 2)) * l_pitch + (qt * 16 + 4 * (li & 3)) * 2;
+            b = lds_read_frag_tr(p, p + 4 * l_pitch);
+          }
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+            acc[rt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[rt], b, acc[rt][qt], 0, 0, 0);
+        }
+    }
+  }
+#undef SR_DMA
+  // D layout: row = 4 * (lane / 16) + v, column = lane % 16
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt)
+      if (qt < nqt)
+        for (int v = 0; v < 4; ++v) {
+          const int mr = row0 + wave * 32 + rt * 16 + 4 * g + v;
+          if (mr < hi) {
+            if (a.ksplit > 1) a.partials[((int64_t)ks * a.T_lora + mr) * a.r_stride + qt * 16 + li] = acc[rt][qt][v];
+            else shrink_store(a, mr, qt * 16 + li, r_pad, e.scale * acc[rt][qt][v]);
+          }
+        }
+}
+
 // Small batches (decode): one block per (adapter, 16 grouped rows); its 8 waves split the
 // contraction, take both operands straight from global memory (L_t stored [r_t, C], so a lane's 8
 // contraction values are one 16-byte load) and add their partial tiles through LDS in wave order,
@@ -267,8 +442,8 @@ __global__ __launch_bounds__(256) void shrink_finalize_kernel(ShrinkArgs a) {
 }
 
 // Splits of the shrink's contraction: enough blocks to fill the chip when the rows alone do not.
-static int shrink_splits(int64_t C, int64_t T_lora, int n_adapters) {
-  const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
+static int shrink_splits(int64_t C, int64_t T_lora, int n_adapters, int rows = SH_ROWS) {
+  const int64_t real_blocks = (T_lora + rows - 1) / rows + n_adapters;
   const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
   int ksplit = 1;
   if (real_blocks < 512) {
@@ -280,21 +455,22 @@ static int shrink_splits(int64_t C, int64_t T_lora, int n_adapters) {
 
 size_t shrink_partial_bytes(int64_t C, int64_t T_lora, int n_adapters, int r_stride) {
   if (T_lora <= 0 || n_adapters <= 0) return 0;
-  const int ks = shrink_splits(C, T_lora, n_adapters);
-  return ks > 1 ? (size_t)ks * T_lora * r_stride * sizeof(float) : 0;
+  const int ks = shrink_splits(C, T_lora, n_adapters, SH_ROWS), kr = shrink_splits(C, T_lora, n_adapters, SR_ROWS);
+  const int k = ks > kr ? ks : kr;
+  return k > 1 ? (size_t)k * T_lora * r_stride * sizeof(float) : 0;
 }
 
 hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, int which, int lora_form, float* u,
                               int r_stride, int64_t T_lora, float* partials, size_t partial_bytes,
-                              bf16_t* u2, bool* wrote_u2, hipStream_t stream) {
+                              bf16_t* u2, bool* wrote_u2, const bf16_t* zero_line, bool ranks_mult8, hipStream_t stream) {
   if (wrote_u2) *wrote_u2 = false;
   if (n_adapters <= 0 || max_seg <= 0 || T_lora <= 0) return hipSuccess;
   ShrinkArgs a;
   a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
   a.which = which; a.u = u; a.r_stride = r_stride;
-  a.partials = nullptr; a.T_lora = T_lora; a.u2 = nullptr;
+  a.partials = nullptr; a.T_lora = T_lora; a.u2 = nullptr; a.zero_line = zero_line;
   const int64_t real_blocks = (T_lora + SH_ROWS - 1) / SH_ROWS + n_adapters;
   if (lora_form == FORM_NT && real_blocks <= 96) {
     a.ksplit = 1; a.kchunk = 0;
@@ -303,9 +479,15 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                        stream, a);
     return hipGetLastError();
   }
-  const int rb_max = (max_seg + SH_ROWS - 1) / SH_ROWS;
+  // both operands by DMA where every piece of a factor row stays inside the row and the segments
+  // are long (measured on MI355X: 10 % faster than the register-staged kernel at 1280 and 16384
+  // rows per adapter, 25 % slower at 264, where a 128-row block is half a segment and its 96 KB of
+  // LDS leave room for one block per compute unit)
+  const bool ring = zero_line != nullptr && (lora_form == FORM_NT || ranks_mult8) && T_lora >= (int64_t)512 * n_adapters;
+  const int rows = ring ? SR_ROWS : SH_ROWS;
+  const int rb_max = (max_seg + rows - 1) / rows;
   const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
-  int ksplit = shrink_splits(C, T_lora, n_adapters);
+  int ksplit = shrink_splits(C, T_lora, n_adapters, rows);
   // (no room for the splits' sums: fewer splits)
   const size_t per_split = (size_t)T_lora * r_stride * sizeof(float);
   if (ksplit > 1 && (partials == nullptr || partial_bytes < (size_t)ksplit * per_split))
@@ -317,17 +499,28 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   a.partials = partials;
   a.u2 = u2;
   if (wrote_u2) *wrote_u2 = u2 != nullptr;
-  const size_t lds = (size_t)r_stride * SH_PITCH;   // r_stride >= every r_pad
+  size_t lds = (size_t)r_stride * SH_PITCH;   // r_stride >= every r_pad
   typedef void (*kern_t)(ShrinkArgs);
   const int nq = r_stride / 16;
   kern_t kern;
-  if (lora_form == FORM_NT)
+  if (ring) {
+    const int nqt_max = nq <= 1 ? 1 : nq <= 2 ? 2 : nq <= 4 ? 4 : 8;
+    lds = (size_t)SR_NS * (SR_X_BYTES + nqt_max * 16 * 128);
+    if (lora_form == FORM_NT)
+      kern = nq <= 1 ? shrink_ring_kernel<FORM_NT, 1> : nq <= 2 ? shrink_ring_kernel<FORM_NT, 2>
+           : nq <= 4 ? shrink_ring_kernel<FORM_NT, 4> : shrink_ring_kernel<FORM_NT, 8>;
+    else
+      kern = nq <= 1 ? shrink_ring_kernel<FORM_NN, 1> : nq <= 2 ? shrink_ring_kernel<FORM_NN, 2>
+           : nq <= 4 ? shrink_ring_kernel<FORM_NN, 4> : shrink_ring_kernel<FORM_NN, 8>;
+    hipError_t e = allow_big_lds((const void*)kern, 16 + (lora_form == FORM_NT ? 0 : 4) + (nq <= 1 ? 0 : nq <= 2 ? 1 : nq <= 4 ? 2 : 3));
+    if (e != hipSuccess) return e;
+  } else if (lora_form == FORM_NT)
     kern = nq <= 1 ? shrink_bf16_kernel<FORM_NT, 1> : nq <= 2 ? shrink_bf16_kernel<FORM_NT, 2>
          : nq <= 4 ? shrink_bf16_kernel<FORM_NT, 4> : shrink_bf16_kernel<FORM_NT, 8>;
   else
     kern = nq <= 1 ? shrink_bf16_kernel<FORM_NN, 1> : nq <= 2 ? shrink_bf16_kernel<FORM_NN, 2>
          : nq <= 4 ? shrink_bf16_kernel<FORM_NN, 4> : shrink_bf16_kernel<FORM_NN, 8>;
-  if (lds > 64 * 1024) {
+  if (!ring && lds > 64 * 1024) {
     hipError_t e = allow_big_lds((const void*)kern, (lora_form == FORM_NT ? 0 : 4) + (nq <= 1 ? 0 : nq <= 2 ? 1 : nq <= 4 ? 2 : 3));
     if (e != hipSuccess) return e;
   }

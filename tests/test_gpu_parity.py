@@ -154,6 +154,32 @@ def test_ragged_shapes_and_ranks(oracle, layout, use_table):
 
 
 @pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("ranks", [(8, 40, 64), (5, 12, 100), (128, 16)])
+def test_long_segments_ragged_contraction(oracle, layout, ranks):
+    """Around a thousand rows per adapter (the shrink then moves both operands by DMA through a ring
+    of k-tiles, for factors stored rank-major with any rank, for factors stored contraction-major
+    with ranks that are multiples of 8; odd ranks there take the register-staged kernel), 520 and
+    328 features (a partial last k-tile in both passes), ragged segment lengths, rows without an
+    adapter, ranks whose padded size is not a power of two."""
+    rng = np.random.default_rng(19 + len(ranks))
+    T = 1100 * len(ranks)
+    ids = rng.integers(-1, len(ranks), size=T).astype(np.int32)
+    w = wl.make_layer(53, T, 520, 328, list(ranks), [2.0, 0.5, 1.0][:len(ranks)], ids, dtype="bf16", layout=layout, want_dY=True)
+    L = HipLayer(w, want_bwd=True)
+    y, u = L.fwd(save_u=True)
+    args = (w["x"], w["W"], w["A"], w["B"], w["ranks"], w["scales"], w["ids"])
+    assert_close(to_host(y), oracle.fwd(*args, layout=layout), "y")
+    check_u_save(oracle, w, L, u, "long segments")
+    dX, dA, dB = L.bwd(u_saved=u)
+    dX_ref, dA_ref, dB_ref = oracle.bwd(*args, w["dY"], layout=layout)
+    dA_ref, dB_ref = oracle_grads_in_layout(dA_ref, dB_ref, layout)
+    assert_close(to_host(dX), dX_ref, "dX")
+    for t in range(len(ranks)):
+        assert_close(to_host(dA[t]), dA_ref[t], "dA[%d]" % t)
+        assert_close(to_host(dB[t]), dB_ref[t], "dB[%d]" % t)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("ranks", [(8, 16, 24, 32), (1, 5, 12, 16, 7), (64, 64)])
 def test_small_batch_paths(oracle, layout, ranks, use_table):
     """Few rows: the GEMM splits the contraction and, when the summed ranks fit its extended
