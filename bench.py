@@ -71,6 +71,8 @@ def parse_args():
                     help="decode configuration without the packed copy of the weight (the kernels then stage W through LDS)")
     ap.add_argument("--stack-layers", type=int, default=8,
                     help="layers of the decode layer-stack measurement of the decode configuration (0: skip)")
+    ap.add_argument("--no-single-task", action="store_true",
+                    help="skip the single-task update measurement of the training configuration")
     ap.add_argument("--layer-stack-only", action="store_true",
                     help="time only the decode layer stack and print its line (for profiles)")
     ap.add_argument("--seed", type=int, default=0)
@@ -370,6 +372,59 @@ def multi_projection_decode(case, args, steps, warmup, torch, api):
     return out
 
 
+def single_task_update(args, steps, warmup, torch, api):
+    """The training engine's step for one task (the paper trains one task per update): forward,
+    then the backward with the AdamW update of the task's adapter attached (marlaas_lora_bwd_adamw),
+    on one adapter's share of the training configuration (16 384 tokens, 14336 -> 4096, rank 32),
+    against forward + plain backward (gradients written to fp32 buffers, no optimizer)."""
+    T, K, N, r = 16384, 14336, 4096, 32
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4242 + args.seed)
+    ctx = api.marlaas_create(0)
+    ids = torch.zeros(T, dtype=torch.int32, device="cuda")
+    segmap = api.marlaas_segmap_build(ctx, ids, 1)
+    x = device_normal((T, K), 1.0, gen, torch)
+    W = device_normal((N, K), K ** -0.5, gen, torch)
+    A = device_normal((r, K), K ** -0.5, gen, torch)
+    B = device_normal((N, r), r ** -0.5, gen, torch)
+    dY = device_normal((T, N), 1.0, gen, torch)
+    gA, gB = torch.empty((r, K), dtype=torch.float32, device="cuda"), torch.empty((N, r), dtype=torch.float32, device="cuda")
+    table = api.marlaas_adapter_table_create(ctx, 1, 1, r)
+    api.marlaas_adapter_table_update(ctx, table, 0, 0, A, B, r, 2.0, gA, gB)
+    Wt = api.marlaas_transpose_weight(ctx, W, 1)
+    desc = api.LoraDesc(x, W, None, None, None, None, segmap, layout=1, out_dtype=torch.bfloat16, table=table, W_t=Wt)
+    ws = torch.empty(max(api.marlaas_workspace_bytes(desc, True), 256), dtype=torch.uint8, device="cuda")
+    api.marlaas_set_workspace(ctx, ws)
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+    u = torch.empty((T, api.marlaas_u_stride(desc)), dtype=torch.float32, device="cuda")
+    f32 = lambda t: t.float().clone()
+    state = [dict(master_A=f32(A), master_B=f32(B), m_A=torch.zeros_like(gA), v_A=torch.zeros_like(gA),
+                  m_B=torch.zeros_like(gB), v_B=torch.zeros_like(gB), A_next=torch.empty_like(A), B_next=torch.empty_like(B))]
+    hp = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, step=1)
+    torch.cuda.synchronize()
+
+    def fused(i):
+        api.marlaas_lora_fwd(ctx, desc, y, u_save=u)
+        api.marlaas_lora_bwd_adamw(ctx, desc, dY, state, dict(hp, step=i + 1), dX=dX, u_saved=u)
+
+    def plain(i):
+        api.marlaas_lora_fwd(ctx, desc, y, u_save=u)
+        api.marlaas_lora_bwd(ctx, desc, dY, dX=dX, dA=api.MARLAAS_GRADS_IN_TABLE, dB=api.MARLAAS_GRADS_IN_TABLE, u_saved=u)
+
+    n = max(3, min(steps, 10))
+    # alternated, best of two each: the engine clock drifts by a few per cent over a run
+    t_plain = t_fused = float("inf")
+    for _ in range(2):
+        t_plain = min(t_plain, time_steps(plain, n, max(1, min(warmup, 2)), "eager", torch, event_stats=False)["ms_per_step"])
+        t_fused = min(t_fused, time_steps(fused, n, max(1, min(warmup, 2)), "eager", torch, event_stats=False)["ms_per_step"])
+    flops = 2 * (2.0 * T * K * N) + 2.0 * T * r * (K + N) * 3
+    return dict(workload="single-task update: T=%d, %d -> %d, 1 adapter r=%d, forward + backward with AdamW attached" % (T, K, N, r),
+                ms_per_update=t_fused, ms_forward_backward_without_optimizer=t_plain,
+                tokens_per_s=T / (t_fused * 1e-3), tflops=flops / (t_fused * 1e-3) / 1e12,
+                params_finite=bool(torch.isfinite(state[0]["master_A"]).all().item() and torch.isfinite(state[0]["master_B"]).all().item()))
+
+
 def layer_stack_decode(args, torch, api, wl):
     """One decode token step through a stack of layers under one HIP graph (harness/layer_stack.py):
     per layer q/k/v in one call, o, gate/up in one call, down; 8B-class shapes (4096, kv 1024, ffn
@@ -517,6 +572,8 @@ def main():
                 extra["multi_projection"] = multi_projection_decode(case, args, steps, warmup, torch, api)
             if cfg == 1 and args.stack_layers > 0:
                 extra["layer_stack"] = layer_stack_decode(args, torch, api, wl)
+            if cfg == 3 and not args.no_single_task:
+                extra["single_task_update"] = single_task_update(args, steps, warmup, torch, api)
             if cfg == 4:
                 # the timed steps reuse a prebuilt segment map; regrouping a batch into an existing map
                 # object (five small kernels, a read-back of the offsets and one wait) costs this much
@@ -596,7 +653,8 @@ def main():
         "tflops": h["tflops"], "roofline": h["roofline"],
     }
     for k in ("cpu_baseline", "event_iterations", "event_median_ms", "event_min_ms", "event_unit", "clocks",
-              "vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection", "layer_stack", "extras_error"):
+              "vendor_base_gemm_only_ms_per_step", "hot_cache_ms_per_step", "multi_projection", "layer_stack", "single_task_update",
+              "segmap_update_ms", "ms_per_step_with_segmap_update", "extras_error"):
         if k in h:
             line[k] = h[k]
     line["others"] = [dict(results[c], workload=names[c]) for c in cfgs if c != head_cfg]

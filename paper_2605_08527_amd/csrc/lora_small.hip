@@ -719,34 +719,53 @@ __global__ __launch_bounds__(RD_THREADS, NQT >= 8 ? 1 : 2) void reduce_bf16_kern
 // batch are not trained by it and are left alone.
 template <int OFORM>
 __global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
+  // block = 32 columns x 32 rank indices of one adapter.  The chunks' sums are read with the rank
+  // index fastest (their storage order) and handed over through LDS, so that the gradient and the
+  // optimizer state are touched in THEIR storage order: rank fastest for [C, r] outputs, column
+  // fastest for [r, C] outputs.
+  __shared__ float tile[32][33];
   const int t = blockIdx.y;
   const AdapterEntry e = a.table[t];
   const int r = e.rank;
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= a.C * r) return;
-  const int64_t c = idx / r;
-  const int q = (int)(idx - c * r);
+  const int qtiles = (a.r_stride + 31) / 32;
+  const int64_t c0 = (int64_t)(blockIdx.x / qtiles) * 32;
+  const int q0 = (int)(blockIdx.x % qtiles) * 32;
+  if (q0 >= r) return;
   const int len = a.seg_off[t + 1] - a.seg_off[t];
+  if (a.opt.on && len == 0) return;
   const int nch = (len + a.tchunk - 1) / a.tchunk;
-  float sum = 0.f;
-  for (int ch = 0; ch < nch; ++ch)
-    sum += a.partials[(((int64_t)t * a.chunks_max + ch) * a.C + c) * a.r_stride + q];
-  const int64_t off = OFORM == FORM_NN ? c * r + q : (int64_t)q * a.C + c;
-  if (a.opt.on) {
-    if (len == 0) return;
-    const OptFactor f = a.opt.f[t];
-    float p = f.master[off];
-    p -= a.opt.lr * a.opt.wd * p;
-    const float m = a.opt.beta1 * f.m[off] + (1.f - a.opt.beta1) * sum;
-    const float v = a.opt.beta2 * f.v[off] + (1.f - a.opt.beta2) * sum * sum;
-    p -= a.opt.lr * (m * a.opt.inv_c1) / (sqrtf(v * a.opt.inv_c2) + a.opt.eps);
-    f.master[off] = p; f.m[off] = m; f.v[off] = v;
-    f.out[off] = float_to_bf16_bits(p);
-    return;
+  for (int i = threadIdx.x; i < 1024; i += 256) {
+    const int cc = i >> 5, qq = i & 31;
+    const int64_t c = c0 + cc;
+    const int q = q0 + qq;
+    float sum = 0.f;
+    if (c < a.C && q < r)
+      for (int ch = 0; ch < nch; ++ch)
+        sum += a.partials[(((int64_t)t * a.chunks_max + ch) * a.C + c) * a.r_stride + q];
+    tile[cc][qq] = sum;
   }
-  float* outp = a.which ? a.grads[t].dB : a.grads[t].dA;
-  float* o = outp + off;
-  *o = a.accumulate ? *o + sum : sum;
+  __syncthreads();
+  for (int i = threadIdx.x; i < 1024; i += 256) {
+    const int cc = OFORM == FORM_NN ? i >> 5 : i & 31, qq = OFORM == FORM_NN ? i & 31 : i >> 5;
+    const int64_t c = c0 + cc;
+    const int q = q0 + qq;
+    if (c >= a.C || q >= r) continue;
+    const float sum = tile[cc][qq];
+    const int64_t off = OFORM == FORM_NN ? c * r + q : (int64_t)q * a.C + c;
+    if (a.opt.on) {
+      const OptFactor f = a.opt.f[t];
+      float p = f.master[off];
+      p -= a.opt.lr * a.opt.wd * p;
+      const float m = a.opt.beta1 * f.m[off] + (1.f - a.opt.beta1) * sum;
+      const float v = a.opt.beta2 * f.v[off] + (1.f - a.opt.beta2) * sum * sum;
+      p -= a.opt.lr * (m * a.opt.inv_c1) / (sqrtf(v * a.opt.inv_c2) + a.opt.eps);
+      f.master[off] = p; f.m[off] = m; f.v[off] = v;
+      f.out[off] = float_to_bf16_bits(p);
+    } else {
+      float* o = (a.which ? a.grads[t].dB : a.grads[t].dA) + off;
+      *o = a.accumulate ? *o + sum : sum;
+    }
+  }
 }
 
 static void reduce_plan(int64_t C, int n_adapters, int max_seg, int* tchunk, int* chunks_max) {
@@ -819,7 +838,7 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   if (e != hipSuccess) return e;
   if (a.to_partials) {
     auto fin = out_form == FORM_NN ? reduce_finalize_kernel<FORM_NN> : reduce_finalize_kernel<FORM_NT>;
-    hipLaunchKernelGGL(fin, dim3((unsigned)((C * r_stride + 255) / 256), n_adapters), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(fin, dim3((unsigned)(((C + 31) / 32) * ((r_stride + 31) / 32)), n_adapters), dim3(256), 0, stream, a);
     e = hipGetLastError();
   }
   return e;
