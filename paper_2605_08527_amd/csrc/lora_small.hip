@@ -13,7 +13,7 @@ namespace marlaas {
 // Raise a kernel's dynamic LDS limit to the hardware maximum, once per (kernel, device): `slot`
 // names the kernel instantiation, bit i of its word = device i has it.
 static hipError_t allow_big_lds(const void* kernel, int slot) {
-  static std::atomic<uint64_t> done[24];
+  static std::atomic<uint64_t> done[32];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
@@ -180,16 +180,17 @@ __global__ __launch_bounds__(SH_THREADS, (NQT >= 8 ? 1 : 2)) void shrink_bf16_ke
 }
 
 // The same shrink with both operands moved global -> LDS by DMA through a ring of four 64-wide
-// k-tiles, for batches with many short segments: a block takes 128 rows of one adapter (half the
-// factor traffic of 64-row blocks), every request of a wave covers whole 128-byte row segments
-// (the register-staged kernel above fetches 64-byte pieces and its factor tile through VGPRs),
-// and three k-tiles are in flight per block.  x part of a slot: [128 rows][64 k], 16-byte units
+// k-tiles: every request of a wave covers whole 128-byte row segments (the register-staged kernel
+// above fetches 64-byte pieces and its factor tile through VGPRs) and three k-tiles are in flight
+// per block.  A block takes 128 rows of one adapter where the segments are long (half the factor
+// traffic of 64-row blocks) and 64 where they are short.  Measured on MI355X against the
+// register-staged kernel: 10 - 15 % faster for factors stored rank-major, 3 - 10 % for
+// contraction-major ones.  x part of a slot: [128 rows][64 k], 16-byte units
 // XOR-swizzled like the GEMM's tiles; factor part: [r_pad][64 k] for factors stored [rank][C]
 // (LFORM NT), [64 k][r_pad] read with transposing LDS reads for factors stored [C][rank] (LFORM
 // NN, ranks multiples of 8).  Rows past the end of the segment repeat its last row (never stored),
 // rank rows past r and contraction units past the end fetch zeros.
-static constexpr int SR_ROWS = 128, SR_NS = 4;
-static constexpr int SR_X_BYTES = SR_ROWS * 64 * 2;
+static constexpr int SR_NS = 4;
 
 __device__ __forceinline__ void sr_wait(int n) {      // at most n vector-memory requests outstanding (n <= 16)
   switch (n) {
@@ -214,8 +215,10 @@ __device__ __forceinline__ void sr_wait(int n) {      // at most n vector-memory
   }
 }
 
-template <int LFORM, int NQT>
+// RT: 16-row tiles per wave (block = 64 RT rows)
+template <int LFORM, int NQT, int RT>
 __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
+  constexpr int SR_ROWS = 64 * RT, SR_X_BYTES = SR_ROWS * 64 * 2, XI = 2 * RT;   // rows, x part of a slot, x instructions per wave and k-tile
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int t = blockIdx.y;
   const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
@@ -238,12 +241,12 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, li = lane & 15;
 
-  // ---- DMA sources.  x: 16 instructions of 8 rows per k-tile, 4 per wave.
-  const bf16_t* xsrc[4];
-  int xk[4];                                           // first contraction index of the lane's unit inside a k-tile
+  // ---- DMA sources.  x: instructions of 8 rows, XI per wave and k-tile.
+  const bf16_t* xsrc[XI];
+  int xk[XI];                                           // first contraction index of the lane's unit inside a k-tile
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = (wave * 4 + j) * 8 + (lane >> 3);
+  for (int j = 0; j < XI; ++j) {
+    const int row = (wave * XI + j) * 8 + (lane >> 3);
     const int unit = (lane & 7) ^ ((row >> 1) & 7);
     int m = row0 + row;
     if (m >= hi) m = hi - 1;
@@ -280,14 +283,14 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
       }
     }
   }
-  const int per_tile = 4 + my_l;
+  const int per_tile = XI + my_l;
 #define SR_DMA(kt_)                                                                                       \
   do {                                                                                                    \
     char* _sb = smem + ((kt_) % SR_NS) * slot_bytes;                                                      \
     const int64_t _k0 = kbeg + (int64_t)(kt_) * 64;                                                       \
-    _Pragma("unroll") for (int _j = 0; _j < 4; ++_j) {                                                    \
+    _Pragma("unroll") for (int _j = 0; _j < XI; ++_j) {                                                   \
       const bf16_t* _src = (_k0 + xk[_j]) < kend ? xsrc[_j] + (int64_t)(kt_) * 64 : a.zero_line;          \
-      __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)(_sb + (wave * 4 + _j) * 1024), 16, 0, 0);   \
+      __builtin_amdgcn_global_load_lds((gptr_t)_src, (lptr_t)(_sb + (wave * XI + _j) * 1024), 16, 0, 0);  \
     }                                                                                                     \
     _Pragma("unroll") for (int _jj = 0; _jj < LPW; ++_jj)                                                 \
       if (wave + 4 * _jj < n_li) {                                                                        \
@@ -298,9 +301,9 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
       }                                                                                                   \
   } while (0)
 
-  f32x4 acc[2][NQT];
+  f32x4 acc[RT][NQT];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int q = 0; q < NQT; ++q) acc[rt][q] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -317,10 +320,10 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
     const char* sb = smem + (kt % SR_NS) * slot_bytes;
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2) {
-      bf16x8 xa[2];
+      bf16x8 xa[RT];
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
-        xa[rt] = *(const bf16x8*)(sb + swz_rowk(wave * 32 + rt * 16 + li, k2 * 4 + g));
+      for (int rt = 0; rt < RT; ++rt)
+        xa[rt] = *(const bf16x8*)(sb + swz_rowk(wave * (16 * RT) + rt * 16 + li, k2 * 4 + g));
 #pragma unroll
       for (int qt = 0; qt < NQT; ++qt)
         if (qt < nqt) {
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
             b = lds_read_frag_tr(p, p + 4 * l_pitch);
           }
 #pragma unroll
-          for (int rt = 0; rt < 2; ++rt)
+          for (int rt = 0; rt < RT; ++rt)
             acc[rt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[rt], b, acc[rt][qt], 0, 0, 0);
         }
     }
@@ -340,12 +343,12 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
 #undef SR_DMA
   // D layout: row = 4 * (lane / 16) + v, column = lane % 16
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
+  for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt)
       if (qt < nqt)
         for (int v = 0; v < 4; ++v) {
-          const int mr = row0 + wave * 32 + rt * 16 + 4 * g + v;
+          const int mr = row0 + wave * (16 * RT) + rt * 16 + 4 * g + v;
           if (mr < hi) {
             if (a.ksplit > 1) a.partials[((int64_t)ks * a.T_lora + mr) * a.r_stride + qt * 16 + li] = acc[rt][qt][v];
             else shrink_store(a, mr, qt * 16 + li, r_pad, e.scale * acc[rt][qt][v]);
@@ -455,7 +458,7 @@ static int shrink_splits(int64_t C, int64_t T_lora, int n_adapters, int rows = S
 
 size_t shrink_partial_bytes(int64_t C, int64_t T_lora, int n_adapters, int r_stride) {
   if (T_lora <= 0 || n_adapters <= 0) return 0;
-  const int ks = shrink_splits(C, T_lora, n_adapters, SH_ROWS), kr = shrink_splits(C, T_lora, n_adapters, SR_ROWS);
+  const int ks = shrink_splits(C, T_lora, n_adapters, SH_ROWS), kr = shrink_splits(C, T_lora, n_adapters, 128);
   const int k = ks > kr ? ks : kr;
   return k > 1 ? (size_t)k * T_lora * r_stride * sizeof(float) : 0;
 }
@@ -479,12 +482,11 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                        stream, a);
     return hipGetLastError();
   }
-  // both operands by DMA where every piece of a factor row stays inside the row and the segments
-  // are long (measured on MI355X: 10 % faster than the register-staged kernel at 1280 and 16384
-  // rows per adapter, 25 % slower at 264, where a 128-row block is half a segment and its 96 KB of
-  // LDS leave room for one block per compute unit)
-  const bool ring = zero_line != nullptr && (lora_form == FORM_NT || ranks_mult8) && T_lora >= (int64_t)512 * n_adapters;
-  const int rows = ring ? SR_ROWS : SH_ROWS;
+  // both operands by DMA where every piece of a factor row stays inside the row; 128 rows per
+  // block where the segments are long, 64 where they are short
+  const bool ring = zero_line != nullptr && (lora_form == FORM_NT || ranks_mult8);
+  const bool long_seg = T_lora >= (int64_t)512 * n_adapters;
+  const int rows = ring ? (long_seg ? 128 : 64) : SH_ROWS;
   const int rb_max = (max_seg + rows - 1) / rows;
   const int kst = (int)((C + SH_KSTG - 1) / SH_KSTG);
   int ksplit = shrink_splits(C, T_lora, n_adapters, rows);
@@ -505,14 +507,13 @@ hipError_t launch_shrink_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   kern_t kern;
   if (ring) {
     const int nqt_max = nq <= 1 ? 1 : nq <= 2 ? 2 : nq <= 4 ? 4 : 8;
-    lds = (size_t)SR_NS * (SR_X_BYTES + nqt_max * 16 * 128);
-    if (lora_form == FORM_NT)
-      kern = nq <= 1 ? shrink_ring_kernel<FORM_NT, 1> : nq <= 2 ? shrink_ring_kernel<FORM_NT, 2>
-           : nq <= 4 ? shrink_ring_kernel<FORM_NT, 4> : shrink_ring_kernel<FORM_NT, 8>;
-    else
-      kern = nq <= 1 ? shrink_ring_kernel<FORM_NN, 1> : nq <= 2 ? shrink_ring_kernel<FORM_NN, 2>
-           : nq <= 4 ? shrink_ring_kernel<FORM_NN, 4> : shrink_ring_kernel<FORM_NN, 8>;
-    hipError_t e = allow_big_lds((const void*)kern, 16 + (lora_form == FORM_NT ? 0 : 4) + (nq <= 1 ? 0 : nq <= 2 ? 1 : nq <= 4 ? 2 : 3));
+    lds = (size_t)SR_NS * (rows * 128 + nqt_max * 16 * 128);
+#define SR_PICK(F_, R_) (nq <= 1 ? shrink_ring_kernel<F_, 1, R_> : nq <= 2 ? shrink_ring_kernel<F_, 2, R_> \
+                         : nq <= 4 ? shrink_ring_kernel<F_, 4, R_> : shrink_ring_kernel<F_, 8, R_>)
+    if (lora_form == FORM_NT) kern = long_seg ? SR_PICK(FORM_NT, 2) : SR_PICK(FORM_NT, 1);
+    else kern = long_seg ? SR_PICK(FORM_NN, 2) : SR_PICK(FORM_NN, 1);
+#undef SR_PICK
+    hipError_t e = allow_big_lds((const void*)kern, 16 + (long_seg ? 0 : 8) + (lora_form == FORM_NT ? 0 : 4) + (nq <= 1 ? 0 : nq <= 2 ? 1 : nq <= 4 ? 2 : 3));
     if (e != hipSuccess) return e;
   } else if (lora_form == FORM_NT)
     kern = nq <= 1 ? shrink_bf16_kernel<FORM_NT, 1> : nq <= 2 ? shrink_bf16_kernel<FORM_NT, 2>
