@@ -26,6 +26,7 @@ its weight from HBM); the large configurations launch eagerly.
 import argparse
 import json
 import os
+import select
 import statistics
 import subprocess
 import sys
@@ -245,32 +246,65 @@ def time_steps(step, steps, warmup, launch, torch, event_stats=True, during=None
     return out
 
 
+# The clock sampler is a helper process started BEFORE this process touches the GPU (a process that
+# has initialised the GPU must not exec another program on these machines); it runs rocm-smi each
+# time it is sent a line and answers with one line of JSON.
+_SAMPLER_CODE = r"""
+import json, subprocess, sys
+for _ in sys.stdin:
+    keep = {}
+    try:
+        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, timeout=30).stdout
+        card = next(iter(json.loads(out.decode()).values()))
+        for k, v in card.items():
+            kl = k.lower()
+            if "sclk" in kl or "mclk" in kl or "fclk" in kl:
+                keep[k] = v
+    except Exception:
+        pass
+    sys.stdout.write(json.dumps(keep) + "\n")
+    sys.stdout.flush()
+"""
+_sampler_proc = None
+
+
+def start_clock_helper():
+    global _sampler_proc
+    try:
+        _sampler_proc = subprocess.Popen([sys.executable, "-c", _SAMPLER_CODE], stdin=subprocess.PIPE, stdout=subprocess.PIPE,
+                                         stderr=subprocess.DEVNULL)
+    except OSError:
+        _sampler_proc = None
+
+
 class ClockSampler:
-    """rocm-smi in a child process while the timed loop runs: the engine and memory clocks under this load."""
+    """rocm-smi (through the helper process) while the timed loop runs: the engine and memory clocks under this load."""
 
     def __init__(self):
-        self.proc = None
+        self.asked = False
         try:
-            self.proc = subprocess.Popen(["rocm-smi", "--showclocks", "--json"], stdout=subprocess.PIPE,
-                                         stderr=subprocess.DEVNULL)
+            if _sampler_proc is not None and _sampler_proc.poll() is None:
+                _sampler_proc.stdin.write(b"go\n")
+                _sampler_proc.stdin.flush()
+                self.asked = True
         except OSError:
             pass
 
     def poll(self):
-        return 0 if self.proc is None else self.proc.poll()
+        """None while the helper has not answered yet (the caller keeps the load running meanwhile)."""
+        if not self.asked:
+            return 0
+        try:
+            ready, _, _ = select.select([_sampler_proc.stdout], [], [], 0)
+            return 0 if ready or _sampler_proc.poll() is not None else None
+        except (OSError, ValueError):
+            return 0
 
     def result(self):
-        if self.proc is None:
+        if not self.asked:
             return None
         try:
-            out, _ = self.proc.communicate(timeout=30)
-            card = next(iter(json.loads(out.decode()).values()))
-            keep = {}
-            for k, v in card.items():
-                kl = k.lower()
-                if "sclk" in kl or "mclk" in kl or "fclk" in kl:
-                    keep[k] = v
-            return keep or None
+            return json.loads(_sampler_proc.stdout.readline().decode()) or None
         except Exception:
             return None
 
@@ -518,6 +552,8 @@ def main():
         print("bench.py: this build runs on exactly one GPU (the layer is data parallel over tokens; "
               "no collective is part of it). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if not args.no_clocks:
+        start_clock_helper()       # before anything here touches the GPU
     import torch
     from paper_2605_08527_amd import api
     from harness import workloads as wl
