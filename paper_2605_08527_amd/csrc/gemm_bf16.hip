@@ -1456,12 +1456,14 @@ static double plan_cost(const GemmPlan& p, int n_ext) {
   return us;
 }
 
-static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout, int n_ext) {
+// small_only: only the 128 x 128 kernels are candidates (the several-projections pass exists for
+// them alone); the unsplit large-batch plan is returned when none of them qualifies.
+static GemmPlan gemm_plan(int64_t T, int64_t Kc, int64_t Nout, int n_ext, bool small_only = false) {
   GemmPlan best = plan_for(0, 1, T, Kc, Nout, n_ext);
   const int64_t G = (int64_t)best.tiles_m * best.tiles_n;
   if (G <= 0 || G > CUS / 2) return best;          // at least half a round of 256 x 256 tiles: no split
-  double best_us = plan_cost(best, n_ext);
-  for (int mode = 1; mode <= 2; ++mode) {
+  double best_us = small_only ? 1e30 : plan_cost(best, n_ext);
+  for (int mode = small_only ? 2 : 1; mode <= 2; ++mode) {
     const int64_t min_k = mode == 2 ? 256 : 128;    // contraction values per split, at least
     int64_t max_s = Kc / min_k;
     if (max_s > 32) max_s = 32;
@@ -1606,7 +1608,7 @@ static int64_t multi_tiles(const ProjEntry* proj, int n_proj) {
 
 size_t gemm_multi_bytes(int64_t T, int64_t Kc, const ProjEntry* proj_host, int n_proj, int n_ext) {
   if (T <= 0 || n_proj <= 0) return 0;
-  const GemmPlan p = gemm_plan(T, Kc, multi_tiles(proj_host, n_proj) * SK_BN, n_ext);
+  const GemmPlan p = gemm_plan(T, Kc, multi_tiles(proj_host, n_proj) * SK_BN, n_ext, true);
   return p.mode == 2 ? p.bytes + p.u_bytes : 0;
 }
 
@@ -1616,7 +1618,7 @@ bool gemm_multi_ok(int form, int64_t T, int64_t Kc, const ProjEntry* proj_host, 
   if (n_ext > 0 && form == FORM_NN && !ranks_mult8) return false;
   const int64_t tiles = multi_tiles(proj_host, n_proj);
   if (tiles * SK_BN > (1 << 24)) return false;
-  const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext);
+  const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext, true);
   if (p.mode != 2 || (n_ext > 0 && p.u_bytes == 0)) return false;
   return partial_bytes >= p.bytes + p.u_bytes;
 }
@@ -1633,7 +1635,7 @@ hipError_t launch_gemm_bf16_multi(const bf16_t* Aop, int64_t lda, int form, int6
                      partials ? partial_bytes : 0) || chunks == nullptr || n_proj > MAX_PROJ)
     return hipErrorInvalidValue;
   const int64_t tiles = multi_tiles(proj_host, n_proj);
-  const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext);
+  const GemmPlan p = gemm_plan(T, Kc, tiles * SK_BN, n_ext, true);
   GemmArgs a;
   a.Aop = Aop; a.lda = lda; a.Bop = (const bf16_t*)proj_host[0].W; a.ldb = proj_host[0].ldw;
   a.T = T; a.Kc = Kc; a.Nout = proj_host[0].Nout;
