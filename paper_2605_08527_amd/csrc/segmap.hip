@@ -74,20 +74,22 @@ __global__ __launch_bounds__(1024) void segmap_scan(int32_t* __restrict__ block_
   }
 }
 
-// Stable scatter: tokens are taken 256 at a time in index order; inside such a
-// group a token's slot is the bucket cursor plus the number of earlier tokens
-// of the group with the same bucket.
+// Stable scatter: tokens are taken 256 at a time in index order.  Inside a wave a token's rank
+// among the earlier tokens of its bucket comes from ballots (one round per distinct bucket in
+// the wave); the four waves of a group then take their slots from the bucket cursors one after
+// the other, in wave order, so the order of equal ids is the order of their indices.
 __global__ __launch_bounds__(SEG_THREADS) void segmap_scatter(const int32_t* __restrict__ ids,
                                                               int64_t T, int n,
                                                               const int32_t* __restrict__ block_base,
                                                               int32_t* __restrict__ perm,
                                                               int32_t* __restrict__ grp_ids) {
-  extern __shared__ int32_t smem[];
-  int32_t* cursor = smem;              // [n + 1]
-  int32_t* grp = smem + (n + 1);       // [SEG_THREADS]
+  extern __shared__ int32_t cursor[];  // [n + 1]
   for (int b = threadIdx.x; b <= n; b += SEG_THREADS)
     cursor[b] = block_base[(int64_t)blockIdx.x * (n + 1) + b];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t below = lane == 0 ? 0ull : (~0ull >> (64 - lane));      // lanes before this one
   int64_t base = (int64_t)blockIdx.x * SEG_CHUNK;
+  __syncthreads();
   for (int g = 0; g < SEG_CHUNK / SEG_THREADS; ++g) {
     int64_t i = base + (int64_t)g * SEG_THREADS + threadIdx.x;
     int b = -1;
@@ -95,18 +97,25 @@ __global__ __launch_bounds__(SEG_THREADS) void segmap_scatter(const int32_t* __r
       int id = ids[i];
       if (id >= -1 && id < n) b = id < 0 ? n : id;
     }
-    __syncthreads();  // cursor updates of the previous group are visible, grp is free
-    grp[threadIdx.x] = b;
-    __syncthreads();
-    int before = 0, after = 0;
-    if (b >= 0) {
-      for (int j = 0; j < (int)threadIdx.x; ++j) before += (grp[j] == b);
-      for (int j = threadIdx.x + 1; j < SEG_THREADS; ++j) after += (grp[j] == b);
-      perm[cursor[b] + before] = (int32_t)i;
-      grp_ids[cursor[b] + before] = b < n ? b : -1;      // adapter of that grouped row
+    // rank inside the wave, and the number of the wave's tokens in the same bucket
+    int rank = 0, cnt = 0;
+    uint64_t todo = __ballot(b >= 0);
+    while (todo) {
+      const int leader = __ffsll((unsigned long long)todo) - 1;
+      const int lb = __shfl(b, leader);
+      const uint64_t same = __ballot(b == lb);
+      if (b == lb) { rank = __popcll(same & below); cnt = __popcll(same); }
+      todo &= ~same;
     }
-    __syncthreads();  // every slot of this group has been read from cursor
-    if (b >= 0 && after == 0) cursor[b] += before + 1;
+    for (int w = 0; w < SEG_THREADS / 64; ++w) {
+      if (wave == w && b >= 0) {
+        const int slot = cursor[b] + rank;
+        perm[slot] = (int32_t)i;
+        grp_ids[slot] = b < n ? b : -1;                  // adapter of that grouped row
+        if (rank == cnt - 1) cursor[b] += cnt;           // (the wave's reads of this cursor are behind it)
+      }
+      __syncthreads();
+    }
   }
 }
 
@@ -158,7 +167,7 @@ hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, in
                      block_hist, nblk, n, seg_off);
   if (nblk > 0) {
     hipLaunchKernelGGL(segmap_scatter, dim3(nblk), dim3(SEG_THREADS),
-                       (n + 1 + SEG_THREADS) * sizeof(int32_t), stream, ids, T, n, block_hist, perm, grp_ids);
+                       (n + 1) * sizeof(int32_t), stream, ids, T, n, block_hist, perm, grp_ids);
   }
   hipLaunchKernelGGL(segmap_chunks, dim3(1), dim3(1024), (n + 2) * sizeof(int32_t), stream, seg_off, n, chunks);
   return hipGetLastError();
