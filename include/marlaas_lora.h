@@ -31,6 +31,14 @@
  *    message retrievable by marlaas_last_error(); HIP failures map to
  *    MARLAAS_EHIP.  No C++ exception crosses this boundary.
  *  - A ctx may be used by one host thread at a time.
+ *  - Two environment variables are read when a ctx is created; both only select between ways of
+ *    computing the same result for small batches with a packed weight (see marlaas_pack_weight):
+ *    MARLAAS_DECODE_FINISH = 0 | 1 | 2 | 3: who adds up the contraction splits and applies the
+ *    expand after the decode kernel: the generic finish kernel, the decode kernel itself, a
+ *    second launch of the decode kernel's own finish, or (default, 3) the second for an unsplit
+ *    contraction and the third otherwise.  MARLAAS_SPIN_LIMIT = n: polls of the one bounded wait
+ *    of the in-kernel finish before a workgroup stops waiting and the work is finished without it
+ *    (0 exercises that path; default 2^20).
  */
 #ifndef MARLAAS_LORA_H
 #define MARLAAS_LORA_H
