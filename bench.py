@@ -638,7 +638,8 @@ def main():
             span_ms = tm.get("event_median_ms", ms) if fused else g["avg_ms"]
             ach = (work["bytes"] if fused else work["gemm"]["bytes"]) / (span_ms * 1e-3) / 1e9
             roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                        traffic=measured_traffic(1, ["gemm_skinny_kernel", "splitk_finish_kernel", "gemm_decode_kernel"]),
+                        traffic=measured_traffic(1, ["gemm_skinny_kernel", "splitk_finish_kernel", "gemm_decode_kernel<true, 0>",
+                                                         "gemm_decode_kernel<true, 1>"]),
                         traffic_source=src,
                         kernel="small-batch GEMM launches of the step" + (" (shrink fused)" if fused else ""),
                         avg_kernel_ms=span_ms,
