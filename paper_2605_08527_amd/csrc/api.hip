@@ -53,6 +53,10 @@ struct marlaas_segmap {
   int max_seg = 0;                  // largest adapter segment
   int64_t T_lora = 0;               // tokens that have an adapter
   RowChunk* chunks_dev = nullptr;   // row chunks of the grouped order (see RowChunk)
+  int32_t* order_dev = nullptr;     // [n_cap] adapters by falling segment length
+  int32_t* chunk_base_dev = nullptr; // [n_cap + 1] first partial-sum slot of the adapters cut into several token chunks
+  int ragged_chunk = 0, ragged_slots = 0;   // the chunk length of that cut, and how many slots it needs in all
+  int ragged_adapters = 0;                  // adapters that are cut (the first ones of order_dev)
   int n_chunks = 0;
 };
 
@@ -251,6 +255,8 @@ extern "C" int marlaas_segmap_create(marlaas_ctx* ctx, int64_t T_max, int32_t n_
     if ((e = hipMalloc((void**)&m->block_hist, sizeof(int32_t) * nb * nn)) != hipSuccess) break;
     if ((e = hipMalloc((void**)&m->flags_dev, 2 * sizeof(int32_t))) != hipSuccess) break;
     if ((e = hipMalloc((void**)&m->chunks_dev, sizeof(RowChunk) * (size_t)segmap_chunk_bound(T_max, n_adapters_max))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->order_dev, sizeof(int32_t) * (size_t)(n_adapters_max > 0 ? n_adapters_max : 1))) != hipSuccess) break;
+    if ((e = hipMalloc((void**)&m->chunk_base_dev, sizeof(int32_t) * ((size_t)n_adapters_max + 1))) != hipSuccess) break;
     e = hipHostMalloc((void**)&m->readback, sizeof(int32_t) * (nn + 2), hipHostMallocDefault);
   } while (0);
   if (e != hipSuccess) {
@@ -278,7 +284,7 @@ extern "C" int marlaas_segmap_update(marlaas_ctx* ctx, marlaas_segmap* m, const 
   m->built = false;
   const size_t nn = (size_t)n_adapters + 2;
   HIP_TRY(ctx, launch_segmap(token_adapter, T, n_adapters, m->perm_dev, m->grp_dev, m->seg_off_dev, m->block_hist, m->flags_dev,
-                             m->chunks_dev, st));
+                             m->chunks_dev, m->order_dev, m->chunk_base_dev, st));
   HIP_TRY(ctx, hipMemcpyAsync(m->readback, m->seg_off_dev, sizeof(int32_t) * nn, hipMemcpyDeviceToHost, st));
   HIP_TRY(ctx, hipMemcpyAsync(m->readback + nn, m->flags_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(ctx, hipStreamSynchronize(st));
@@ -292,6 +298,12 @@ extern "C" int marlaas_segmap_update(marlaas_ctx* ctx, marlaas_segmap* m, const 
     if (len > m->max_seg) m->max_seg = len;
   }
   m->T_lora = m->seg_off[n_adapters];
+  m->ragged_chunk = reduce_ragged_chunk(m->T_lora, n_adapters);
+  m->ragged_slots = 0; m->ragged_adapters = 0;
+  for (int t = 0; t < n_adapters; ++t) {
+    const int nch = (m->seg_off[t + 1] - m->seg_off[t] + m->ragged_chunk - 1) / m->ragged_chunk;
+    if (nch > 1) { m->ragged_slots += nch; ++m->ragged_adapters; }
+  }
   m->n_chunks = (int)segmap_chunk_count(m->seg_off.data(), n_adapters);
   m->built = true;
   return MARLAAS_OK;
@@ -321,6 +333,8 @@ extern "C" void marlaas_segmap_destroy(marlaas_segmap* map) {
   (void)hipFree(map->block_hist);
   (void)hipFree(map->flags_dev);
   (void)hipFree(map->chunks_dev);
+  (void)hipFree(map->order_dev);
+  (void)hipFree(map->chunk_base_dev);
   if (map->readback) (void)hipHostFree(map->readback);
   delete map;
 }
@@ -529,8 +543,8 @@ static WsPlan plan_workspace(const marlaas_lora_desc* d, int want_bwd) {
       // (few adapters: room for the reductions' sums even where one chunk covers a segment, so
       // that a backward with the optimizer step attached can always run)
       const bool always = d->n_adapters <= OPT_MAX_ADAPTERS;
-      const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs, always);
-      const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs, always);
+      const size_t pa = reduce_partial_bytes(d->d_in, d->n_adapters, d->map->max_seg, (int)rs, always, d->map->ragged_chunk, d->map->ragged_slots);
+      const size_t pb = reduce_partial_bytes(d->d_out, d->n_adapters, d->map->max_seg, (int)rs, always, d->map->ragged_chunk, d->map->ragged_slots);
       const size_t pg = gemm_splitk_bytes(d->T, d->d_out, d->d_in, n_ext);
       if (pa > part) part = pa;
       if (pb > part) part = pb;
@@ -1058,9 +1072,11 @@ static int bwd_impl(marlaas_ctx* ctx, const marlaas_lora_desc* d, const void* dY
                                     p.wt_bytes, d->layout == MARLAAS_LAYOUT_TORCH ? (const bf16_t*)d->W_t : nullptr, &dma, (const bf16_t*)d->W_packed_bwd, &dsync, st));
     if (want_grads && d->n_adapters > 0) {
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(dy, lddy, d->d_out, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[1] : nullptr, st));
+                                      table, grads, 1, db_form, u, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[1] : nullptr, map->order_dev, map->chunk_base_dev,
+                                      map->ragged_chunk, map->ragged_slots, map->ragged_adapters, st));
       PROFILED(ctx, MARLAAS_KERNEL_REDUCE, st, launch_reduce_bf16(x, d->ldx, d->d_in, perm, map->seg_off_dev, d->n_adapters, map->max_seg,
-                                      table, grads, 0, da_form, v, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[0] : nullptr, st));
+                                      table, grads, 0, da_form, v, rs, accumulate, part, part ? p.part_bytes : 0, opt ? &opt[0] : nullptr, map->order_dev, map->chunk_base_dev,
+                                      map->ragged_chunk, map->ragged_slots, map->ragged_adapters, st));
     }
   } else {
     if (opt) return fail(ctx, MARLAAS_EUNSUPPORTED, "the optimizer step is attached to the bf16 backward only");

@@ -117,7 +117,17 @@ struct SegmapDev {
 
 // perm[m] = token of grouped row m, grp_ids[m] = its adapter (-1: none)
 hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* grp_ids, int32_t* seg_off,
-                         int32_t* block_hist, int32_t* flags, RowChunk* chunks, hipStream_t stream);
+                         int32_t* block_hist, int32_t* flags, RowChunk* chunks, int32_t* order, int32_t* chunk_base,
+                         hipStream_t stream);
+// Token chunk of the weight-gradient reductions for batches whose segments are very unequal: a
+// segment longer than this is cut into pieces of this many rows (twice the mean segment, at least
+// 512, a multiple of 64), each piece a block of its own; chunk_base[t] (segment map) is the first
+// partial-sum slot of adapter t's pieces, counting only adapters with more than one piece.
+__host__ __device__ inline int reduce_ragged_chunk(int64_t T_lora, int n) {
+  int64_t c = n > 0 ? 2 * T_lora / n : 0;
+  if (c < 512) c = 512;
+  return (int)((c + 63) / 64 * 64);
+}
 int segmap_blocks(int64_t T);
 // Row chunks of a grouped order with these segment offsets (n + 2 entries): how many there are.
 int64_t segmap_chunk_count(const int32_t* seg_off, int n);
@@ -240,8 +250,11 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, const GradEntry* grads, int which,
                               int out_form, const float* V, int r_stride, int accumulate,
-                              float* partials, size_t partial_bytes, const ReduceOpt* opt, hipStream_t stream);
-size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int max_rank, bool always = false);
+                              float* partials, size_t partial_bytes, const ReduceOpt* opt, const int32_t* order,
+                              const int32_t* chunk_base, int ragged_chunk, int ragged_slots, int ragged_adapters,
+                              hipStream_t stream);
+size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int max_rank, bool always = false,
+                            int ragged_chunk = 0, int ragged_slots = 0);
 
 // fp32 path (plain ALU arithmetic, any shape)
 hipError_t launch_shrink_f32(const float* X, int64_t ldx, int64_t C, const int32_t* perm,

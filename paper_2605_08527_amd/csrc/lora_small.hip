@@ -544,6 +544,10 @@ struct ReduceArgs {
   const float* V; int r_stride;
   int accumulate;
   int slabs; int tchunk; int chunks_max;   // tchunk multiple of RD_TOK
+  const int32_t* order;                    // blockIdx.y -> adapter (longest segment first), or null
+  // ragged = 1: only segments longer than tchunk are cut; adapter t's pieces use partial-sum slots
+  // chunk_base[t] .. ([slot][C][r_stride]), every other adapter's block writes its result itself
+  int ragged; const int32_t* chunk_base;
   float* partials;                         // [adapter][chunk][C][r_stride] when to_partials
   int to_partials;                         // 1: the chunks' sums go to `partials`, reduce_finalize_kernel completes
   ReduceOpt opt;                           // (finalize) optimizer step on every completed gradient element
@@ -564,12 +568,13 @@ __global__ __launch_bounds__(RD_THREADS, NQT >= 8 ? 1 : 2) void reduce_bf16_kern
   extern __shared__ __attribute__((aligned(16))) char rsm[];
   char* Xs = rsm;                               // [RD_TOK][RD_COLS] bf16, swizzled
   char* Vh = rsm + RD_TOK * RD_COLS * 2;        // [RD_TOK][r_pad] bf16: leading halves of V
-  const int t = blockIdx.y;
+  const int t = a.order ? a.order[blockIdx.y] : blockIdx.y;
   const int slab = blockIdx.x % a.slabs, ch = blockIdx.x / a.slabs;
   const int lo = a.seg_off[t], hi = a.seg_off[t + 1];
   const int beg = lo + ch * a.tchunk;
   const bool empty = beg >= hi;
-  if (empty && !(ch == 0 && a.chunks_max == 1 && !a.accumulate)) return;  // empty adapter: write zeros
+  const int nch_t = (hi - lo + a.tchunk - 1) / a.tchunk;                    // token chunks of this adapter
+  if (empty && !(ch == 0 && (a.chunks_max == 1 || a.ragged) && !a.accumulate)) return;  // empty adapter: write zeros
   const int end = (beg + a.tchunk) < hi ? (beg + a.tchunk) : hi;
   const AdapterEntry e = a.table[t];
   const int r = e.rank, r_pad = (r + 15) & ~15, nqt = r_pad >> 4;
@@ -690,9 +695,10 @@ __global__ __launch_bounds__(RD_THREADS, NQT >= 8 ? 1 : 2) void reduce_bf16_kern
     }
   }
   // D layout: row (column c of X) = 4 * (lane / 16) + v, column (q) = lane % 16
-  float* outp = a.to_partials ? nullptr : (a.which ? a.grads[t].dB : a.grads[t].dA);
-  float* part = a.to_partials
-      ? a.partials + ((int64_t)t * a.chunks_max + ch) * a.C * a.r_stride : nullptr;
+  const bool via_part = a.ragged ? nch_t > 1 : a.to_partials != 0;
+  float* outp = via_part ? nullptr : (a.which ? a.grads[t].dB : a.grads[t].dA);
+  float* part = !via_part ? nullptr
+                : a.partials + (a.ragged ? (int64_t)a.chunk_base[t] + ch : (int64_t)t * a.chunks_max + ch) * a.C * a.r_stride;
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -725,7 +731,8 @@ __global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
   // optimizer state are touched in THEIR storage order: rank fastest for [C, r] outputs, column
   // fastest for [r, C] outputs.
   __shared__ float tile[32][33];
-  const int t = blockIdx.y;
+  // (ragged: the grid covers the adapters that are cut, the longest ones, first in `order`)
+  const int t = a.ragged ? a.order[blockIdx.y] : blockIdx.y;
   const AdapterEntry e = a.table[t];
   const int r = e.rank;
   const int qtiles = (a.r_stride + 31) / 32;
@@ -735,6 +742,8 @@ __global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
   const int len = a.seg_off[t + 1] - a.seg_off[t];
   if (a.opt.on && len == 0) return;
   const int nch = (len + a.tchunk - 1) / a.tchunk;
+  if (a.ragged && nch <= 1) return;      // (written by its one block)
+  const int64_t slot0 = a.ragged ? (int64_t)a.chunk_base[t] : (int64_t)t * a.chunks_max;
   for (int i = threadIdx.x; i < 1024; i += 256) {
     const int cc = i >> 5, qq = i & 31;
     const int64_t c = c0 + cc;
@@ -742,7 +751,7 @@ __global__ __launch_bounds__(256) void reduce_finalize_kernel(ReduceArgs a) {
     float sum = 0.f;
     if (c < a.C && q < r)
       for (int ch = 0; ch < nch; ++ch)
-        sum += a.partials[(((int64_t)t * a.chunks_max + ch) * a.C + c) * a.r_stride + q];
+        sum += a.partials[((slot0 + ch) * a.C + c) * a.r_stride + q];
     tile[cc][qq] = sum;
   }
   __syncthreads();
@@ -785,20 +794,35 @@ static void reduce_plan(int64_t C, int n_adapters, int max_seg, int* tchunk, int
   }
 }
 
-size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int r_stride, bool always) {
+// Very unequal segments with enough blocks in all: cut only the long ones (see reduce_ragged_chunk).
+static bool reduce_ragged(int64_t C, int n_adapters, int max_seg, int ragged_chunk, int ragged_slots) {
+  const int slabs = (int)((C + RD_COLS - 1) / RD_COLS);
+  return (int64_t)slabs * n_adapters >= 256 && ragged_slots > 0 && ragged_chunk > 0 && max_seg > 2 * ragged_chunk;
+}
+
+size_t reduce_partial_bytes(int64_t C, int n_adapters, int max_seg, int r_stride, bool always, int ragged_chunk,
+                            int ragged_slots) {
   int tc, cm;
   reduce_plan(C, n_adapters, max_seg, &tc, &cm);
-  if (cm <= 1 && !always) return 0;
-  return (size_t)n_adapters * cm * C * r_stride * sizeof(float);
+  size_t need = (cm <= 1 && !always) ? 0 : (size_t)n_adapters * cm * C * r_stride * sizeof(float);
+  if (reduce_ragged(C, n_adapters, max_seg, ragged_chunk, ragged_slots)) {
+    const size_t rg = (size_t)ragged_slots * C * r_stride * sizeof(float);
+    if (rg > need) need = rg;
+  }
+  return need;
 }
 
 hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int32_t* perm,
                               const int32_t* seg_off, int n_adapters, int max_seg,
                               const AdapterEntry* table, const GradEntry* grads, int which,
                               int out_form, const float* V, int r_stride, int accumulate,
-                              float* partials, size_t partial_bytes, const ReduceOpt* opt, hipStream_t stream) {
+                              float* partials, size_t partial_bytes, const ReduceOpt* opt, const int32_t* order,
+                              const int32_t* chunk_base, int ragged_chunk, int ragged_slots, int ragged_adapters,
+                              hipStream_t stream) {
   if (n_adapters <= 0) return hipSuccess;
   ReduceArgs a;
+  a.order = order;
+  a.ragged = 0; a.chunk_base = nullptr;
   a.X = X; a.ldx = ldx; a.C = C; a.perm = perm; a.seg_off = seg_off; a.table = table;
   a.grads = grads; a.which = which; a.V = V; a.r_stride = r_stride; a.accumulate = accumulate;
   a.slabs = (int)((C + RD_COLS - 1) / RD_COLS);
@@ -811,6 +835,15 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   }
   a.partials = partials;
   a.to_partials = a.chunks_max > 1;
+  if (!(opt && opt->on) && a.chunks_max == 1 && chunk_base != nullptr && order != nullptr && partials != nullptr &&
+      ragged_adapters > 0 && ragged_adapters <= n_adapters &&
+      reduce_ragged(C, n_adapters, max_seg, ragged_chunk, ragged_slots) &&
+      partial_bytes >= (size_t)ragged_slots * C * r_stride * sizeof(float)) {
+    a.ragged = 1; a.chunk_base = chunk_base;
+    a.tchunk = ragged_chunk;
+    a.chunks_max = (max_seg + ragged_chunk - 1) / ragged_chunk;
+    a.to_partials = 1;               // (the finalize kernel runs; it skips the adapters with one piece)
+  }
   a.opt.on = 0;
   if (opt && opt->on) {
     // the optimizer step lives in the finalize kernel: the sums always go through `partials`
@@ -839,7 +872,8 @@ hipError_t launch_reduce_bf16(const bf16_t* X, int64_t ldx, int64_t C, const int
   if (e != hipSuccess) return e;
   if (a.to_partials) {
     auto fin = out_form == FORM_NN ? reduce_finalize_kernel<FORM_NN> : reduce_finalize_kernel<FORM_NT>;
-    hipLaunchKernelGGL(fin, dim3((unsigned)(((C + 31) / 32) * ((r_stride + 31) / 32)), n_adapters), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(fin, dim3((unsigned)(((C + 31) / 32) * ((r_stride + 31) / 32)), a.ragged ? ragged_adapters : n_adapters),
+                       dim3(256), 0, stream, a);
     e = hipGetLastError();
   }
   return e;

@@ -144,6 +144,34 @@ __global__ __launch_bounds__(1024) void segmap_chunks(const int32_t* __restrict_
   }
 }
 
+// Adapters by falling segment length (ties: by index): order[k] = the adapter with the k-th longest
+// segment.  Kernels whose blocks own whole segments take their adapter from it, so that the long
+// segments start first and the short ones fill the end of the launch.  One block; every thread
+// ranks its adapters by counting the ones that come before them (n <= 4096).
+__global__ __launch_bounds__(1024) void segmap_order(const int32_t* __restrict__ seg_off, int n, int32_t* __restrict__ order,
+                                                     int32_t* __restrict__ chunk_base) {
+  extern __shared__ int32_t len[];     // [n]
+  for (int t = threadIdx.x; t < n; t += blockDim.x) len[t] = seg_off[t + 1] - seg_off[t];
+  __syncthreads();
+  if (threadIdx.x == 0 && chunk_base != nullptr) {
+    // first partial-sum slot of every adapter whose segment is cut into several token chunks
+    const int tc = reduce_ragged_chunk(seg_off[n], n);
+    int run = 0;
+    for (int t = 0; t < n; ++t) {
+      chunk_base[t] = run;
+      const int nch = (len[t] + tc - 1) / tc;
+      if (nch > 1) run += nch;
+    }
+    chunk_base[n] = run;
+  }
+  for (int t = threadIdx.x; t < n; t += blockDim.x) {
+    const int mine = len[t];
+    int before = 0;
+    for (int s = 0; s < n; ++s) before += (len[s] > mine) || (len[s] == mine && s < t);
+    order[before] = t;
+  }
+}
+
 int64_t segmap_chunk_count(const int32_t* seg_off, int n) {
   int64_t c = 0;
   for (int b = 0; b <= n; ++b) c += (seg_off[b + 1] - seg_off[b] + ROW_CHUNK - 1) / ROW_CHUNK;
@@ -156,7 +184,8 @@ int64_t segmap_chunk_bound(int64_t T, int n) { return T / ROW_CHUNK + n + 2; }
 __global__ void segmap_clear_flags(int32_t* flags) { flags[threadIdx.x] = 0; }
 
 hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, int32_t* grp_ids, int32_t* seg_off,
-                         int32_t* block_hist, int32_t* flags, RowChunk* chunks, hipStream_t stream) {
+                         int32_t* block_hist, int32_t* flags, RowChunk* chunks, int32_t* order, int32_t* chunk_base,
+                         hipStream_t stream) {
   int nblk = segmap_blocks(T);
   hipLaunchKernelGGL(segmap_clear_flags, dim3(1), dim3(2), 0, stream, flags);
   if (nblk > 0) {
@@ -170,6 +199,8 @@ hipError_t launch_segmap(const int32_t* ids, int64_t T, int n, int32_t* perm, in
                        (n + 1) * sizeof(int32_t), stream, ids, T, n, block_hist, perm, grp_ids);
   }
   hipLaunchKernelGGL(segmap_chunks, dim3(1), dim3(1024), (n + 2) * sizeof(int32_t), stream, seg_off, n, chunks);
+  if (n > 0 && order != nullptr)
+    hipLaunchKernelGGL(segmap_order, dim3(1), dim3(1024), n * sizeof(int32_t), stream, seg_off, n, order, chunk_base);
   return hipGetLastError();
 }
 
