@@ -256,7 +256,11 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
   }
   // factor: n_li instructions per k-tile, instruction i = wave + 4 jj
   constexpr int LPW = (2 * NQT + 3) / 4;
-  const int n_li = LFORM == FORM_NT ? 2 * nqt : 2 * NQT;
+  // (contraction-major factors: a k-row of the tile holds 16 lq ranks, lq = the adapter's own count
+  // of 16-rank blocks when that is a power of two (a whole number of k-rows per instruction), else
+  // the template's; low-rank adapters then move a fraction of the tile)
+  const int lq = (nqt & (nqt - 1)) == 0 ? nqt : NQT;
+  const int n_li = LFORM == FORM_NT ? 2 * nqt : 2 * lq;
   const bf16_t* lsrc[LPW];
   int lk[LPW];                                         // contraction index (inside the k-tile) the lane's piece starts at
   bool lon[LPW];                                       // the piece exists (rank row / ranks inside r)
@@ -274,7 +278,7 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
         lon[jj] = q < r;
         lsrc[jj] = L + (int64_t)q * a.C + kbeg + unit * 8;
       } else {                           // L[k * r + q]: k-rows of 16 NQT values (pieces past r are zeros), 2 NQT lanes per row
-        constexpr int lpr = 2 * NQT;     // lanes (16-byte pieces) per k-row
+        const int lpr = 2 * lq;          // lanes (16-byte pieces) per k-row
         const int krow = i * (64 / lpr) + lane / lpr;
         const int q0 = (lane % lpr) * 8;
         lk[jj] = krow;
@@ -310,7 +314,7 @@ __global__ __launch_bounds__(256) void shrink_ring_kernel(ShrinkArgs a) {
 #pragma unroll
   for (int s0 = 0; s0 < SR_NS - 1; ++s0)
     if (s0 < ntile) SR_DMA(s0);
-  constexpr int l_pitch = 32 * NQT;                    // bytes per k-row of an NN factor tile
+  const int l_pitch = 32 * lq;                         // bytes per k-row of an NN factor tile
   for (int kt = 0; kt < ntile; ++kt) {
     // tile kt has landed (everything but the younger tiles' requests), everywhere; nobody reads tile kt - 1 any more
     const int last_issued = (kt + SR_NS - 2) < (ntile - 1) ? (kt + SR_NS - 2) : (ntile - 1);
