@@ -114,7 +114,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
 
   // ---- block -> tile: each XCD (blocks b = x mod 8) walks a compact run of
   // tiles; inside a run, groups of 8 row tiles share their column tiles.
-  int tm, tn, ks_idx, tile_lin;
+  int tm, tn, ks_idx;
   {
     const int G = a.tiles_m * a.tiles_n * a.ksplit;
     const int b = blockIdx.x;
@@ -124,7 +124,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs a) {
     const int bbs = start + idx;
     const int bb = bbs / a.ksplit;          // the splits of one tile stay on one XCD (one L2)
     ks_idx = bbs - bb * a.ksplit;
-    tile_lin = bb;
     const int GM = 8;
     const int per_group = GM * a.tiles_n;
     const int gid = bb / per_group;
